@@ -1,0 +1,169 @@
+/* libmqgrad -- the data-parallel hot path of MQGrad (arXiv 1804.08066) for AMD MI355X (gfx950).
+ *
+ * The paper trains on a parameter server.  Every iteration each worker quantizes its gradient to
+ * K bits and pushes it; the server de-quantizes all workers' gradients, averages them and updates
+ * the parameters (Section 3.2; Algorithm 1, WorkerIterate and ReceiveQGThenSendQG).  K is chosen
+ * by a small MDP agent on the server from the recent loss values (Section 3.3; Algorithm 2).
+ *
+ * This library is that path for one GPU:
+ *   mqg_quantize          worker side: per-bucket range, stochastic rounding to the 2^K-level
+ *                         grid, dense bit packing            (the paper's Quantize(g, K))
+ *   mqg_aggregate_update  server side: unpack, de-quantize, mean over W workers, SGD update
+ *                         (the paper's De-quantize + average + w <- w - eta g)
+ *   mqg_mdp_*             the host-side agent that picks K  (the paper's MQGrad-SARSA)
+ *
+ * Conventions
+ *   - Plain C ABI.  No function throws, aborts or allocates device memory.
+ *   - "device pointer" = memory the current HIP device can read/write.  The library neither
+ *     retains nor frees any pointer it is given.
+ *   - GPU calls are asynchronous: they enqueue work on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and return.  A returned MQG_OK means "enqueued".
+ *   - Every error is reported through the return code; nothing is enqueued when it is not MQG_OK.
+ *
+ * The quantizer (the paper gives only "range-linear encode/decode to K bits"; the rest is this
+ * library's reading of it):
+ *   bucket k covers elements [k*bucket, min((k+1)*bucket, n));  s_k = max |g_i| over the bucket
+ *   (stored as 0 when below 2^-96);  L = 2^bits - 1;  the 2^bits levels are s_k*(2c - L)/L for
+ *   code c = 0..L (top bit of c = sign, low bits = magnitude level).  Element i is placed at
+ *   u = clamp(fma(g_i, (L/2)/s_k, L/2), 0, L) and rounded down or up at random so that the
+ *   expectation is u: c = floor(u) + [r < u - floor(u)], r = (h + 1/2) / 65536, where h is the
+ *   16-bit uniform that Philox4x32-10 (Salmon et al., SC'11) yields for key = seed and counter =
+ *   (group lo, group hi, iteration, worker), group = (elem_base + i) >> 3, 16-bit slot
+ *   (elem_base + i) & 7 of the 128-bit output.  Code i occupies bits [i*bits, (i+1)*bits) of a
+ *   little-endian stream of 32-bit words; unused bits of the last word are 0.
+ */
+#ifndef MQGRAD_H
+#define MQGRAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MQG_OK = 0,
+    MQG_EINVAL = -1,  /* an argument is out of its documented range, or a required pointer is NULL */
+    MQG_EALIGN = -2,  /* a pointer is not 4-byte aligned */
+    MQG_ELAUNCH = -3  /* the HIP runtime refused the launch (hipGetLastError was consumed) */
+} mqg_status;
+
+typedef enum {
+    MQG_SCALE_MAXABS = 0, /* s_k = max |g_i|  (order independent, bit exact) */
+    MQG_SCALE_L2 = 1      /* s_k = ||bucket||_2 (>= max |g_i|), same grid */
+} mqg_scale_mode;
+
+#define MQG_MAX_WORKERS 64u
+#define MQG_MIN_BUCKET 32u
+#define MQG_MAX_BUCKET 16384u
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* mqg_status_string(mqg_status st);
+
+/* Number of buckets, ceil(n / bucket), and of 32-bit words in the packed stream,
+ * ceil(n * bits / 32).  Pure host arithmetic; bucket and bits must be non-zero. */
+size_t mqg_num_buckets(uint64_t n, uint32_t bucket);
+size_t mqg_packed_words(uint64_t n, uint32_t bits);
+
+/* Worker side: Quantize(g, K) of Algorithm 1 (WorkerIterate), Section 3.2 footnote.
+ *
+ *   grad        device, n floats, read only.  Values must be finite (non-finite values never
+ *               fault but give unspecified codes for their bucket).
+ *   n           element count; 0 is a no-op.
+ *   bits        K, 1..8.
+ *   bucket      elements per scale; a multiple of 32 in [32, 16384].  bucket >= n gives the
+ *               paper's one-range-per-tensor quantizer.
+ *   seed, iteration, worker, elem_base
+ *               select the random stream (see top of file).  elem_base must be a multiple of 8;
+ *               it offsets the element index so that several tensors of one model draw from
+ *               disjoint parts of one stream.
+ *   packed_out  device, mqg_packed_words(n, bits) words, fully overwritten.
+ *   scales_out  device, mqg_num_buckets(n, bucket) floats, fully overwritten.
+ *   stream      hipStream_t.
+ * Pointers need 4-byte alignment; 16-byte aligned `grad` takes the fast path.
+ * Errors: MQG_EINVAL (bits, bucket, elem_base out of range; NULL pointer with n > 0),
+ *         MQG_EALIGN, MQG_ELAUNCH. */
+mqg_status mqg_quantize(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                        uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                        uint32_t* packed_out, float* scales_out, void* stream);
+
+/* Same, with the bucket range taken as the L2 norm of the bucket when mode == MQG_SCALE_L2
+ * (the norm scaling of the QSGD family the paper cites in Section 2).  mode == MQG_SCALE_MAXABS
+ * is exactly mqg_quantize.  The L2 scale is accumulated in fp32 in a fixed tree order, so it is
+ * reproducible but only close (about 1e-6 relative) to a scale summed in another order. */
+mqg_status mqg_quantize_mode(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                             mqg_scale_mode mode,
+                             uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                             uint32_t* packed_out, float* scales_out, void* stream);
+
+/* Same as mqg_quantize, but the bucket scales are READ from scales_in (device,
+ * mqg_num_buckets(n, bucket) floats) instead of being computed; they are copied to scales_out
+ * (scales_out may equal scales_in).  Elements larger than their scale clamp to the end levels.
+ * Lets a caller fix the range across workers, or inject scales computed elsewhere. */
+mqg_status mqg_quantize_with_scales(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                                    uint64_t seed, uint32_t iteration, uint32_t worker,
+                                    uint64_t elem_base, const float* scales_in,
+                                    uint32_t* packed_out, float* scales_out, void* stream);
+
+/* Server side: De-quantize each worker's gradient, average over the W workers, update the
+ * parameters (Algorithm 1, ReceiveQGThenSendQG: mean over P workers; WorkerIterate: w <- w - eta g).
+ *
+ *   params[i] <- fma(-(lr / W), sum_{w=0}^{W-1} (2 c_{w,i} - L) * (s_{w,k} / L), params[i])
+ *
+ * with the sum taken in worker order, one fused multiply-add per worker, all in fp32.
+ *
+ *   packed, scales  HOST arrays of W device pointers (read during the call only): worker w's
+ *                   packed stream and bucket scales as written by mqg_quantize with the same
+ *                   n, bits and bucket (the paper broadcasts one K to all workers).
+ *   W               1..MQG_MAX_WORKERS.
+ *   lr              learning rate eta.
+ *   params          device, n floats, updated in place.
+ * Errors as for mqg_quantize; additionally MQG_EINVAL for W out of range or a NULL entry. */
+mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                uint64_t n, uint32_t bits, uint32_t bucket,
+                                float lr, float* params, void* stream);
+
+/* ---- host-side agent that chooses K (Section 3.3, Algorithm 2).  No GPU involved. ---------- */
+
+typedef struct mqg_mdp mqg_mdp;
+
+typedef struct {
+    uint64_t seed;          /* seeds the Q-network initialisation and the epsilon-greedy draws */
+    uint32_t bits_min;      /* paper: 2 */
+    uint32_t bits_max;      /* paper: 8 */
+    uint32_t window;        /* T, losses per MDP state; paper: 5 */
+    uint32_t decide_every;  /* training iterations between decisions; paper: T = 5 */
+    uint32_t hidden;        /* hidden units of the Q network; paper: 10 */
+    double alpha;           /* moving-average weight of Eq. (1); paper: 0.01 */
+    double epsilon;         /* exploration rate; paper: 0.1 */
+    double eta;             /* SARSA step size; paper: 0.1 */
+    double reward_scale;    /* gamma of the reward equation; paper: 300 */
+    double discount;        /* gamma of the SARSA update; the paper gives no value */
+} mqg_mdp_config;
+
+/* Fill cfg with the paper's values (Section 4.1) and discount = 0.9. */
+void mqg_mdp_default_config(mqg_mdp_config* cfg);
+
+/* Create / destroy an agent.  Returns NULL for an invalid configuration
+ * (bits_min < 1, bits_max > 8, bits_min > bits_max, window < 2, decide_every < 1, hidden < 1). */
+mqg_mdp* mqg_mdp_create(const mqg_mdp_config* cfg);
+void mqg_mdp_destroy(mqg_mdp* agent);
+
+/* Feed the global loss of training iteration m = 0, 1, 2, ... and the wall time (ms) that the
+ * previous iteration took; returns the number of bits to use for iteration m.  The bit width
+ * changes only when m is a multiple of decide_every and never decreases.  Returns 0 if agent
+ * is NULL. */
+uint32_t mqg_mdp_step(mqg_mdp* agent, double loss, double elapsed_ms);
+
+/* Introspection for tests: current n_t, the smoothed-loss window (writes `window` doubles,
+ * oldest first), the last reward, and the number of decisions taken so far. */
+uint32_t mqg_mdp_current_bits(const mqg_mdp* agent);
+void mqg_mdp_smoothed_losses(const mqg_mdp* agent, double* out);
+double mqg_mdp_last_reward(const mqg_mdp* agent);
+uint64_t mqg_mdp_decisions(const mqg_mdp* agent);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQGRAD_H */

@@ -1,0 +1,136 @@
+// C-ABI layer of libmqgrad: argument validation and launch set-up.  No arithmetic of the method
+// happens here; the kernels are in quantize_pack.hip and aggregate_update.hip.
+
+#include "kernels.h"
+
+namespace {
+
+bool valid_common(uint32_t bits, uint32_t bucket) {
+    return bits >= 1u && bits <= 8u && bucket >= MQG_MIN_BUCKET && bucket <= MQG_MAX_BUCKET &&
+           (bucket % 32u) == 0u;
+}
+
+int log2_if_pow2(uint32_t v) {
+    if (v == 0u || (v & (v - 1u)) != 0u) return -1;
+    int s = 0;
+    while ((1u << s) != v) ++s;
+    return s;
+}
+
+bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+
+mqg_status quantize_impl(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket, int mode,
+                         uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                         const float* scales_in, bool use_scales_in, uint32_t* packed_out,
+                         float* scales_out, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if ((elem_base & 7u) != 0u) return MQG_EINVAL;
+    if (mode != MQG_SCALE_MAXABS && mode != MQG_SCALE_L2) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (grad == nullptr || packed_out == nullptr || scales_out == nullptr) return MQG_EINVAL;
+    if (use_scales_in && scales_in == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4) || elem_base > UINT64_MAX - n) return MQG_EINVAL;
+    if (misaligned4(grad) || misaligned4(packed_out) || misaligned4(scales_out) ||
+        (use_scales_in && misaligned4(scales_in)))
+        return MQG_EALIGN;
+
+    mqg::QuantizeArgs a;
+    a.grad = grad;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.scale_mode = mode;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.iteration = iteration;
+    a.worker = worker;
+    a.elem_base = elem_base;
+    a.scales_in = use_scales_in ? scales_in : nullptr;
+    a.packed = packed_out;
+    a.scales = scales_out;
+    const hipError_t err = mqg::launch_quantize(a, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mqg_status_string(mqg_status st) {
+    switch (st) {
+        case MQG_OK: return "MQG_OK";
+        case MQG_EINVAL: return "MQG_EINVAL: argument out of range or NULL";
+        case MQG_EALIGN: return "MQG_EALIGN: pointer not 4-byte aligned";
+        case MQG_ELAUNCH: return "MQG_ELAUNCH: HIP launch failed";
+    }
+    return "MQG: unknown status";
+}
+
+size_t mqg_num_buckets(uint64_t n, uint32_t bucket) {
+    if (bucket == 0u) return 0;
+    return (size_t)(n / bucket + (n % bucket != 0u ? 1u : 0u));
+}
+
+size_t mqg_packed_words(uint64_t n, uint32_t bits) {
+    if (bits == 0u) return 0;
+    // n * bits without overflow for any n: split n into whole 32-element cells and the rest
+    const uint64_t cells = n >> 5, rest = n & 31u;
+    return (size_t)(cells * bits + ((rest * bits + 31u) >> 5));
+}
+
+mqg_status mqg_quantize(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                        uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                        uint32_t* packed_out, float* scales_out, void* stream) {
+    return quantize_impl(grad, n, bits, bucket, MQG_SCALE_MAXABS, seed, iteration, worker, elem_base,
+                         nullptr, false, packed_out, scales_out, stream);
+}
+
+mqg_status mqg_quantize_mode(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                             mqg_scale_mode mode,
+                             uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                             uint32_t* packed_out, float* scales_out, void* stream) {
+    return quantize_impl(grad, n, bits, bucket, (int)mode, seed, iteration, worker, elem_base,
+                         nullptr, false, packed_out, scales_out, stream);
+}
+
+mqg_status mqg_quantize_with_scales(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                                    uint64_t seed, uint32_t iteration, uint32_t worker,
+                                    uint64_t elem_base, const float* scales_in,
+                                    uint32_t* packed_out, float* scales_out, void* stream) {
+    return quantize_impl(grad, n, bits, bucket, MQG_SCALE_MAXABS, seed, iteration, worker, elem_base,
+                         scales_in, true, packed_out, scales_out, stream);
+}
+
+mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                uint64_t n, uint32_t bits, uint32_t bucket,
+                                float lr, float* params, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (packed == nullptr || scales == nullptr || params == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(params)) return MQG_EALIGN;
+    mqg::AggregateArgs a;
+    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
+        a.packed[w] = nullptr;
+        a.scales[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || misaligned4(scales[w])) return MQG_EALIGN;
+        a.packed[w] = packed[w];
+        a.scales[w] = scales[w];
+    }
+    a.W = W;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.neg_c = -(lr / (float)W);
+    a.params = params;
+    const hipError_t err = mqg::launch_aggregate(a, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+}  // extern "C"

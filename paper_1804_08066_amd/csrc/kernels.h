@@ -1,0 +1,40 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mqgrad.h"
+
+namespace mqg {
+
+struct QuantizeArgs {
+    const float* grad;       // n floats
+    uint64_t n;
+    uint32_t bits;           // 1..8
+    uint32_t bucket;         // multiple of 32, 32..16384
+    int bucket_shift;        // log2(bucket) when bucket is a power of two, else -1
+    int scale_mode;          // mqg_scale_mode
+    uint32_t key0, key1;     // Philox key = seed
+    uint32_t iteration, worker;
+    uint64_t elem_base;      // multiple of 8
+    const float* scales_in;  // nullable: when set, scales are read, not computed
+    uint32_t* packed;        // ceil(n*bits/32) words
+    float* scales;           // ceil(n/bucket) floats
+};
+
+struct AggregateArgs {
+    const uint32_t* packed[MQG_MAX_WORKERS];
+    const float* scales[MQG_MAX_WORKERS];
+    uint32_t W;
+    uint64_t n;
+    uint32_t bits;
+    uint32_t bucket;
+    int bucket_shift;
+    float neg_c;             // -(lr / W)
+    float* params;
+};
+
+hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
+hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);
+
+}  // namespace mqg

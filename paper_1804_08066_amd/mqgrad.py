@@ -1,0 +1,215 @@
+"""Thin binding over the C-ABI library libmqgrad.so (see include/mqgrad.h).
+
+Argument marshalling only: every step of the quantize / aggregate path runs in the library's
+gfx950 kernels.  torch is used for device memory and streams.  There is no fallback: if the
+library cannot be loaded, importing symbols from it raises.
+"""
+import ctypes as C
+import os
+
+import torch  # noqa: F401  (must be imported before the library so both share one HIP runtime)
+
+from . import build as _build
+
+MQG_OK, MQG_EINVAL, MQG_EALIGN, MQG_ELAUNCH = 0, -1, -2, -3
+MQG_SCALE_MAXABS, MQG_SCALE_L2 = 0, 1
+MQG_MAX_WORKERS = 64
+
+EXPORTS = [
+    "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
+    "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
+    "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
+    "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
+]
+
+
+class MqgError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s" % (where, status_string(status)))
+
+
+class MdpConfig(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("bits_min", C.c_uint32), ("bits_max", C.c_uint32),
+                ("window", C.c_uint32), ("decide_every", C.c_uint32), ("hidden", C.c_uint32),
+                ("alpha", C.c_double), ("epsilon", C.c_double), ("eta", C.c_double),
+                ("reward_scale", C.c_double), ("discount", C.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libmqgrad.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    L = C.CDLL(_build.LIB)
+    vp, u32, u64, f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_float
+    L.mqg_status_string.argtypes = [C.c_int]
+    L.mqg_status_string.restype = C.c_char_p
+    L.mqg_num_buckets.argtypes = [u64, u32]
+    L.mqg_num_buckets.restype = C.c_size_t
+    L.mqg_packed_words.argtypes = [u64, u32]
+    L.mqg_packed_words.restype = C.c_size_t
+    L.mqg_quantize.argtypes = [vp, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp]
+    L.mqg_quantize.restype = C.c_int
+    L.mqg_quantize_mode.argtypes = [vp, u64, u32, u32, C.c_int, u64, u32, u32, u64, vp, vp, vp]
+    L.mqg_quantize_mode.restype = C.c_int
+    L.mqg_quantize_with_scales.argtypes = [vp, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp, vp]
+    L.mqg_quantize_with_scales.restype = C.c_int
+    L.mqg_aggregate_update.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, vp]
+    L.mqg_aggregate_update.restype = C.c_int
+    L.mqg_mdp_default_config.argtypes = [C.POINTER(MdpConfig)]
+    L.mqg_mdp_default_config.restype = None
+    L.mqg_mdp_create.argtypes = [C.POINTER(MdpConfig)]
+    L.mqg_mdp_create.restype = vp
+    L.mqg_mdp_destroy.argtypes = [vp]
+    L.mqg_mdp_destroy.restype = None
+    L.mqg_mdp_step.argtypes = [vp, C.c_double, C.c_double]
+    L.mqg_mdp_step.restype = u32
+    L.mqg_mdp_current_bits.argtypes = [vp]
+    L.mqg_mdp_current_bits.restype = u32
+    L.mqg_mdp_smoothed_losses.argtypes = [vp, C.POINTER(C.c_double)]
+    L.mqg_mdp_smoothed_losses.restype = None
+    L.mqg_mdp_last_reward.argtypes = [vp]
+    L.mqg_mdp_last_reward.restype = C.c_double
+    L.mqg_mdp_decisions.argtypes = [vp]
+    L.mqg_mdp_decisions.restype = u64
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return lib().mqg_status_string(int(status)).decode()
+
+
+def mqg_num_buckets(n, bucket):
+    return int(lib().mqg_num_buckets(n, bucket))
+
+
+def mqg_packed_words(n, bits):
+    return int(lib().mqg_packed_words(n, bits))
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(t, dtype, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (what, dtype))
+
+
+def alloc_outputs(n, bits, bucket, device):
+    packed = torch.empty(mqg_packed_words(n, bits), dtype=torch.int32, device=device)
+    scales = torch.empty(mqg_num_buckets(n, bucket), dtype=torch.float32, device=device)
+    return packed, scales
+
+
+def mqg_quantize(grad, bits, bucket, seed, iteration=0, worker=0, elem_base=0,
+                 packed_out=None, scales_out=None, stream=None, mode=None, scales_in=None):
+    """Worker side.  grad: fp32 CUDA tensor.  Returns (packed int32[words], scales fp32[nb]).
+
+    mode selects mqg_quantize_mode; scales_in selects mqg_quantize_with_scales."""
+    _check(grad, torch.float32, "grad")
+    n = grad.numel()
+    if packed_out is None or scales_out is None:
+        p, s = alloc_outputs(n, bits, bucket, grad.device)
+        packed_out = p if packed_out is None else packed_out
+        scales_out = s if scales_out is None else scales_out
+    _check(packed_out, torch.int32, "packed_out")
+    _check(scales_out, torch.float32, "scales_out")
+    if packed_out.numel() < mqg_packed_words(n, bits) or scales_out.numel() < mqg_num_buckets(n, bucket):
+        raise ValueError("output buffers too small")
+    L = lib()
+    sh = _stream_handle(stream)
+    if scales_in is not None:
+        _check(scales_in, torch.float32, "scales_in")
+        if scales_in.numel() < mqg_num_buckets(n, bucket):
+            raise ValueError("scales_in too small")
+        st = L.mqg_quantize_with_scales(grad.data_ptr(), n, bits, bucket, seed, iteration, worker,
+                                        elem_base, scales_in.data_ptr(), packed_out.data_ptr(),
+                                        scales_out.data_ptr(), sh)
+    elif mode is not None:
+        st = L.mqg_quantize_mode(grad.data_ptr(), n, bits, bucket, int(mode), seed, iteration, worker,
+                                 elem_base, packed_out.data_ptr(), scales_out.data_ptr(), sh)
+    else:
+        st = L.mqg_quantize(grad.data_ptr(), n, bits, bucket, seed, iteration, worker, elem_base,
+                            packed_out.data_ptr(), scales_out.data_ptr(), sh)
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_quantize")
+    return packed_out, scales_out
+
+
+def mqg_aggregate_update(packed, scales, n, bits, bucket, lr, params, stream=None):
+    """Server side.  packed / scales: lists of W CUDA tensors; params: fp32 CUDA tensor, updated in place."""
+    W = len(packed)
+    if W != len(scales):
+        raise ValueError("packed and scales must have one entry per worker")
+    _check(params, torch.float32, "params")
+    if params.numel() != n:
+        raise ValueError("params must have n elements")
+    for p, s in zip(packed, scales):
+        _check(p, torch.int32, "packed[w]")
+        _check(s, torch.float32, "scales[w]")
+        if p.numel() < mqg_packed_words(n, bits) or s.numel() < mqg_num_buckets(n, bucket):
+            raise ValueError("a worker's buffers are too small for n")
+    pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    sa = (C.c_void_p * max(W, 1))(*[s.data_ptr() for s in scales])
+    st = lib().mqg_aggregate_update(pa, sa, W, n, bits, bucket, lr, params.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_update")
+    return params
+
+
+class Mdp:
+    """The host-side agent of Section 3.3 / Algorithm 2 (mqg_mdp_* of the C ABI)."""
+
+    def __init__(self, **overrides):
+        cfg = MdpConfig()
+        lib().mqg_mdp_default_config(C.byref(cfg))
+        for k, v in overrides.items():
+            if not hasattr(cfg, k):
+                raise AttributeError(k)
+            setattr(cfg, k, v)
+        self.cfg = cfg
+        self._h = lib().mqg_mdp_create(C.byref(cfg))
+        if not self._h:
+            raise ValueError("mqg_mdp_create rejected the configuration")
+
+    def step(self, loss, elapsed_ms):
+        return int(lib().mqg_mdp_step(self._h, float(loss), float(elapsed_ms)))
+
+    @property
+    def current_bits(self):
+        return int(lib().mqg_mdp_current_bits(self._h))
+
+    @property
+    def smoothed_losses(self):
+        out = (C.c_double * self.cfg.window)()
+        lib().mqg_mdp_smoothed_losses(self._h, out)
+        return list(out)
+
+    @property
+    def last_reward(self):
+        return float(lib().mqg_mdp_last_reward(self._h))
+
+    @property
+    def decisions(self):
+        return int(lib().mqg_mdp_decisions(self._h))
+
+    def close(self):
+        if self._h:
+            lib().mqg_mdp_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,87 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol that
+include/mqgrad.h declares, does its size arithmetic, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1804_08066_amd import mqgrad
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mqgrad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mqg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = mqgrad.lib()
+    names = declared_symbols()
+    assert set(names) == set(mqgrad.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_size_helpers():
+    assert mqgrad.mqg_num_buckets(0, 512) == 0
+    assert mqgrad.mqg_num_buckets(1, 512) == 1
+    assert mqgrad.mqg_num_buckets(512, 512) == 1
+    assert mqgrad.mqg_num_buckets(513, 512) == 2
+    assert mqgrad.mqg_num_buckets(100_000_000, 1024) == 97657
+    for bits in range(1, 9):
+        for n in (0, 1, 31, 32, 33, 65536, 100_000_000, 1_000_000_000, (1 << 40) + 5):
+            assert mqgrad.mqg_packed_words(n, bits) == (n * bits + 31) // 32
+
+
+def test_status_strings():
+    for st in (0, -1, -2, -3, 5):
+        assert mqgrad.status_string(st)
+    assert "EINVAL" in mqgrad.status_string(mqgrad.MQG_EINVAL)
+
+
+def test_invalid_arguments_are_rejected_before_any_launch():
+    L = mqgrad.lib()
+    fake = C.c_void_p(0x1000)            # never dereferenced: validation fails first
+    q = lambda **kw: L.mqg_quantize(kw.get("grad", fake), kw.get("n", 64), kw.get("bits", 4),
+                                    kw.get("bucket", 512), 0, 0, 0, kw.get("elem_base", 0),
+                                    kw.get("packed", fake), kw.get("scales", fake), None)
+    assert q(bits=0) == mqgrad.MQG_EINVAL
+    assert q(bits=9) == mqgrad.MQG_EINVAL
+    assert q(bucket=0) == mqgrad.MQG_EINVAL
+    assert q(bucket=16) == mqgrad.MQG_EINVAL
+    assert q(bucket=48) == mqgrad.MQG_EINVAL
+    assert q(bucket=16416) == mqgrad.MQG_EINVAL
+    assert q(elem_base=4) == mqgrad.MQG_EINVAL
+    assert q(grad=None) == mqgrad.MQG_EINVAL
+    assert q(packed=None) == mqgrad.MQG_EINVAL
+    assert q(scales=None) == mqgrad.MQG_EINVAL
+    assert q(grad=C.c_void_p(0x1002)) == mqgrad.MQG_EALIGN
+    assert q(packed=C.c_void_p(0x1001)) == mqgrad.MQG_EALIGN
+    assert q(n=0, grad=None, packed=None, scales=None) == mqgrad.MQG_OK      # empty input is a no-op
+    assert L.mqg_quantize_mode(fake, 64, 4, 512, 7, 0, 0, 0, 0, fake, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_quantize_with_scales(fake, 64, 4, 512, 0, 0, 0, 0, None, fake, fake, None) == mqgrad.MQG_EINVAL
+
+    vp = C.c_void_p
+    one = (vp * 1)(0x1000)
+    null1 = (vp * 1)(None)
+    a = lambda packed=one, scales=one, W=1, n=64, bits=4, bucket=512, params=fake: \
+        L.mqg_aggregate_update(packed, scales, W, n, bits, bucket, 0.1, params, None)
+    assert a(W=0) == mqgrad.MQG_EINVAL
+    assert a(W=65) == mqgrad.MQG_EINVAL
+    assert a(bits=0) == mqgrad.MQG_EINVAL
+    assert a(bucket=100) == mqgrad.MQG_EINVAL
+    assert a(params=None) == mqgrad.MQG_EINVAL
+    assert a(packed=None) == mqgrad.MQG_EINVAL
+    assert a(packed=null1) == mqgrad.MQG_EINVAL
+    assert a(scales=null1) == mqgrad.MQG_EINVAL
+    assert a(params=C.c_void_p(0x1003)) == mqgrad.MQG_EALIGN
+    assert a(n=0, params=None) == mqgrad.MQG_OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        mqgrad.mqg_quantize(torch.zeros(64), 4, 32, 0)

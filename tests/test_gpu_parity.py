@@ -1,0 +1,185 @@
+"""GPU parity: the gfx950 library against the CPU oracle, element by element, through the C ABI.
+
+Bars: packed words and max-abs scales bit-exact; updated parameters within 1e-6 relative
+(the fp32 operation order is fixed on both sides, so they are in fact expected to be equal).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_1804_08066_amd import mqgrad, workloads
+from helpers import (assert_quantize_parity, gpu_quantize, param_tolerance, to_u32, ulp_distance)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ALL_BITS = list(range(1, 9))
+
+
+def run_aggregate(pk_list, sc_list, n, bits, bucket, lr, params_host):
+    dev_pk = [torch.from_numpy(p.view(np.int32).copy()).to(DEV) for p in pk_list]
+    dev_sc = [torch.from_numpy(s.copy()).to(DEV) for s in sc_list]
+    p = torch.from_numpy(params_host.copy()).to(DEV)
+    mqgrad.mqg_aggregate_update(dev_pk, dev_sc, n, bits, bucket, lr, p)
+    torch.cuda.synchronize()
+    return p.cpu().numpy()
+
+
+def assert_aggregate_parity(pk_list, sc_list, n, bits, bucket, lr, params_host, label=""):
+    got = run_aggregate(pk_list, sc_list, n, bits, bucket, lr, params_host)
+    want = ref.aggregate_update(pk_list, sc_list, n, bits, bucket, lr, params_host)
+    deq = [ref.dequantize(pk_list[w], sc_list[w], n, bits, bucket) for w in range(len(pk_list))]
+    tol = param_tolerance(params_host, lr, len(pk_list), deq)
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= tol), "%s params off by up to %g (tol %g)" % (label, err.max(), tol[err.argmax()])
+    ulps = ulp_distance(got, want)
+    assert ulps.max() == 0, "%s params differ from the oracle by up to %d ulp" % (label, ulps.max())
+    return got
+
+
+# ---- configuration 1: every word, every parameter, every b -------------------------------------
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_config1_full_parity(bits):
+    cfg = workloads.config1(DEV)
+    g, p = cfg["grad"], cfg["params"]
+    pk, sc = assert_quantize_parity(g, bits, cfg["bucket"], seed=0, label="cfg1 b=%d" % bits)
+    got = assert_aggregate_parity([pk], [sc], g.numel(), bits, cfg["bucket"], cfg["lr"], p.cpu().numpy(),
+                                  label="cfg1 b=%d" % bits)
+    # round trip: |dequant - g| < 2 s / L
+    deq = ref.dequantize(pk, sc, g.numel(), bits, cfg["bucket"])
+    delta = 2 * np.repeat(sc, cfg["bucket"]).astype(np.float64) / ((1 << bits) - 1)
+    assert np.all(np.abs(deq.astype(np.float64) - g.cpu().numpy()) < delta * (1 + 1e-5))
+    assert not np.array_equal(got, p.cpu().numpy())
+
+
+# ---- ragged sizes, every bucket class, every b ---------------------------------------------------
+
+RAGGED_N = [1, 3, 4, 31, 32, 33, 100, 511, 513, 4095, 4096, 4097, 5000, 12345, 40000]
+BUCKETS = [32, 96, 128, 480, 512, 1024, 2048, 4096, 4128, 8192, 12000 // 32 * 32, 16384]
+
+
+@pytest.mark.parametrize("bucket", BUCKETS)
+def test_ragged_sizes_all_bits(bucket):
+    for n in RAGGED_N:
+        g = workloads.laplace(n, 3e-3, 100 + n, DEV)
+        p = workloads.uniform(n, -0.05, 0.05, 7 + n, DEV).cpu().numpy()
+        for bits in ALL_BITS:
+            label = "n=%d B=%d b=%d" % (n, bucket, bits)
+            pk, sc = assert_quantize_parity(g, bits, bucket, seed=n * 8 + bits, iteration=3, worker=1, label=label)
+            assert_aggregate_parity([pk], [sc], n, bits, bucket, 0.1, p, label=label)
+
+
+def test_multi_tile_with_ragged_tail_and_straddling_widths():
+    n = 3 * 16384 + 4096 + 777
+    g = workloads.normal_with_outliers(n, 1e-3, 1e-3, 100.0, 5, DEV)
+    for bucket in (128, 512, 2048, 8192, 16384):
+        for bits in (3, 5, 6, 7):
+            assert_quantize_parity(g, bits, bucket, seed=11, iteration=9, worker=5, label="B=%d b=%d" % (bucket, bits))
+
+
+def test_unaligned_views():
+    base = workloads.normal(20000, 0.01, 3, DEV)
+    pbase = workloads.uniform(20000, -0.05, 0.05, 4, DEV)
+    n = 9001
+    for off in (1, 2, 3):
+        g = base[off:off + n]                      # 4-byte aligned only
+        for bits in (1, 3, 8):
+            pk, sc = assert_quantize_parity(g, bits, 512, seed=2, label="off=%d b=%d" % (off, bits))
+            whole = pbase.clone()
+            pv = whole[off:off + n]
+            dpk = [torch.from_numpy(pk.view(np.int32).copy()).to(DEV)]
+            dsc = [torch.from_numpy(sc.copy()).to(DEV)]
+            mqgrad.mqg_aggregate_update(dpk, dsc, n, bits, 512, 0.1, pv)
+            torch.cuda.synchronize()
+            want = ref.aggregate_update([pk], [sc], n, bits, 512, 0.1, pbase[off:off + n].cpu().numpy())
+            assert np.array_equal(pv.cpu().numpy(), want)
+            # neighbours of the view are untouched
+            assert torch.equal(whole[:off], pbase[:off]) and torch.equal(whole[off + n:], pbase[off + n:])
+
+
+def test_random_stream_arguments():
+    g = workloads.normal(8192 + 40, 0.01, 9, DEV)
+    for (seed, it, wk, base) in [(0, 0, 0, 0), (1, 0, 0, 0), (0, 1, 0, 0), (0, 0, 1, 0), (0, 0, 0, 8),
+                                 (0xDEADBEEFCAFEF00D, 4000000000, 4000000001, (1 << 36) + 4096),
+                                 (5, 6, 7, (1 << 35) - 8)]:
+        assert_quantize_parity(g, 4, 512, seed, it, wk, base, label=str((seed, it, wk, base)))
+    # different stream arguments give different codes
+    a, _ = gpu_quantize(g, 4, 512, 0, 0, 0, 0)
+    b, _ = gpu_quantize(g, 4, 512, 0, 1, 0, 0)
+    c, _ = gpu_quantize(g, 4, 512, 0, 0, 0, 8)
+    assert not np.array_equal(a, b) and not np.array_equal(a, c)
+
+
+def test_degenerate_buckets():
+    n = 4096
+    g = torch.zeros(n, device=DEV)
+    g[512:1024] = 2.0 ** -100          # below the kept range: scale stored as 0
+    g[1024:1536] = 1.0                 # every element at +s
+    g[1536:2048] = -3.5                # every element at -s
+    g[2048] = 1e-30                    # one tiny element alone in an otherwise zero bucket
+    g[2560:3072] = torch.linspace(-1, 1, 512, device=DEV)
+    for bits in ALL_BITS:
+        pk, sc = assert_quantize_parity(g, bits, 512, seed=bits, label="degenerate b=%d" % bits)
+        assert sc[0] == 0 and sc[1] == 0
+        p = np.zeros(n, dtype=np.float32)
+        got = assert_aggregate_parity([pk], [sc], n, bits, 512, 1.0, p)
+        assert np.all(got[:1024] == 0)
+        assert np.all(got[1024:1536] == -1.0) and np.all(got[1536:2048] == 3.5)
+
+
+def test_injected_scales():
+    n, bucket = 10000, 512
+    g = workloads.normal(n, 0.01, 21, DEV)
+    gh = g.cpu().numpy()
+    nb = ref.num_buckets(n, bucket)
+    rng = np.random.default_rng(0)
+    inj = (np.abs(rng.normal(0.02, 0.01, nb)) + 1e-3).astype(np.float32)   # some smaller than max|g|: clamps
+    inj[3] = 0.0
+    for bits in (2, 5, 8):
+        s_in = torch.from_numpy(inj).to(DEV)
+        pk_g, sc_g = gpu_quantize(g, bits, bucket, 77, 1, 2, 0, scales_in=s_in)
+        pk_o, sc_o = ref.quantize(gh, bits, bucket, 77, 1, 2, 0, scales_in=inj)
+        assert sc_g.tobytes() == inj.tobytes() == sc_o.tobytes()
+        assert np.array_equal(pk_g, pk_o)
+
+
+@pytest.mark.parametrize("W", [2, 4, 8, 9, 16, 17, 64])
+def test_many_workers(W):
+    n, bucket = 6000, 96
+    for bits in (1, 3, 4, 8):
+        pks, scs = [], []
+        for w in range(W):
+            g = workloads.laplace(n, 1e-3 * (1 + w), 300 + w, DEV)
+            pk, sc = assert_quantize_parity(g, bits, bucket, seed=5, iteration=2, worker=w)
+            pks.append(pk)
+            scs.append(sc)
+        p = workloads.uniform(n, -0.05, 0.05, 8, "cpu").numpy()
+        assert_aggregate_parity(pks, scs, n, bits, bucket, 0.2, p, label="W=%d b=%d" % (W, bits))
+
+
+def test_outputs_are_fully_overwritten_and_neighbours_untouched():
+    n, bits, bucket = 5000, 3, 512
+    g = workloads.normal(n, 0.01, 1, DEV)
+    words, nb = mqgrad.mqg_packed_words(n, bits), mqgrad.mqg_num_buckets(n, bucket)
+    packed = torch.full((words + 8,), -1, dtype=torch.int32, device=DEV)
+    scales = torch.full((nb + 8,), -7.0, dtype=torch.float32, device=DEV)
+    mqgrad.mqg_quantize(g, bits, bucket, 3, packed_out=packed, scales_out=scales)
+    torch.cuda.synchronize()
+    pk_o, sc_o = ref.quantize(g.cpu().numpy(), bits, bucket, 3)
+    assert np.array_equal(to_u32(packed[:words]), pk_o)
+    assert np.all(packed[words:].cpu().numpy() == -1)
+    assert np.array_equal(scales[:nb].cpu().numpy(), sc_o) and np.all(scales[nb:].cpu().numpy() == -7.0)
+
+
+def test_runs_on_a_side_stream_and_is_deterministic():
+    n = 100000
+    g = workloads.normal(n, 0.01, 2, DEV)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        a = mqgrad.mqg_quantize(g, 5, 1024, 9)
+    s.synchronize()
+    b = mqgrad.mqg_quantize(g, 5, 1024, 9)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
