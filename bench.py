@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the MQGrad hot path on one MI355X.
+
+A step is one training iteration's worth of gradient traffic through the whole path: W workers'
+fp32 gradients are each quantized and packed (mqg_quantize), then the server unpacks, de-quantizes
+and averages the W streams and updates the parameters (mqg_aggregate_update).  Inputs are resident
+in HBM before the timed region.  `value` is GB/s of fp32 gradient processed (4*N*W bytes per step).
+
+The headline workload is the bandwidth-sweep configuration: a flat 100M-element gradient
+~ N(0, 0.01^2), W = 8 worker buffers, at b = 4 bits and bucket 1024; `--sweep` adds the whole
+(b, bucket) grid to the JSON line.  Synthetic data stands in for the paper's CIFAR-10 CNN
+gradients (Section 4.1); the paper reports no throughput for this path.
+
+One JSON line on stdout; progress on stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def quantize_bytes(n, bits, bucket):
+    """Algorithmic bytes of one quantize launch: read the gradient once, write codes and scales once."""
+    return 4.0 * n + n * bits / 8.0 + 4.0 * ((n + bucket - 1) // bucket)
+
+
+def aggregate_bytes(n, bits, bucket, W):
+    """Algorithmic bytes of one aggregate_update launch: W code streams + scales in, parameters in and out."""
+    return W * (n * bits / 8.0 + 4.0 * ((n + bucket - 1) // bucket)) + 8.0 * n
+
+
+class Workload:
+    def __init__(self, n, W, device):
+        import torch
+        from paper_1804_08066_amd import workloads
+        self.n, self.W, self.device = n, W, device
+        log("generating %d gradient buffers of %d fp32 (%.2f GB)" % (W, n, 4e-9 * n * W))
+        self.grads = [workloads.config4_grad(w, n, device) for w in range(W)]
+        self.params = workloads.uniform(n, -0.05, 0.05, 1, device)
+        self.bufs = {}
+        torch.cuda.synchronize()
+
+    def outputs(self, bits, bucket):
+        from paper_1804_08066_amd import mqgrad
+        key = (bits, bucket)
+        if key not in self.bufs:
+            self.bufs.clear()
+            self.bufs[key] = [mqgrad.alloc_outputs(self.n, bits, bucket, self.device) for _ in range(self.W)]
+        return self.bufs[key]
+
+
+def run_steps(wl, bits, bucket, lr, steps, iteration0, events=None):
+    """Enqueue `steps` iterations.  events: optional list that receives (e0, e1, e2) per step."""
+    import torch
+    from paper_1804_08066_amd import mqgrad
+    outs = wl.outputs(bits, bucket)
+    pk = [o[0] for o in outs]
+    sc = [o[1] for o in outs]
+    for k in range(steps):
+        if events is not None:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ev[0].record()
+        for w in range(wl.W):
+            mqgrad.mqg_quantize(wl.grads[w], bits, bucket, seed=1234, iteration=iteration0 + k, worker=w,
+                                packed_out=pk[w], scales_out=sc[w])
+        if events is not None:
+            ev[1].record()
+        mqgrad.mqg_aggregate_update(pk, sc, wl.n, bits, bucket, lr, wl.params)
+        if events is not None:
+            ev[2].record()
+            events.append(ev)
+
+
+def time_config(wl, bits, bucket, lr, steps, warmup):
+    import torch
+    run_steps(wl, bits, bucket, lr, warmup, 0)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    run_steps(wl, bits, bucket, lr, steps, warmup, events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    q_ms = sum(e[0].elapsed_time(e[1]) for e in events) / (steps * wl.W)     # per quantize launch
+    a_ms = sum(e[1].elapsed_time(e[2]) for e in events) / steps              # per aggregate launch
+    return (t1 - t0) / steps * 1e3, q_ms, a_ms
+
+
+def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
+    """The oracle as it stands, single thread, on a slice of the same workload (host tensors)."""
+    import numpy as np
+    from oracle import ref
+    from paper_1804_08066_amd import workloads
+    log("cpu baseline: oracle on a %d-element slice, W=%d, %d step(s)" % (sample_n, W, steps))
+    grads = [workloads.config4_grad(w, sample_n, "cpu").numpy() for w in range(W)]
+    params = workloads.uniform(sample_n, -0.05, 0.05, 1, "cpu").numpy()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        outs = [ref.quantize(grads[w], bits, bucket, 1234, k, w) for w in range(W)]
+        params = ref.aggregate_update([o[0] for o in outs], [o[1] for o in outs], sample_n, bits, bucket, lr, params)
+    dt = time.perf_counter() - t0
+    gbs = 4.0 * sample_n * W * steps / dt / 1e9
+    return {"value": gbs, "unit": "GB/s fp32 gradient", "cores": 1, "kind": "oracle",
+            "sample": "%d-element slice of the same workload, W=%d, b=%d, bucket=%d, %d step(s), %.1f s"
+                      % (sample_n, W, bits, bucket, steps, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--n", type=int, default=100_000_000)
+    ap.add_argument("--workers", type=int, default=8)
+    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--bucket", type=int, default=1024)
+    ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--sweep", action="store_true", help="also time every (b, bucket) of the sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
+                         "the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--cpu-sample", type=int, default=16_000_000)
+    ap.add_argument("--cpu-steps", type=int, default=3)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; W workers are W gradient buffers on it. "
+              "--gpus %d is not supported (no inter-GPU path exists)." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1804_08066_amd import mqgrad
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    mqgrad.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    n, W, bits, bucket = args.n, args.workers, args.bits, args.bucket
+    wl = Workload(n, W, dev)
+
+    ms_step, q_ms, a_ms = time_config(wl, bits, bucket, args.lr, args.steps, args.warmup)
+    value = 4.0 * n * W / (ms_step * 1e-3) / 1e9
+    qb, ab = quantize_bytes(n, bits, bucket), aggregate_bytes(n, bits, bucket, W)
+    q_gbs, a_gbs = qb / (q_ms * 1e-3) / 1e9, ab / (a_ms * 1e-3) / 1e9
+    log("step %.3f ms | quantize %.1f us/launch %.0f GB/s | aggregate %.1f us %.0f GB/s" %
+        (ms_step, q_ms * 1e3, q_gbs, a_ms * 1e3, a_gbs))
+
+    out = {
+        "metric": "GB/s fp32 gradient quantize+pack and unpack+aggregate+update; % HBM peak",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "bandwidth sweep point: flat fp32 gradient of %d elements ~ N(0, 0.01^2), "
+                               "W=%d worker buffers, b=%d, bucket=%d; one step = %d x quantize + 1 x aggregate_update"
+                               % (n, W, bits, bucket, W),
+                   "n": n, "workers": W, "bits": bits, "bucket": bucket},
+        # quantize_pack runs W times per step and is the dominant kernel by time
+        "roofline": {"bound": "hbm", "kernel": "quantize_pack_kernel", "achieved": q_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": q_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": qb, "avg_launch_us": q_ms * 1e3},
+        "roofline_aggregate": {"bound": "hbm", "kernel": "aggregate_update_kernel", "achieved": a_gbs,
+                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a_gbs / HBM_PEAK_GBS, "traffic": None,
+                               "algorithmic_bytes_per_launch": ab, "avg_launch_us": a_ms * 1e3},
+        "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    }
+
+    if args.sweep:
+        rows = []
+        for bk in (128, 1024, 8192):
+            for b in (1, 2, 4, 8):
+                ms, q, a = time_config(wl, b, bk, args.lr, max(5, args.steps // 4), 2)
+                rows.append({"bits": b, "bucket": bk, "ms_per_step": ms,
+                             "grad_gbs": 4.0 * n * W / (ms * 1e-3) / 1e9,
+                             "quantize_us": q * 1e3, "quantize_hbm_frac": quantize_bytes(n, b, bk) / (q * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "aggregate_us": a * 1e3, "aggregate_hbm_frac": aggregate_bytes(n, b, bk, W) / (a * 1e-3) / 1e9 / HBM_PEAK_GBS})
+                log("sweep b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%)" %
+                    (b, bk, q * 1e3, 100 * rows[-1]["quantize_hbm_frac"], a * 1e3, 100 * rows[-1]["aggregate_hbm_frac"]))
+        out["sweep"] = rows
+
+    if args.calibrate_copy:
+        dst = torch.empty_like(wl.grads[0])
+        for w in range(3):
+            dst.copy_(wl.grads[w % W])
+        torch.cuda.synchronize()
+        del dst
+
+    del wl
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(bits, bucket, W, args.lr, min(args.cpu_sample, n), args.cpu_steps)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
