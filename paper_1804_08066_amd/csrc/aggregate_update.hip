@@ -8,44 +8,53 @@
 //   a7  update                 p <- fma(-(lr/W), acc, p)
 //
 // Work decomposition.  A workgroup of 256 lanes owns a tile of 1024*R consecutive parameters
-// (R float4 per lane, coalesced).  The code words of the tile (tile*bits/32 words per worker,
-// contiguous because tiles start at multiples of 32 elements) are staged through LDS in chunks of
-// workers, together with the per-bucket steps s_w/L, so the small code stream is also read with
-// full-width coalesced loads and no lane fetches a word twice from memory.  The de-quantized
-// gradient never exists in HBM.
+// (R float4 per lane, coalesced 128-bit loads and stores).  The 4 codes of a lane's quad are the
+// 4*bits stream bits that start at bit 4*bits*quad: inside one 32-bit word when bits divides 32,
+// spilling into the next word otherwise.  Each lane fetches that word (or word pair) of every
+// worker with aligned dword loads -- adjacent lanes read the same or adjacent words, so a wave's
+// request is one contiguous run of 32*bits bytes -- and all loads of a chunk of 8 workers are
+// issued before any is consumed.  Parameters and codes are touched once, so they move with the
+// non-temporal hint.  The de-quantized gradient never exists in HBM.
+//
+// The per-bucket steps d = s_w / L (one IEEE division per bucket and worker) are shared in one of
+// two ways.  Buckets that are multiples of 128 elements: a wave's row of 256 parameters touches
+// at most two buckets, so lane w divides worker w's scale(s) of the row and the worker loop reads
+// them back with v_readlane -- no LDS, no barrier.  Any other bucket size: a table in LDS, one
+// barrier.
 
 #include "kernels.h"
+
+#ifndef MQG_AGG_ROWS_R
+#define MQG_AGG_ROWS_R 2
+#endif
 
 namespace mqg {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kR = 2;                         // float4 per lane
-constexpr uint32_t kTile = 1024u * kR;        // parameters per workgroup
-constexpr uint32_t kChunk = 8;                // workers staged in LDS at a time
-constexpr uint32_t kMaxWords = kTile * 8u / 32u + 2u;   // per worker, at 8 bits, + pad for the straddle read
-constexpr uint32_t kMaxBuckets = kTile / 32u + 1u;      // buckets a tile can touch
+constexpr int kChunk = 8;   // workers whose code loads are in flight together
 
-template <bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void aggregate_update_kernel(const AggregateArgs a) {
-    __shared__ uint32_t s_words[kChunk][kMaxWords];
-    __shared__ float s_step[kChunk][kMaxBuckets];
+typedef float v4f __attribute__((ext_vector_type(4)));
 
+__device__ __forceinline__ float4 load_f4_stream(const float* p) {
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void store_f4_stream(float* p, const float4& r) {
+    v4f t = {r.x, r.y, r.z, r.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+}
+
+template <int R, bool ALIGNED>
+__device__ __forceinline__ void load_params(const float* __restrict__ p, uint32_t tile_count, bool full,
+                                            float4 (&x)[R]) {
     const uint32_t tid = threadIdx.x;
-    const uint64_t tile_base = (uint64_t)blockIdx.x * kTile;
-    const uint64_t left = a.n - tile_base;
-    const uint32_t tile_count = left < kTile ? (uint32_t)left : kTile;
-    const bool full = tile_count == kTile;
-    float* __restrict__ p = a.params + tile_base;
-
-    // ---- parameters of the tile -------------------------------------------------------------
-    float4 x[kR];
 #pragma unroll
-    for (int j = 0; j < kR; ++j) {
+    for (int j = 0; j < R; ++j) {
         const uint32_t el = 4u * (j * kThreads + tid);
         if (full || el + 4u <= tile_count) {
             if (ALIGNED) {
-                x[j] = *reinterpret_cast<const float4*>(p + el);
+                x[j] = load_f4_stream(p + el);
             } else {
                 x[j] = make_float4(p[el], p[el + 1], p[el + 2], p[el + 3]);
             }
@@ -53,83 +62,27 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_kernel(const Aggreg
             x[j].x = (el + 0u < tile_count) ? p[el + 0] : 0.0f;
             x[j].y = (el + 1u < tile_count) ? p[el + 1] : 0.0f;
             x[j].z = (el + 2u < tile_count) ? p[el + 2] : 0.0f;
-            x[j].w = 0.0f;
+            x[j].w = 0.0f;   // el + 3 >= tile_count here
         }
     }
+}
 
-    const uint32_t b = a.bits;
-    const uint32_t L = (1u << b) - 1u;
-    const float Lf = (float)L;
-    const uint32_t nwords = (tile_count * b + 31u) >> 5;
-    const uint64_t word_base = (tile_base >> 5) * b;
-    const uint64_t kb0 = tile_base / a.bucket;
-    const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;
-    const uint32_t first_off = (uint32_t)(tile_base - kb0 * a.bucket);   // offset of the tile in its first bucket
-
-    // per-quad constants
-    uint32_t bl[kR], wi[kR], sh[kR];
+// a7: p <- fma(-(lr/W), acc, p)
+template <int R, bool ALIGNED>
+__device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t tile_count, bool full, float neg_c,
+                                              const float4 (&x)[R], const float4 (&acc)[R]) {
+    const uint32_t tid = threadIdx.x;
 #pragma unroll
-    for (int j = 0; j < kR; ++j) {
-        const uint32_t ql = j * kThreads + tid;
-        const uint32_t eo = 4u * ql + first_off;
-        bl[j] = a.bucket_shift >= 0 ? (eo >> a.bucket_shift) : (eo / a.bucket);
-        const uint32_t bit = 4u * b * ql;
-        wi[j] = bit >> 5;
-        sh[j] = bit & 31u;
-    }
-
-    float4 acc[kR];
-#pragma unroll
-    for (int j = 0; j < kR; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-
-    for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        const uint32_t wc = (a.W - w0 < kChunk) ? (a.W - w0) : kChunk;
-        if (w0 > 0) __syncthreads();   // the previous chunk has been consumed
-        // ---- stage code words and bucket steps of workers [w0, w0 + wc) ----------------------
-        for (uint32_t w = 0; w < wc; ++w) {
-            const uint32_t* __restrict__ src = a.packed[w0 + w] + word_base;
-            for (uint32_t i = tid; i < nwords; i += kThreads) s_words[w][i] = src[i];
-            if (tid < 2u) s_words[w][nwords + tid] = 0u;
-        }
-        for (uint32_t i = tid; i < wc * nbt; i += kThreads) {
-            const uint32_t w = i / nbt, kb = i - w * nbt;
-            s_step[w][kb] = a.scales[w0 + w][kb0 + kb] / Lf;   // IEEE-correct fp32 division
-        }
-        __syncthreads();
-
-        // ---- a5, a6: unpack, de-quantize, accumulate in worker order ------------------------
-        for (uint32_t w = 0; w < wc; ++w) {
-#pragma unroll
-            for (int j = 0; j < kR; ++j) {
-                if (bl[j] >= nbt) continue;   // quad entirely past the end of the vector
-                const float d = s_step[w][bl[j]];
-                const uint32_t lo = s_words[w][wi[j]];
-                const uint32_t hi = s_words[w][wi[j] + 1u];
-                const uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh[j]);   // ({hi,lo} >> sh)[31:0]
-                const int k0 = (int)__builtin_amdgcn_ubfe(v, 0u, b);
-                const int k1 = (int)__builtin_amdgcn_ubfe(v, b, b);
-                const int k2 = (int)__builtin_amdgcn_ubfe(v, 2u * b, b);
-                const int k3 = (int)__builtin_amdgcn_ubfe(v, 3u * b, b);
-                acc[j].x = __builtin_fmaf((float)(2 * k0 - (int)L), d, acc[j].x);
-                acc[j].y = __builtin_fmaf((float)(2 * k1 - (int)L), d, acc[j].y);
-                acc[j].z = __builtin_fmaf((float)(2 * k2 - (int)L), d, acc[j].z);
-                acc[j].w = __builtin_fmaf((float)(2 * k3 - (int)L), d, acc[j].w);
-            }
-        }
-    }
-
-    // ---- a7: SGD step with the mean -----------------------------------------------------------
-#pragma unroll
-    for (int j = 0; j < kR; ++j) {
+    for (int j = 0; j < R; ++j) {
         const uint32_t el = 4u * (j * kThreads + tid);
         float4 r;
-        r.x = __builtin_fmaf(a.neg_c, acc[j].x, x[j].x);
-        r.y = __builtin_fmaf(a.neg_c, acc[j].y, x[j].y);
-        r.z = __builtin_fmaf(a.neg_c, acc[j].z, x[j].z);
-        r.w = __builtin_fmaf(a.neg_c, acc[j].w, x[j].w);
+        r.x = __builtin_fmaf(neg_c, acc[j].x, x[j].x);
+        r.y = __builtin_fmaf(neg_c, acc[j].y, x[j].y);
+        r.z = __builtin_fmaf(neg_c, acc[j].z, x[j].z);
+        r.w = __builtin_fmaf(neg_c, acc[j].w, x[j].w);
         if (full || el + 4u <= tile_count) {
             if (ALIGNED) {
-                *reinterpret_cast<float4*>(p + el) = r;
+                store_f4_stream(p + el, r);
             } else {
                 p[el] = r.x; p[el + 1] = r.y; p[el + 2] = r.z; p[el + 3] = r.w;
             }
@@ -141,20 +94,270 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_kernel(const Aggreg
     }
 }
 
-}  // namespace
+// Where the codes of the lane's R quads sit in every worker's stream (tile-local word indices,
+// clamped to the last word of the stream so that quads past the end still read valid memory).
+template <int R>
+struct CodeWindows {
+    uint32_t word[R];    // first word
+    uint32_t word2[R];   // following word (clamped); used only by widths that straddle
+    uint32_t sh[R];      // bit offset of the first code inside `word`
+    uint64_t tile_word;  // first word of the tile in the stream
+};
 
-hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream) {
-    if (a.n == 0) return hipSuccess;
-    const uint64_t tiles = (a.n + kTile - 1) / kTile;
+template <int R>
+__device__ __forceinline__ CodeWindows<R> code_windows(uint64_t n, uint64_t tile_base, uint32_t b) {
+    CodeWindows<R> cw;
+    cw.tile_word = (tile_base >> 5) * b;   // tile_base is a multiple of 32
+    const uint64_t stream_words = (n >> 5) * b + ((((n & 31u) * b) + 31u) >> 5);
+    const uint64_t room = stream_words - cw.tile_word;   // >= 1
+    const uint32_t last_word = room - 1u > 0x3FFFFFFFull ? 0x3FFFFFFFu : (uint32_t)(room - 1u);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t ql = j * kThreads + threadIdx.x;
+        const uint32_t bit = 4u * b * ql;
+        uint32_t word = bit >> 5, sh = bit & 31u;
+        if (word > last_word) {   // quad entirely past the end
+            word = last_word;
+            sh = 0u;
+        }
+        cw.word[j] = word;
+        cw.word2[j] = word < last_word ? word + 1u : last_word;
+        cw.sh[j] = sh;
+    }
+    return cw;
+}
+
+template <int R, bool STRADDLE>
+struct CodeRegs {
+    uint32_t lo[kChunk][R];
+    uint32_t hi[kChunk][STRADDLE ? R : 1];
+};
+
+// a5 (fetch): code words of workers [w0, w0 + kChunk); surplus slots reload the last worker.
+template <int R, bool STRADDLE>
+__device__ __forceinline__ void fetch_codes(const AggregateArgs& a, uint32_t w0, const CodeWindows<R>& cw,
+                                            CodeRegs<R, STRADDLE>& c) {
+#pragma unroll
+    for (int t = 0; t < kChunk; ++t) {
+        const uint32_t w = (w0 + t < a.W) ? w0 + t : a.W - 1u;
+        const uint32_t* __restrict__ src = a.packed[w] + cw.tile_word;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            c.lo[t][j] = __builtin_nontemporal_load(src + cw.word[j]);
+            if (STRADDLE) c.hi[t][j] = __builtin_nontemporal_load(src + cw.word2[j]);
+        }
+    }
+}
+
+// a5 (decode) + a6: one worker's 4 codes of one quad, de-quantized with step d and accumulated.
+template <bool STRADDLE>
+__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t hi, uint32_t sh, uint32_t b, int negL,
+                                                float d, float4& acc) {
+    uint32_t v, o;
+    if (STRADDLE) {
+        v = __builtin_amdgcn_alignbit(hi, lo, sh);   // ({hi,lo} >> sh)[31:0]
+        o = 0u;
+    } else {
+        v = lo;
+        o = sh;
+    }
+    const int k0 = (int)__builtin_amdgcn_ubfe(v, o, b);
+    const int k1 = (int)__builtin_amdgcn_ubfe(v, o + b, b);
+    const int k2 = (int)__builtin_amdgcn_ubfe(v, o + 2u * b, b);
+    const int k3 = (int)__builtin_amdgcn_ubfe(v, o + 3u * b, b);
+    acc.x = __builtin_fmaf((float)(2 * k0 + negL), d, acc.x);
+    acc.y = __builtin_fmaf((float)(2 * k1 + negL), d, acc.y);
+    acc.z = __builtin_fmaf((float)(2 * k2 + negL), d, acc.z);
+    acc.w = __builtin_fmaf((float)(2 * k3 + negL), d, acc.w);
+}
+
+__device__ __forceinline__ float readlane_f32(float v, uint32_t lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), (int)lane));
+}
+
+// ---- buckets that are multiples of 128: bucket steps live in the wave ---------------------------
+// NBR = buckets a 256-element row can touch: 1 when the bucket is a multiple of 256, else 2.
+template <int R, int NBR, bool STRADDLE, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const AggregateArgs a) {
+    constexpr uint32_t TILE = 1024u * R;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint64_t tile_base = (uint64_t)blockIdx.x * TILE;
+    const uint64_t left = a.n - tile_base;
+    const uint32_t tile_count = left < TILE ? (uint32_t)left : TILE;
+    const bool full = tile_count == TILE;
+    float* __restrict__ p = a.params + tile_base;
+
+    // lane w holds worker w's scale pointer (one vector load from the kernel-argument table)
+    const float* my_scales = a.scales[lane < a.W ? lane : 0u];
+
+    float4 x[R];
+    load_params<R, ALIGNED>(p, tile_count, full, x);
+
+    const uint32_t b = a.bits;
+    const int negL = -(int)((1u << b) - 1u);
+    const float Lf = (float)((1u << b) - 1u);
+    const CodeWindows<R> cw = code_windows<R>(a.n, tile_base, b);
+    CodeRegs<R, STRADDLE> c;
+    fetch_codes<R, STRADDLE>(a, 0u, cw, c);
+
+    // bucket steps of this wave's rows: lane w divides worker w's scale(s)
+    const uint64_t nb_total = (a.n + a.bucket - 1u) / a.bucket;
+    const uint64_t kb0 = tile_base / a.bucket;
+    const uint32_t first_off = (uint32_t)(tile_base - kb0 * a.bucket);
+    float d[R][NBR];
+    bool second[R];   // this lane's quad lies in the row's second bucket
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t row_off = first_off + 1024u * j + 256u * wave;   // row start relative to bucket kb0
+        const uint32_t kr = a.bucket_shift >= 0 ? (row_off >> a.bucket_shift) : (row_off / a.bucket);
+        const uint32_t in_bucket = row_off - kr * a.bucket;
+        second[j] = (NBR > 1) && (in_bucket + 4u * lane >= a.bucket);
+#pragma unroll
+        for (int i = 0; i < NBR; ++i) {
+            uint64_t kb = kb0 + kr + i;
+            if (kb >= nb_total) kb = nb_total - 1u;   // row (or its second bucket) past the end
+            d[j][i] = my_scales[kb] / Lf;             // IEEE-correct fp32 division
+        }
+    }
+
+    float4 acc[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+    for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
+        if (w0 > 0) fetch_codes<R, STRADDLE>(a, w0, cw, c);
+#pragma unroll
+        for (int t = 0; t < kChunk; ++t) {
+            if (w0 + t < a.W) {
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    float dw = readlane_f32(d[j][0], w0 + t);
+                    if (NBR > 1) dw = second[j] ? readlane_f32(d[j][NBR - 1], w0 + t) : dw;
+                    accumulate_quad<STRADDLE>(c.lo[t][j], c.hi[t][STRADDLE ? j : 0], cw.sh[j], b, negL, dw, acc[j]);
+                }
+            }
+        }
+    }
+    update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+}
+
+// ---- any other bucket size: bucket steps shared through LDS -------------------------------------
+constexpr int kLdsR = 2;
+constexpr uint32_t kLdsTile = 1024u * kLdsR;
+constexpr uint32_t kMaxBuckets = kLdsTile / 32u + 1u;   // buckets a tile can touch
+
+template <bool STRADDLE, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const AggregateArgs a) {
+    constexpr int R = kLdsR;
+    extern __shared__ float s_step[];   // [W][nbt]
+
+    const uint32_t tid = threadIdx.x;
+    const uint64_t tile_base = (uint64_t)blockIdx.x * kLdsTile;
+    const uint64_t left = a.n - tile_base;
+    const uint32_t tile_count = left < kLdsTile ? (uint32_t)left : kLdsTile;
+    const bool full = tile_count == kLdsTile;
+    float* __restrict__ p = a.params + tile_base;
+
+    float4 x[R];
+    load_params<R, ALIGNED>(p, tile_count, full, x);
+
+    const uint32_t b = a.bits;
+    const int negL = -(int)((1u << b) - 1u);
+    const float Lf = (float)((1u << b) - 1u);
+    const CodeWindows<R> cw = code_windows<R>(a.n, tile_base, b);
+    CodeRegs<R, STRADDLE> c;
+    fetch_codes<R, STRADDLE>(a, 0u, cw, c);   // in flight while the bucket steps are computed
+
+    const uint64_t kb0 = tile_base / a.bucket;
+    const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
+    const uint32_t first_off = (uint32_t)(tile_base - kb0 * a.bucket);
+    uint32_t bl[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t eo = 4u * (j * kThreads + tid) + first_off;
+        bl[j] = a.bucket_shift >= 0 ? (eo >> a.bucket_shift) : (eo / a.bucket);
+        if (bl[j] >= nbt) bl[j] = nbt - 1u;   // quads past the end: any valid slot
+    }
+    if (tid < nbt) {
+        for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
+            float sv[kChunk];
+#pragma unroll
+            for (int t = 0; t < kChunk; ++t) {
+                const uint32_t w = (w0 + t < a.W) ? w0 + t : a.W - 1u;
+                sv[t] = a.scales[w][kb0 + tid];
+            }
+#pragma unroll
+            for (int t = 0; t < kChunk; ++t) {
+                if (w0 + t < a.W) s_step[(w0 + t) * nbt + tid] = sv[t] / Lf;   // IEEE-correct fp32 division
+            }
+        }
+    }
+    __syncthreads();
+
+    float4 acc[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+    for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
+        if (w0 > 0) fetch_codes<R, STRADDLE>(a, w0, cw, c);
+#pragma unroll
+        for (int t = 0; t < kChunk; ++t) {
+            if (w0 + t < a.W) {
+                const float* __restrict__ dw = s_step + (w0 + t) * nbt;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    accumulate_quad<STRADDLE>(c.lo[t][j], c.hi[t][STRADDLE ? j : 0], cw.sh[j], b, negL, dw[bl[j]], acc[j]);
+                }
+            }
+        }
+    }
+    update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+}
+
+template <int R, int NBR, bool STRADDLE>
+hipError_t launch_rows(const AggregateArgs& a, hipStream_t stream) {
+    const uint32_t tile = 1024u * R;
+    const uint64_t tiles = (a.n + tile - 1) / tile;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     if (aligned) {
-        hipLaunchKernelGGL((aggregate_update_kernel<true>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, true>), grid, block, 0, stream, a);
     } else {
-        hipLaunchKernelGGL((aggregate_update_kernel<false>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, false>), grid, block, 0, stream, a);
     }
     return hipGetLastError();
+}
+
+template <bool STRADDLE>
+hipError_t launch_lds(const AggregateArgs& a, hipStream_t stream) {
+    const uint64_t tiles = (a.n + kLdsTile - 1) / kLdsTile;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
+    const dim3 grid((uint32_t)tiles), block(kThreads);
+    const size_t lds = sizeof(float) * a.W * kMaxBuckets;
+    if (aligned) {
+        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, true>), grid, block, lds, stream, a);
+    } else {
+        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, false>), grid, block, lds, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream) {
+    if (a.n == 0) return hipSuccess;
+    constexpr int R = MQG_AGG_ROWS_R;
+    const bool straddle = (32u % a.bits) != 0u;   // widths 3, 5, 6, 7
+    if (a.bucket % 256u == 0u) {
+        return straddle ? launch_rows<R, 1, true>(a, stream) : launch_rows<R, 1, false>(a, stream);
+    }
+    if (a.bucket % 128u == 0u) {
+        return straddle ? launch_rows<R, 2, true>(a, stream) : launch_rows<R, 2, false>(a, stream);
+    }
+    return straddle ? launch_lds<true>(a, stream) : launch_lds<false>(a, stream);
 }
 
 }  // namespace mqg
