@@ -35,6 +35,8 @@ struct AggregateArgs {
 };
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
+bool quantize_wave_supported(const QuantizeArgs& a);          // quantize_wave.hip
+hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);
 
 }  // namespace mqg

@@ -33,6 +33,8 @@ constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]: lane ^ 1
 constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]: lane ^ 2
 constexpr int kDppRowHalfMirror = 0x141; // lane i <-> 7 - i inside each group of 8
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
@@ -95,7 +97,8 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
         const uint32_t el = 4u * (j * kThreads + tid);
         if (FULL || el + 4u <= tile_count) {
             if (ALIGNED) {
-                x[j] = *reinterpret_cast<const float4*>(g + el);
+                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + el));   // read once: streaming
+                x[j] = make_float4(t.x, t.y, t.z, t.w);
             } else {
                 x[j] = make_float4(g[el], g[el + 1], g[el + 2], g[el + 3]);
             }
@@ -236,7 +239,7 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
 
     // ---- store whole words, coalesced -------------------------------------------------------
     uint32_t* __restrict__ out = a.packed + (tile_base >> 5) * b;
-    for (uint32_t i = tid; i < nwords; i += kThreads) out[i] = s_words[i];
+    for (uint32_t i = tid; i < nwords; i += kThreads) __builtin_nontemporal_store(s_words[i], out + i);
 }
 
 template <int R, bool ALIGNED>
@@ -275,6 +278,7 @@ hipError_t launch_r(const QuantizeArgs& a, hipStream_t stream) {
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
+    if (quantize_wave_supported(a)) return launch_quantize_wave(a, stream);
     if (a.bucket <= 4096u) return launch_r<4>(a, stream);
     if (a.bucket <= 8192u) return launch_r<8>(a, stream);
     return launch_r<16>(a, stream);

@@ -1,0 +1,308 @@
+// Worker side of MQGrad's hot path on gfx950, wavefront-local variant: Quantize(g, K) of
+// Algorithm 1 (WorkerIterate), the range-linear K-bit encode of the Section 3.2 footnote, for
+// power-of-two buckets and 16-byte aligned gradients.  (Other bucket sizes and alignments take the
+// workgroup-cooperative kernel in quantize_pack.hip; both produce the same bits.)
+//
+//   a1  per-bucket range  s = max |g|           DPP / swizzle butterfly inside the wave
+//   a2  position on the 2^K-level grid          u = clamp(fma(g, (L/2)/s, L/2), 0, L)
+//   a3  stochastic rounding, Philox4x32-10      c = floor(u) + [(h + 1/2)/65536 < frac(u)]
+//   a4  dense little-endian bit packing         LDS-staged per wave, 128-bit stores
+//
+// Work decomposition.  Each 64-lane wave owns a chunk of CH = 256*R consecutive elements and keeps
+// it in registers (R float4 per lane: row j of the chunk is the 256 elements the wave loads with
+// one float4 per lane), so every gradient byte is read from HBM exactly once.  Buckets of up to CH
+// elements live entirely inside one wave: range reduction, the one IEEE division per bucket, the
+// rounding and the packing need no workgroup barrier.  Larger buckets (WPB = 2 or 4 waves per
+// bucket) exchange one value per wave through LDS behind a single barrier.
+//
+// The kernel is bound by vector-ALU issue rather than by HBM once the loads stream, so work is
+// moved off the vector ALU where possible: cross-lane exchange through LDS-pipe swizzles, per-bucket
+// values through small per-wave LDS tables, bit placement through LDS atomics.
+
+#include "kernels.h"
+
+namespace mqg {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+
+constexpr int kDppQuadSwap1 = 0xB1;       // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int kDppQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
+constexpr int kDppRowMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
+constexpr int kSwizzleXor16 = 0x401F;     // bit-mode swizzle: and 0x1F, or 0, xor 0x10
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
+}
+__device__ __forceinline__ float swizzle_xor16_f32(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleXor16));
+}
+__device__ __forceinline__ float bpermute_xor32_f32(float v, uint32_t lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), __builtin_bit_cast(int, v)));
+}
+
+// max over the `seg_lanes` lanes (8, 16, 32 or 64) that share a bucket; every lane of the segment
+// ends up with the segment's maximum
+__device__ __forceinline__ float segment_max(float m, uint32_t seg_lanes, uint32_t lane) {
+    m = fmaxf(m, dpp_f32<kDppQuadSwap1>(m));
+    m = fmaxf(m, dpp_f32<kDppQuadSwap2>(m));
+    m = fmaxf(m, dpp_f32<kDppRowHalfMirror>(m));
+    if (seg_lanes >= 16u) m = fmaxf(m, dpp_f32<kDppRowMirror>(m));
+    if (seg_lanes >= 32u) m = fmaxf(m, swizzle_xor16_f32(m));
+    if (seg_lanes >= 64u) m = fmaxf(m, bpermute_xor32_f32(m, lane));
+    return m;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11).
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+    }
+    o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
+}
+
+// code of one element: floor(u) + [(h + 1/2) / 65536 < frac(u)].
+// The comparison is evaluated as  h < frac*65536 - 1/2 : the right-hand side is exact in fp32
+// whenever it is non-negative (frac*65536 < 2^16 has an ulp of at most 2^-8), and negative
+// otherwise, so both forms decide identically for every integer h in [0, 65535].
+__device__ __forceinline__ uint32_t round_code(float x, float ainv, float halfL, float Lf, uint32_t h16) {
+    float u = __builtin_fmaf(x, ainv, halfL);
+    u = __builtin_amdgcn_fmed3f(u, 0.0f, Lf);
+    const float fr = __builtin_amdgcn_fractf(u);
+    const float t = __builtin_fmaf(fr, 65536.0f, -0.5f);
+    const float hf = (float)h16;
+    return (uint32_t)u + ((hf < t) ? 1u : 0u);
+}
+
+// LDS of one workgroup: everything is indexed by wave, so waves never touch each other's entries
+// (except wave_max, which is what the WPB > 1 barrier is for).
+template <int R>
+struct WaveShared {
+    alignas(16) uint32_t words[kWaves][64 * R + 4];   // packed output of a chunk: 8*R*bits <= 64*R words
+    float smax[kWaves][8 * R];            // per-bucket max |g| of the chunk (<= CH/32 buckets)
+    float ainv[kWaves][8 * R];            // per-bucket (L/2)/s
+    float wave_max[kWaves];               // chunk maximum, for buckets that span several waves
+};
+
+// R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; 2, 4: bucket = WPB*CH)
+template <int R, int WPB>
+__global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeArgs a) {
+    constexpr uint32_t CH = 256u * R;
+    __shared__ WaveShared<R> sm;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint64_t chunk = (uint64_t)blockIdx.x * kWaves + wave;
+    const uint64_t cb = chunk * CH;                 // first element of the chunk
+    const bool active = cb < a.n;                   // waves past the end only keep the barrier company
+    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
+    const bool full = count == CH;
+    const uint32_t b = a.bits;
+    const uint32_t nwords = (count * b + 31u) >> 5;
+    const float* __restrict__ g = a.grad + cb;
+
+    // ---- load the chunk (one HBM pass) -------------------------------------------------------
+    float4 x[R];
+    if (full) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + 4u * (j * 64u + lane)));
+            x[j] = make_float4(t.x, t.y, t.z, t.w);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const uint32_t el = 4u * (j * 64u + lane);
+            x[j].x = (el + 0u < count) ? g[el + 0] : 0.0f;
+            x[j].y = (el + 1u < count) ? g[el + 1] : 0.0f;
+            x[j].z = (el + 2u < count) ? g[el + 2] : 0.0f;
+            x[j].w = (el + 3u < count) ? g[el + 3] : 0.0f;
+        }
+    }
+
+    // clear the packing area of this wave while the loads are in flight (LDS is in order per wave)
+    for (uint32_t i = lane; i < 16u * R; i += 64u) {
+        *reinterpret_cast<v4u*>(&sm.words[wave][4u * i]) = v4u{0u, 0u, 0u, 0u};
+    }
+
+    // ---- a1: bucket range ----------------------------------------------------------------------
+    // WPB == 1: the chunk holds nbc = CH / bucket whole buckets; a bucket is `seg_lanes` lanes of one
+    // row (bucket <= 256) or `rpb` whole rows (bucket >= 256).  WPB > 1: the chunk is part of one bucket.
+    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 5
+    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);                    // buckets per chunk
+    const uint32_t seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
+    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);   // rows per bucket
+    const float Lf = (float)((1u << b) - 1u);
+    const float halfL = 0.5f * Lf;
+    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);    // global index of the chunk's first bucket
+    uint32_t slot[R];                                                      // bucket (chunk-local) of row j's quad
+#pragma unroll
+    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> shift);
+
+    if (a.scales_in == nullptr) {
+        float m[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            m[j] = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
+        }
+        // fold the rows of one bucket into its first row
+#pragma unroll
+        for (int step = 1; step < R; step <<= 1) {
+            if (rpb > (uint32_t)step) {
+#pragma unroll
+                for (int j = 0; j + step < R; j += 2 * step) m[j] = fmaxf(m[j], m[j + step]);
+            }
+        }
+        // reduce across the lanes of the bucket; the first lane of each bucket publishes the result
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (((uint32_t)j & (rpb - 1u)) == 0u) {
+                const float r = segment_max(m[j], seg_lanes, lane);
+                if ((lane & (seg_lanes - 1u)) == 0u) sm.smax[wave][slot[j]] = r;
+            }
+        }
+    }
+    if (WPB > 1) {
+        // buckets spanning WPB waves: share the chunk maxima
+        if (a.scales_in == nullptr && lane == 0u) sm.wave_max[wave] = sm.smax[wave][0];
+        __syncthreads();
+        if (a.scales_in == nullptr && lane == 0u) {
+            const uint32_t w0 = wave & ~(uint32_t)(WPB - 1);
+            float r = sm.wave_max[w0];
+#pragma unroll
+            for (int t = 1; t < WPB; ++t) r = fmaxf(r, sm.wave_max[w0 + t]);
+            sm.smax[wave][0] = r;
+        }
+    }
+    if (!active) return;
+
+    // one lane per bucket: floor, store the scale, divide once
+    if (lane < nbc) {
+        const bool exists = WPB > 1 ? true : ((lane << shift) < count);    // bucket starts inside the vector
+        float s = 0.0f;
+        if (exists) {
+            if (a.scales_in != nullptr) {
+                s = a.scales_in[kb_first + lane];
+            } else {
+                s = sm.smax[wave][lane];
+                if (!(s >= 0x1p-96f)) s = 0.0f;
+            }
+            if (WPB == 1 || (wave & (WPB - 1)) == 0u) a.scales[kb_first + lane] = s;
+        }
+        sm.ainv[wave][lane] = (s > 0.0f) ? halfL / s : 0.0f;   // IEEE-correct fp32 division, once per bucket
+    }
+
+    // ---- a2..a4: grid position, stochastic rounding, packing -----------------------------------
+    const uint32_t odd = lane & 1u;
+    const uint64_t group0 = (a.elem_base + cb) >> 3;           // both multiples of 8
+    const uint32_t cell_bit = 4u * b * (lane & 7u);            // this lane's bit offset in its 32-element cell
+    const uint32_t sh = cell_bit & 31u;
+    const uint32_t word_in_cell = cell_bit >> 5;
+    const bool straddle = sh + 4u * b > 32u;
+
+#pragma unroll
+    for (int jp = 0; jp < R; jp += 2) {
+        // One Philox call covers 8 consecutive elements = the quads of an even/odd lane pair.  The
+        // even lane draws for row jp, the odd lane for row jp + 1; each then takes the half it
+        // needs from its partner (a select whose other input comes through a DPP lane swap).
+        const uint32_t my_row = jp + odd;
+        const uint64_t grp = group0 + (uint64_t)((my_row * 64u + lane) >> 1);
+        uint32_t o[4];
+        philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
+        // the swaps run with every lane active (a lane swap under a divergent branch would read
+        // switched-off partners); the selects that follow keep the half each lane needs
+        const uint32_t p0 = dpp_u32<kDppQuadSwap1>(o[0]), p1 = dpp_u32<kDppQuadSwap1>(o[1]);
+        const uint32_t p2 = dpp_u32<kDppQuadSwap1>(o[2]), p3 = dpp_u32<kDppQuadSwap1>(o[3]);
+        const uint32_t rw[2][2] = {{odd ? p2 : o[0], odd ? p3 : o[1]},    // row jp: the even lane's call
+                                   {odd ? o[2] : p0, odd ? o[3] : p1}};   // row jp+1: the odd lane's call
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int j = jp + t;
+            const uint32_t ql = j * 64u + lane;
+            const uint32_t el = 4u * ql;
+            const float ainv = sm.ainv[wave][slot[j]];
+            uint32_t k0 = round_code(x[j].x, ainv, halfL, Lf, rw[t][0] & 0xFFFFu);
+            uint32_t k1 = round_code(x[j].y, ainv, halfL, Lf, rw[t][0] >> 16);
+            uint32_t k2 = round_code(x[j].z, ainv, halfL, Lf, rw[t][1] & 0xFFFFu);
+            uint32_t k3 = round_code(x[j].w, ainv, halfL, Lf, rw[t][1] >> 16);
+            if (!full) {   // elements past the end contribute zero bits
+                if (el + 0u >= count) k0 = 0u;
+                if (el + 1u >= count) k1 = 0u;
+                if (el + 2u >= count) k2 = 0u;
+                if (el + 3u >= count) k3 = 0u;
+            }
+            const uint32_t v = k0 | (k1 << b) | (k2 << (2u * b)) | (k3 << (3u * b));
+            if (full || el < count) {
+                const uint32_t w0 = (ql >> 3) * b + word_in_cell;
+                atomicOr(&sm.words[wave][w0], v << sh);
+                if (straddle) atomicOr(&sm.words[wave][w0 + 1u], v >> (32u - sh));
+            }
+        }
+    }
+
+    // ---- store the chunk's words ----------------------------------------------------------------
+    uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
+    if (full && (reinterpret_cast<uintptr_t>(a.packed) & 15u) == 0u) {
+        for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
+            const v4u w = *reinterpret_cast<const v4u*>(&sm.words[wave][4u * i]);
+            __builtin_nontemporal_store(w, reinterpret_cast<v4u*>(out) + i);
+        }
+    } else {
+        for (uint32_t i = lane; i < nwords; i += 64u) out[i] = sm.words[wave][i];
+    }
+}
+
+template <int R, int WPB>
+hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
+    const uint64_t per_group = (uint64_t)kWaves * 256u * R;
+    const uint64_t groups = (a.n + per_group - 1) / per_group;
+    if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB>), dim3((uint32_t)groups), dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// True when the wave-local kernel covers this call: max-abs or injected scales, power-of-two bucket,
+// 16-byte aligned gradient.
+bool quantize_wave_supported(const QuantizeArgs& a) {
+    return a.bucket_shift >= 5 && a.scale_mode == MQG_SCALE_MAXABS &&
+           (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
+}
+
+hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
+    switch (a.bucket) {
+        case 2048: return launch_wave<4, 2>(a, stream);
+        case 4096: return launch_wave<4, 4>(a, stream);
+        case 8192: return launch_wave<8, 4>(a, stream);
+        case 16384: return launch_wave<16, 4>(a, stream);
+        default: return launch_wave<4, 1>(a, stream);   // 32 .. 1024
+    }
+}
+
+}  // namespace mqg
