@@ -151,9 +151,10 @@ mqg_mdp* mqg_mdp_create(const mqg_mdp_config* cfg);
 void mqg_mdp_destroy(mqg_mdp* agent);
 
 /* Feed the global loss of training iteration m = 0, 1, 2, ... and the wall time (ms) that the
- * previous iteration took; returns the number of bits to use for iteration m.  The bit width
- * changes only when m is a multiple of decide_every and never decreases.  Returns 0 if agent
- * is NULL. */
+ * previous iteration took; returns the number of bits K = n_t + a_t to use for iteration m.  K
+ * changes only when m is a multiple of decide_every.  The state's width n_t never decreases; an
+ * exploratory "one more bit" (a_t = 1 against the greedy choice) lasts for one period, as the
+ * paper's transition function moves n_t by the greedy action only.  Returns 0 if agent is NULL. */
 uint32_t mqg_mdp_step(mqg_mdp* agent, double loss, double elapsed_ms);
 
 /* Introspection for tests: current n_t, the smoothed-loss window (writes `window` doubles,

@@ -175,6 +175,7 @@ mqg_mdp* mqg_mdp_create(const mqg_mdp_config* cfg) {
     if (cfg->window < 2 || cfg->window > 1024 || cfg->decide_every < 1 || cfg->hidden < 1 || cfg->hidden > 4096) return nullptr;
     mqg_mdp* m = new (std::nothrow) mqg_mdp();
     if (!m) return nullptr;
+    try {
     m->cfg = *cfg;
     m->rng.state = cfg->seed;
     m->n_out = cfg->bits_max - cfg->bits_min + 1;
@@ -200,6 +201,10 @@ mqg_mdp* mqg_mdp_create(const mqg_mdp_config* cfg) {
     m->prev_action = 0;
     m->prev_greedy = 0;
     m->last_reward = 0.0;
+    } catch (...) {   // allocation failure: nothing crosses the C boundary
+        delete m;
+        return nullptr;
+    }
     return m;
 }
 
@@ -221,7 +226,13 @@ uint32_t mqg_mdp_step(mqg_mdp* agent, double loss, double elapsed_ms) {
     m.window.back() = smooth;
     m.period_ms += elapsed_ms;
     uint32_t bits = m.bits_out;
-    if (m.iteration % m.cfg.decide_every == 0) bits = m.decide();
+    if (m.iteration % m.cfg.decide_every == 0) {
+        try {
+            bits = m.decide();
+        } catch (...) {   // allocation failure inside a decision: keep the current width
+            bits = m.bits_out;
+        }
+    }
     m.iteration += 1;
     return bits;
 }
