@@ -25,6 +25,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
+# of known size (profiles/quantize_aggregate_100M_W8_b4_B1024_hbm_traffic.md).  Only the workload
+# that was profiled has an entry; any other reports null.
+MEASURED_TRAFFIC = {
+    # (n, workers, bits, bucket): (quantize bytes per launch, aggregate_update bytes per launch)
+    (100_000_000, 8, 4, 1024): (450.87e6, 1225.06e6),
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -118,8 +126,9 @@ def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps; the chip needs ~30 ms of sustained load before its clocks settle")
     ap.add_argument("--n", type=int, default=100_000_000)
     ap.add_argument("--workers", type=int, default=8)
     ap.add_argument("--bits", type=int, default=4)
@@ -157,6 +166,7 @@ def main():
     log("step %.3f ms | quantize %.1f us/launch %.0f GB/s | aggregate %.1f us %.0f GB/s" %
         (ms_step, q_ms * 1e3, q_gbs, a_ms * 1e3, a_gbs))
 
+    q_traffic, a_traffic = MEASURED_TRAFFIC.get((n, W, bits, bucket), (None, None))
     out = {
         "metric": "GB/s fp32 gradient quantize+pack and unpack+aggregate+update; % HBM peak",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -166,12 +176,12 @@ def main():
                                "W=%d worker buffers, b=%d, bucket=%d; one step = %d x quantize + 1 x aggregate_update"
                                % (n, W, bits, bucket, W),
                    "n": n, "workers": W, "bits": bits, "bucket": bucket},
-        # quantize_pack runs W times per step and is the dominant kernel by time
-        "roofline": {"bound": "hbm", "kernel": "quantize_pack_kernel", "achieved": q_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": q_gbs / HBM_PEAK_GBS, "traffic": None,
+        # the quantize kernel runs W times per step and is the dominant kernel by time
+        "roofline": {"bound": "hbm", "kernel": "quantize_wave_kernel", "achieved": q_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": q_gbs / HBM_PEAK_GBS, "traffic": q_traffic,
                      "algorithmic_bytes_per_launch": qb, "avg_launch_us": q_ms * 1e3},
-        "roofline_aggregate": {"bound": "hbm", "kernel": "aggregate_update_kernel", "achieved": a_gbs,
-                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a_gbs / HBM_PEAK_GBS, "traffic": None,
+        "roofline_aggregate": {"bound": "hbm", "kernel": "aggregate_update_rows_kernel", "achieved": a_gbs,
+                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a_gbs / HBM_PEAK_GBS, "traffic": a_traffic,
                                "algorithmic_bytes_per_launch": ab, "avg_launch_us": a_ms * 1e3},
         "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
@@ -180,7 +190,7 @@ def main():
         rows = []
         for bk in (128, 1024, 8192):
             for b in (1, 2, 4, 8):
-                ms, q, a = time_config(wl, b, bk, args.lr, max(5, args.steps // 4), 2)
+                ms, q, a = time_config(wl, b, bk, args.lr, max(5, args.steps // 4), max(2, args.warmup // 4))
                 rows.append({"bits": b, "bucket": bk, "ms_per_step": ms,
                              "grad_gbs": 4.0 * n * W / (ms * 1e-3) / 1e9,
                              "quantize_us": q * 1e3, "quantize_hbm_frac": quantize_bytes(n, b, bk) / (q * 1e-3) / 1e9 / HBM_PEAK_GBS,

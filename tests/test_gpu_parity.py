@@ -183,3 +183,27 @@ def test_runs_on_a_side_stream_and_is_deterministic():
     b = mqgrad.mqg_quantize(g, 5, 1024, 9)
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ---- L2-norm bucket scale (the norm scaling of the QSGD family cited in Section 2) --------------
+
+@pytest.mark.parametrize("bucket", [128, 480, 1024, 8192])
+def test_l2_scale_mode(bucket):
+    n = 3 * 8192 + 1000
+    g = workloads.normal_with_outliers(n, 1e-2, 1e-2, 30.0, 77, DEV)
+    gh = g.cpu().numpy()
+    sc_o = ref.bucket_scales(gh, bucket, ref.SCALE_L2)
+    for bits in (2, 5, 8):
+        # scales: within 1e-6 relative of the oracle's fp64 norm
+        pk_g, sc_g = gpu_quantize(g, bits, bucket, 9, 1, 2, 0, mode=mqgrad.MQG_SCALE_L2)
+        assert np.all(np.abs(sc_g.astype(np.float64) - sc_o) <= 1e-6 * sc_o)
+        maxabs = ref.bucket_scales(gh, bucket, ref.SCALE_MAXABS)
+        assert np.all(sc_g >= maxabs)
+        # reproducible
+        pk_g2, sc_g2 = gpu_quantize(g, bits, bucket, 9, 1, 2, 0, mode=mqgrad.MQG_SCALE_L2)
+        assert np.array_equal(pk_g, pk_g2) and np.array_equal(sc_g, sc_g2)
+        # codes: bit-exact once the oracle's scales are injected
+        s_in = torch.from_numpy(sc_o).to(DEV)
+        pk_i, sc_i = gpu_quantize(g, bits, bucket, 9, 1, 2, 0, scales_in=s_in)
+        pk_o, _ = ref.quantize(gh, bits, bucket, 9, 1, 2, 0, scale_mode=ref.SCALE_L2)
+        assert np.array_equal(sc_i, sc_o) and np.array_equal(pk_i, pk_o)
