@@ -10,10 +10,10 @@
 // Work decomposition.  A workgroup of 256 lanes owns a tile of 1024*R consecutive parameters
 // (R float4 per lane, coalesced 128-bit loads and stores).  The 4 codes of a lane's quad are the
 // 4*bits stream bits that start at bit 4*bits*quad: inside one 32-bit word when bits divides 32,
-// spilling into the next word otherwise.  Each lane fetches that word (or word pair) of every
-// worker with aligned dword loads -- adjacent lanes read the same or adjacent words, so a wave's
-// request is one contiguous run of 32*bits bytes -- and all loads of a chunk of 8 workers are
-// issued before any is consumed.  Parameters and codes are touched once, so they move with the
+// spilling into the next word otherwise (and that word is the next lane's first word).  Each lane
+// fetches its first word of every worker with one aligned dword load -- adjacent lanes read the same
+// or adjacent words, so a wave's request is one contiguous run of 32*bits bytes -- and all loads of
+// a chunk of 8 workers are issued before any is consumed.  Parameters and codes are touched once, so they move with the
 // non-temporal hint.  The de-quantized gradient never exists in HBM.
 //
 // The per-bucket steps d = s_w / L (one IEEE division per bucket and worker) are shared in one of
@@ -33,6 +33,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kChunk = 8;   // workers whose code loads are in flight together
+constexpr int kDppWaveShl1 = 0x130;   // DPP wave_shl:1: lane i reads lane i + 1 (lane 63 keeps its old value)
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -99,7 +100,6 @@ __device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t ti
 template <int R>
 struct CodeWindows {
     uint32_t word[R];    // first word
-    uint32_t word2[R];   // following word (clamped); used only by widths that straddle
     uint32_t sh[R];      // bit offset of the first code inside `word`
     uint64_t tile_word;  // first word of the tile in the stream
 };
@@ -121,22 +121,20 @@ __device__ __forceinline__ CodeWindows<R> code_windows(uint64_t n, uint64_t tile
             sh = 0u;
         }
         cw.word[j] = word;
-        cw.word2[j] = word < last_word ? word + 1u : last_word;
         cw.sh[j] = sh;
     }
     return cw;
 }
 
-template <int R, bool STRADDLE>
+template <int R>
 struct CodeRegs {
     uint32_t lo[kChunk][R];
-    uint32_t hi[kChunk][STRADDLE ? R : 1];
 };
 
 // a5 (fetch): code words of workers [w0, w0 + kChunk); surplus slots reload the last worker.
-template <int R, bool STRADDLE>
+template <int R>
 __device__ __forceinline__ void fetch_codes(const AggregateArgs& a, uint32_t w0, const CodeWindows<R>& cw,
-                                            CodeRegs<R, STRADDLE>& c) {
+                                            CodeRegs<R>& c) {
 #pragma unroll
     for (int t = 0; t < kChunk; ++t) {
         const uint32_t w = (w0 + t < a.W) ? w0 + t : a.W - 1u;
@@ -144,17 +142,21 @@ __device__ __forceinline__ void fetch_codes(const AggregateArgs& a, uint32_t w0,
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             c.lo[t][j] = __builtin_nontemporal_load(src + cw.word[j]);
-            if (STRADDLE) c.hi[t][j] = __builtin_nontemporal_load(src + cw.word2[j]);
         }
     }
 }
 
 // a5 (decode) + a6: one worker's 4 codes of one quad, de-quantized with step d and accumulated.
 template <bool STRADDLE>
-__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t hi, uint32_t sh, uint32_t b, int negL,
+__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32_t b, int negL,
                                                 float d, float4& acc) {
     uint32_t v, o;
     if (STRADDLE) {
+        // A quad that spills over its first word continues in the first word of the next lane (that
+        // lane's quad starts where this one ends), so the second word comes through a one-lane DPP
+        // shift instead of a second load.  A wave's 64 quads are 8*bits whole words, so lane 63
+        // never spills and what it reads here is never used.
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, kDppWaveShl1, 0xF, 0xF, false);
         v = __builtin_amdgcn_alignbit(hi, lo, sh);   // ({hi,lo} >> sh)[31:0]
         o = 0u;
     } else {
@@ -198,8 +200,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     const int negL = -(int)((1u << b) - 1u);
     const float Lf = (float)((1u << b) - 1u);
     const CodeWindows<R> cw = code_windows<R>(a.n, tile_base, b);
-    CodeRegs<R, STRADDLE> c;
-    fetch_codes<R, STRADDLE>(a, 0u, cw, c);
+    CodeRegs<R> c;
+    fetch_codes<R>(a, 0u, cw, c);
 
     // bucket steps of this wave's rows: lane w divides worker w's scale(s)
     const uint64_t nb_total = (a.n + a.bucket - 1u) / a.bucket;
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) fetch_codes<R, STRADDLE>(a, w0, cw, c);
+        if (w0 > 0) fetch_codes<R>(a, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
                 for (int j = 0; j < R; ++j) {
                     float dw = readlane_f32(d[j][0], w0 + t);
                     if (NBR > 1) dw = second[j] ? readlane_f32(d[j][NBR - 1], w0 + t) : dw;
-                    accumulate_quad<STRADDLE>(c.lo[t][j], c.hi[t][STRADDLE ? j : 0], cw.sh[j], b, negL, dw, acc[j]);
+                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], b, negL, dw, acc[j]);
                 }
             }
         }
@@ -266,8 +268,8 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const Ag
     const int negL = -(int)((1u << b) - 1u);
     const float Lf = (float)((1u << b) - 1u);
     const CodeWindows<R> cw = code_windows<R>(a.n, tile_base, b);
-    CodeRegs<R, STRADDLE> c;
-    fetch_codes<R, STRADDLE>(a, 0u, cw, c);   // in flight while the bucket steps are computed
+    CodeRegs<R> c;
+    fetch_codes<R>(a, 0u, cw, c);   // in flight while the bucket steps are computed
 
     const uint64_t kb0 = tile_base / a.bucket;
     const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
@@ -300,14 +302,14 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const Ag
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) fetch_codes<R, STRADDLE>(a, w0, cw, c);
+        if (w0 > 0) fetch_codes<R>(a, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {
                 const float* __restrict__ dw = s_step + (w0 + t) * nbt;
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    accumulate_quad<STRADDLE>(c.lo[t][j], c.hi[t][STRADDLE ? j : 0], cw.sh[j], b, negL, dw[bl[j]], acc[j]);
+                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], b, negL, dw[bl[j]], acc[j]);
                 }
             }
         }
