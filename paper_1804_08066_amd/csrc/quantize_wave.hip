@@ -55,6 +55,11 @@ __device__ __forceinline__ float bpermute_xor32_f32(float v, uint32_t lane) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), __builtin_bit_cast(int, v)));
 }
 
+// lane ^ 1 exchange on the LDS pipe (bit-mode swizzle: and 0x1F, or 0, xor 1): costs no vector-ALU issue
+__device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x041F);
+}
+
 // max over the `seg_lanes` lanes (8, 16, 32 or 64) that share a bucket; every lane of the segment
 // ends up with the segment's maximum
 __device__ __forceinline__ float segment_max(float m, uint32_t seg_lanes, uint32_t lane) {
@@ -109,26 +114,13 @@ struct WaveShared {
     float wave_max[kWaves];               // chunk maximum, for buckets that span several waves
 };
 
-// R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; 2, 4: bucket = WPB*CH)
-template <int R, int WPB>
-__global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeArgs a) {
-    constexpr uint32_t CH = 256u * R;
-    __shared__ WaveShared<R> sm;
-
-    const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u, wave = tid >> 6;
-    const uint64_t chunk = (uint64_t)blockIdx.x * kWaves + wave;
-    const uint64_t cb = chunk * CH;                 // first element of the chunk
-    const bool active = cb < a.n;                   // waves past the end only keep the barrier company
-    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
-    const bool full = count == CH;
-    const uint32_t b = a.bits;
-    const uint32_t nwords = (count * b + 31u) >> 5;
-    const float* __restrict__ g = a.grad + cb;
-
-    // ---- load the chunk (one HBM pass) -------------------------------------------------------
-    float4 x[R];
-    if (full) {
+// ---- phase 1: load the chunk, clear the wave's packing area, publish the bucket maxima -----------
+template <int R, int WPB, bool FULL>
+__device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const float* __restrict__ g, uint32_t count,
+                                                uint32_t lane, uint32_t wave, const uint32_t (&slot)[R],
+                                                uint32_t seg_lanes, uint32_t rpb, float4 (&x)[R], WaveShared<R>& sm) {
+    // one HBM pass
+    if (FULL) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + 4u * (j * 64u + lane)));
@@ -144,66 +136,57 @@ __global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeA
             x[j].w = (el + 3u < count) ? g[el + 3] : 0.0f;
         }
     }
-
     // clear the packing area of this wave while the loads are in flight (LDS is in order per wave)
     for (uint32_t i = lane; i < 16u * R; i += 64u) {
         *reinterpret_cast<v4u*>(&sm.words[wave][4u * i]) = v4u{0u, 0u, 0u, 0u};
     }
+    if (a.scales_in != nullptr) return;
 
-    // ---- a1: bucket range ----------------------------------------------------------------------
-    // WPB == 1: the chunk holds nbc = CH / bucket whole buckets; a bucket is `seg_lanes` lanes of one
-    // row (bucket <= 256) or `rpb` whole rows (bucket >= 256).  WPB > 1: the chunk is part of one bucket.
-    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 5
-    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);                    // buckets per chunk
-    const uint32_t seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
-    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);   // rows per bucket
+    // a1: bucket range
+    float m[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        m[j] = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
+    }
+    // fold the rows of one bucket into its first row
+#pragma unroll
+    for (int step = 1; step < R; step <<= 1) {
+        if (rpb > (uint32_t)step) {
+#pragma unroll
+            for (int j = 0; j + step < R; j += 2 * step) m[j] = fmaxf(m[j], m[j + step]);
+        }
+    }
+    // reduce across the lanes of the bucket; the first lane of each bucket publishes the result
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        if (((uint32_t)j & (rpb - 1u)) == 0u) {
+            const float r = segment_max(m[j], seg_lanes, lane);
+            if ((lane & (seg_lanes - 1u)) == 0u) sm.smax[wave][slot[j]] = r;
+        }
+    }
+    if (WPB > 1 && lane == 0u) sm.wave_max[wave] = sm.smax[wave][0];   // buckets spanning WPB waves
+}
+
+// ---- phase 2: scales, grid position, stochastic rounding, packing, store -------------------------
+template <int R, int WPB, bool FULL>
+__device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
+                                                  uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
+                                                  uint64_t kb_first, const float4 (&x)[R], WaveShared<R>& sm) {
+    const uint32_t b = a.bits;
+    const uint32_t shift = (uint32_t)a.bucket_shift;
     const float Lf = (float)((1u << b) - 1u);
     const float halfL = 0.5f * Lf;
-    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);    // global index of the chunk's first bucket
-    uint32_t slot[R];                                                      // bucket (chunk-local) of row j's quad
-#pragma unroll
-    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> shift);
 
-    if (a.scales_in == nullptr) {
-        float m[R];
+    if (WPB > 1 && a.scales_in == nullptr && lane == 0u) {
+        const uint32_t w0 = wave & ~(uint32_t)(WPB - 1);
+        float r = sm.wave_max[w0];
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            m[j] = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
-        }
-        // fold the rows of one bucket into its first row
-#pragma unroll
-        for (int step = 1; step < R; step <<= 1) {
-            if (rpb > (uint32_t)step) {
-#pragma unroll
-                for (int j = 0; j + step < R; j += 2 * step) m[j] = fmaxf(m[j], m[j + step]);
-            }
-        }
-        // reduce across the lanes of the bucket; the first lane of each bucket publishes the result
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            if (((uint32_t)j & (rpb - 1u)) == 0u) {
-                const float r = segment_max(m[j], seg_lanes, lane);
-                if ((lane & (seg_lanes - 1u)) == 0u) sm.smax[wave][slot[j]] = r;
-            }
-        }
+        for (int t = 1; t < WPB; ++t) r = fmaxf(r, sm.wave_max[w0 + t]);
+        sm.smax[wave][0] = r;
     }
-    if (WPB > 1) {
-        // buckets spanning WPB waves: share the chunk maxima
-        if (a.scales_in == nullptr && lane == 0u) sm.wave_max[wave] = sm.smax[wave][0];
-        __syncthreads();
-        if (a.scales_in == nullptr && lane == 0u) {
-            const uint32_t w0 = wave & ~(uint32_t)(WPB - 1);
-            float r = sm.wave_max[w0];
-#pragma unroll
-            for (int t = 1; t < WPB; ++t) r = fmaxf(r, sm.wave_max[w0 + t]);
-            sm.smax[wave][0] = r;
-        }
-    }
-    if (!active) return;
-
     // one lane per bucket: floor, store the scale, divide once
     if (lane < nbc) {
-        const bool exists = WPB > 1 ? true : ((lane << shift) < count);    // bucket starts inside the vector
+        const bool exists = WPB > 1 ? true : ((lane << shift) < count);   // bucket starts inside the vector
         float s = 0.0f;
         if (exists) {
             if (a.scales_in != nullptr) {
@@ -217,7 +200,6 @@ __global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeA
         sm.ainv[wave][lane] = (s > 0.0f) ? halfL / s : 0.0f;   // IEEE-correct fp32 division, once per bucket
     }
 
-    // ---- a2..a4: grid position, stochastic rounding, packing -----------------------------------
     const uint32_t odd = lane & 1u;
     const uint64_t group0 = (a.elem_base + cb) >> 3;           // both multiples of 8
     const uint32_t cell_bit = 4u * b * (lane & 7u);            // this lane's bit offset in its 32-element cell
@@ -229,15 +211,15 @@ __global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeA
     for (int jp = 0; jp < R; jp += 2) {
         // One Philox call covers 8 consecutive elements = the quads of an even/odd lane pair.  The
         // even lane draws for row jp, the odd lane for row jp + 1; each then takes the half it
-        // needs from its partner (a select whose other input comes through a DPP lane swap).
+        // needs from its partner.  The swaps run with every lane active (a lane swap under a
+        // divergent branch would read switched-off partners); the selects that follow keep the
+        // half each lane needs.
         const uint32_t my_row = jp + odd;
         const uint64_t grp = group0 + (uint64_t)((my_row * 64u + lane) >> 1);
         uint32_t o[4];
         philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
-        // the swaps run with every lane active (a lane swap under a divergent branch would read
-        // switched-off partners); the selects that follow keep the half each lane needs
-        const uint32_t p0 = dpp_u32<kDppQuadSwap1>(o[0]), p1 = dpp_u32<kDppQuadSwap1>(o[1]);
-        const uint32_t p2 = dpp_u32<kDppQuadSwap1>(o[2]), p3 = dpp_u32<kDppQuadSwap1>(o[3]);
+        const uint32_t p0 = swap_adjacent(o[0]), p1 = swap_adjacent(o[1]);
+        const uint32_t p2 = swap_adjacent(o[2]), p3 = swap_adjacent(o[3]);
         const uint32_t rw[2][2] = {{odd ? p2 : o[0], odd ? p3 : o[1]},    // row jp: the even lane's call
                                    {odd ? o[2] : p0, odd ? o[3] : p1}};   // row jp+1: the odd lane's call
 #pragma unroll
@@ -250,14 +232,14 @@ __global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeA
             uint32_t k1 = round_code(x[j].y, ainv, halfL, Lf, rw[t][0] >> 16);
             uint32_t k2 = round_code(x[j].z, ainv, halfL, Lf, rw[t][1] & 0xFFFFu);
             uint32_t k3 = round_code(x[j].w, ainv, halfL, Lf, rw[t][1] >> 16);
-            if (!full) {   // elements past the end contribute zero bits
+            if (!FULL) {   // elements past the end contribute zero bits
                 if (el + 0u >= count) k0 = 0u;
                 if (el + 1u >= count) k1 = 0u;
                 if (el + 2u >= count) k2 = 0u;
                 if (el + 3u >= count) k3 = 0u;
             }
-            const uint32_t v = k0 | (k1 << b) | (k2 << (2u * b)) | (k3 << (3u * b));
-            if (full || el < count) {
+            const uint32_t v = (((((k3 << b) | k2) << b) | k1) << b) | k0;   // three shift-or steps
+            if (FULL || el < count) {
                 const uint32_t w0 = (ql >> 3) * b + word_in_cell;
                 atomicOr(&sm.words[wave][w0], v << sh);
                 if (straddle) atomicOr(&sm.words[wave][w0 + 1u], v >> (32u - sh));
@@ -265,15 +247,56 @@ __global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeA
         }
     }
 
-    // ---- store the chunk's words ----------------------------------------------------------------
+    // store the chunk's words
     uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
-    if (full && (reinterpret_cast<uintptr_t>(a.packed) & 15u) == 0u) {
+    if (FULL && (reinterpret_cast<uintptr_t>(a.packed) & 15u) == 0u) {
         for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
             const v4u w = *reinterpret_cast<const v4u*>(&sm.words[wave][4u * i]);
             __builtin_nontemporal_store(w, reinterpret_cast<v4u*>(out) + i);
         }
     } else {
+        const uint32_t nwords = (count * b + 31u) >> 5;
         for (uint32_t i = lane; i < nwords; i += 64u) out[i] = sm.words[wave][i];
+    }
+}
+
+// R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; 2, 4: bucket = WPB*CH)
+template <int R, int WPB>
+__global__ __launch_bounds__(kThreads) void quantize_wave_kernel(const QuantizeArgs a) {
+    constexpr uint32_t CH = 256u * R;
+    __shared__ WaveShared<R> sm;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint64_t chunk = (uint64_t)blockIdx.x * kWaves + wave;
+    const uint64_t cb = chunk * CH;                 // first element of the chunk
+    const bool active = cb < a.n;                   // waves past the end only keep the barrier company
+    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
+    const bool full = count == CH;
+
+    // WPB == 1: the chunk holds nbc = CH / bucket whole buckets; a bucket is `seg_lanes` lanes of one
+    // row (bucket <= 256) or `rpb` whole rows (bucket >= 256).  WPB > 1: the chunk is part of one bucket.
+    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 5
+    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);                    // buckets per chunk
+    const uint32_t seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
+    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);   // rows per bucket
+    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);    // global index of the chunk's first bucket
+    uint32_t slot[R];                                                      // bucket (chunk-local) of row j's quad
+#pragma unroll
+    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> shift);
+
+    float4 x[R];
+    if (full) {
+        load_and_reduce<R, WPB, true>(a, a.grad + cb, count, lane, wave, slot, seg_lanes, rpb, x, sm);
+    } else {
+        load_and_reduce<R, WPB, false>(a, a.grad + cb, count, lane, wave, slot, seg_lanes, rpb, x, sm);
+    }
+    if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
+    if (!active) return;
+    if (full) {
+        quantize_and_pack<R, WPB, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm);
+    } else {
+        quantize_and_pack<R, WPB, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm);
     }
 }
 
