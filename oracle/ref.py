@@ -16,7 +16,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # MQGRAD_ORACLE_LIB: load another build of the oracle (used to check that planted mistakes fail the pins)
+        path = os.environ.get("MQGRAD_ORACLE_LIB") or _build.build(force=False)
         L = C.CDLL(path)
         u8p, u32p, f32p, f64p = (C.POINTER(C.c_uint8), C.POINTER(C.c_uint32),
                                  C.POINTER(C.c_float), C.POINTER(C.c_double))

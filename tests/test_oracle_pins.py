@@ -380,3 +380,65 @@ def test_quantized_sgd_converges_at_8_bits_and_stalls_at_1_bit():
         final[bits] = float(np.abs(p - target).max())
     assert final[8] < 1e-6
     assert final[1] > 100 * final[8]
+
+
+# ---- pins added after planting mistakes in a copy of the oracle ---------------------------------
+
+def test_grid_position_is_a_single_rounding():
+    # inputs for which rounding x*a first and then adding L/2 lands on a different fp32 than the
+    # fused multiply-add: the count of up-rounding uniforms follows the fused value
+    cases = [(0.5647523999214172, 0.6737864017486572, 8), (-0.36927440762519836, 0.5261039137840271, 7),
+             (-0.475243479013443, 0.9990268349647522, 7), (0.08698460459709167, 0.09389900416135788, 7)]
+    for x, s, bits in cases:
+        x32, s32 = np.float32(x), np.float32(s)
+        assert float(x32) == x and float(s32) == s
+        L = (1 << bits) - 1
+        a = f32_round(Fraction(L, 2) / Fraction(s))
+        fused = f32_round(Fraction(x) * a + Fraction(L, 2))
+        split = f32_round(f32_round(Fraction(x) * a) + Fraction(L, 2))
+        assert fused != split
+        lo = fused.numerator // fused.denominator
+        F = (fused - lo) * 65536
+        expect_up = 0 if F <= Fraction(1, 2) else min(65536, math.ceil(F - Fraction(1, 2)))
+        codes = np.array([ref.round_code(x32, s32, bits, h) for h in range(0, 65536)])
+        assert int((codes == lo + 1).sum()) == expect_up and set(np.unique(codes)) <= {lo, lo + 1}
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_values_beyond_the_scale_clamp_to_the_end_codes(bits):
+    L = (1 << bits) - 1
+    s = np.float32(0.37)
+    for h in (0, 1, 32767, 65535):
+        assert ref.round_code(2 * s, s, bits, h) == L
+        assert ref.round_code(-2 * s, s, bits, h) == 0
+        assert ref.round_code(np.float32(1e30), s, bits, h) == L
+        assert ref.round_code(np.float32(-1e30), s, bits, h) == 0
+    # and where fl((L/2)/s) * s exceeds L/2 the end elements themselves need the clamp
+    found = 0
+    for t in range(1, 4000):
+        sc = np.float32(0.001 * t + 1e-4)
+        a = f32_round(Fraction(L, 2) / Fraction(float(sc)))
+        if a * Fraction(float(sc)) > Fraction(L, 2):
+            found += 1
+            for h in (0, 65535):
+                assert ref.round_code(-sc, sc, bits, h) == 0 and ref.round_code(sc, sc, bits, h) == L
+        if found >= 20:
+            break
+    assert found >= 1
+
+
+def test_any_range_can_be_quantized_in_isolation():
+    # the uniform of element i depends on elem_base + i only: quantizing a bucket-aligned tail with
+    # elem_base = its first index reproduces the codes of the whole vector
+    rng = np.random.default_rng(12)
+    n, bucket = 4096 + 200, 256
+    g = rng.normal(0, 0.01, n).astype(np.float32)
+    for bits in (1, 3, 8):
+        pk, sc = ref.quantize(g, bits, bucket, 99, iteration=4, worker=6, elem_base=1 << 33)
+        whole = ref.unpack(pk, n, bits)
+        for lo in (256, 1024, 4096):
+            pk2, sc2 = ref.quantize(g[lo:], bits, bucket, 99, iteration=4, worker=6, elem_base=(1 << 33) + lo)
+            assert np.array_equal(sc2, sc[lo // bucket:])
+            assert np.array_equal(ref.unpack(pk2, n - lo, bits), whole[lo:])
+        pk3, _ = ref.quantize(g, bits, bucket, 99, iteration=4, worker=6, elem_base=0)
+        assert not np.array_equal(pk3, pk)
