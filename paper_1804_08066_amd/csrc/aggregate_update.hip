@@ -22,6 +22,7 @@
 // them back with v_readlane -- no LDS, no barrier.  Any other bucket size: a table in LDS, one
 // barrier.
 
+#include "decode.h"
 #include "kernels.h"
 
 #ifndef MQG_AGG_ROWS_R
@@ -33,7 +34,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kChunk = 8;   // workers whose code loads are in flight together
-constexpr int kDppWaveShl1 = 0x130;   // DPP wave_shl:1: lane i reads lane i + 1 (lane 63 keeps its old value)
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -95,88 +95,8 @@ __device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t ti
     }
 }
 
-// Where the codes of the lane's R quads sit in every worker's stream (tile-local word indices,
-// clamped to the last word of the stream so that quads past the end still read valid memory).
-template <int R>
-struct CodeWindows {
-    uint32_t word[R];    // first word
-    uint32_t sh[R];      // bit offset of the first code inside `word`
-    uint64_t tile_word;  // first word of the tile in the stream
-};
-
-template <int R>
-__device__ __forceinline__ CodeWindows<R> code_windows(uint64_t n, uint64_t tile_base, uint32_t b) {
-    CodeWindows<R> cw;
-    cw.tile_word = (tile_base >> 5) * b;   // tile_base is a multiple of 32
-    const uint64_t stream_words = (n >> 5) * b + ((((n & 31u) * b) + 31u) >> 5);
-    const uint64_t room = stream_words - cw.tile_word;   // >= 1
-    const uint32_t last_word = room - 1u > 0x3FFFFFFFull ? 0x3FFFFFFFu : (uint32_t)(room - 1u);
-#pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const uint32_t ql = j * kThreads + threadIdx.x;
-        const uint32_t bit = 4u * b * ql;
-        uint32_t word = bit >> 5, sh = bit & 31u;
-        if (word > last_word) {   // quad entirely past the end
-            word = last_word;
-            sh = 0u;
-        }
-        cw.word[j] = word;
-        cw.sh[j] = sh;
-    }
-    return cw;
-}
-
-template <int R>
-struct CodeRegs {
-    uint32_t lo[kChunk][R];
-};
-
-// a5 (fetch): code words of workers [w0, w0 + kChunk); surplus slots reload the last worker.
-template <int R>
-__device__ __forceinline__ void fetch_codes(const AggregateArgs& a, uint32_t w0, const CodeWindows<R>& cw,
-                                            CodeRegs<R>& c) {
-#pragma unroll
-    for (int t = 0; t < kChunk; ++t) {
-        const uint32_t w = (w0 + t < a.W) ? w0 + t : a.W - 1u;
-        const uint32_t* __restrict__ src = a.packed[w] + cw.tile_word;
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            c.lo[t][j] = __builtin_nontemporal_load(src + cw.word[j]);
-        }
-    }
-}
-
-// a5 (decode) + a6: one worker's 4 codes of one quad, de-quantized with step d and accumulated.
-template <bool STRADDLE>
-__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32_t b, int negL,
-                                                float d, float4& acc) {
-    uint32_t v, o;
-    if (STRADDLE) {
-        // A quad that spills over its first word continues in the first word of the next lane (that
-        // lane's quad starts where this one ends), so the second word comes through a one-lane DPP
-        // shift instead of a second load.  A wave's 64 quads are 8*bits whole words, so lane 63
-        // never spills and what it reads here is never used.
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, kDppWaveShl1, 0xF, 0xF, false);
-        v = __builtin_amdgcn_alignbit(hi, lo, sh);   // ({hi,lo} >> sh)[31:0]
-        o = 0u;
-    } else {
-        v = lo;
-        o = sh;
-    }
-    const int k0 = (int)__builtin_amdgcn_ubfe(v, o, b);
-    const int k1 = (int)__builtin_amdgcn_ubfe(v, o + b, b);
-    const int k2 = (int)__builtin_amdgcn_ubfe(v, o + 2u * b, b);
-    const int k3 = (int)__builtin_amdgcn_ubfe(v, o + 3u * b, b);
-    acc.x = __builtin_fmaf((float)(2 * k0 + negL), d, acc.x);
-    acc.y = __builtin_fmaf((float)(2 * k1 + negL), d, acc.y);
-    acc.z = __builtin_fmaf((float)(2 * k2 + negL), d, acc.z);
-    acc.w = __builtin_fmaf((float)(2 * k3 + negL), d, acc.w);
-}
-
-__device__ __forceinline__ float readlane_f32(float v, uint32_t lane) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), (int)lane));
-}
-
+using decode::accumulate_quad;
+using decode::readlane_f32;
 // ---- buckets that are multiples of 128: bucket steps live in the wave ---------------------------
 // NBR = buckets a 256-element row can touch: 1 when the bucket is a multiple of 256, else 2.
 template <int R, int NBR, bool STRADDLE, bool ALIGNED>
@@ -199,9 +119,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     const uint32_t b = a.bits;
     const int negL = -(int)((1u << b) - 1u);
     const float Lf = (float)((1u << b) - 1u);
-    const CodeWindows<R> cw = code_windows<R>(a.n, tile_base, b);
-    CodeRegs<R> c;
-    fetch_codes<R>(a, 0u, cw, c);
+    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
+    decode::CodeRegs<R, kChunk> c;
+    decode::fetch_codes<R, kChunk>(a.packed, a.W, 0u, cw, c);
 
     // bucket steps of this wave's rows: lane w divides worker w's scale(s)
     const uint64_t nb_total = (a.n + a.bucket - 1u) / a.bucket;
@@ -228,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) fetch_codes<R>(a, w0, cw, c);
+        if (w0 > 0) decode::fetch_codes<R, kChunk>(a.packed, a.W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {
@@ -267,9 +187,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const Ag
     const uint32_t b = a.bits;
     const int negL = -(int)((1u << b) - 1u);
     const float Lf = (float)((1u << b) - 1u);
-    const CodeWindows<R> cw = code_windows<R>(a.n, tile_base, b);
-    CodeRegs<R> c;
-    fetch_codes<R>(a, 0u, cw, c);   // in flight while the bucket steps are computed
+    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
+    decode::CodeRegs<R, kChunk> c;
+    decode::fetch_codes<R, kChunk>(a.packed, a.W, 0u, cw, c);   // in flight while the bucket steps are computed
 
     const uint64_t kb0 = tile_base / a.bucket;
     const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
@@ -302,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const Ag
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) fetch_codes<R>(a, w0, cw, c);
+        if (w0 > 0) decode::fetch_codes<R, kChunk>(a.packed, a.W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {

@@ -1,0 +1,105 @@
+// Unpack + de-quantize + accumulate (steps a5, a6 of the hot path), shared by the kernels that read
+// packed code streams: the server's aggregate_update and its re-quantizing variant.
+//
+// A lane owns R quads of 4 consecutive elements; quad q of a tile starts at stream bit 4*bits*q of
+// the tile's first word.  Its 4 codes lie inside one 32-bit word when bits divides 32 and spill
+// into the next word otherwise -- and that next word is the first word of the next lane's quad.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mqgrad.h"
+
+namespace mqg {
+namespace decode {
+
+constexpr int kDppWaveShl1 = 0x130;   // DPP wave_shl:1: lane i reads lane i + 1
+
+// Where the codes of the lane's R quads sit in every worker's stream (tile-local word indices,
+// clamped to the last word of the stream so that quads past the end still read valid memory).
+template <int R>
+struct CodeWindows {
+    uint32_t word[R];    // first word
+    uint32_t sh[R];      // bit offset of the first code inside `word`
+    uint64_t tile_word;  // first word of the tile in the stream
+};
+
+// ROW: quads per row of the tile (the lanes that load one row); `idx`: this lane's index in a row.
+// Row j of the lane is quad j*ROW + idx of the tile that starts at element `tile_base`.
+template <int R, int ROW>
+__device__ __forceinline__ CodeWindows<R> code_windows(uint64_t n, uint64_t tile_base, uint32_t b, uint32_t idx) {
+    CodeWindows<R> cw;
+    cw.tile_word = (tile_base >> 5) * b;   // tile_base is a multiple of 32
+    const uint64_t stream_words = (n >> 5) * b + ((((n & 31u) * b) + 31u) >> 5);
+    const uint64_t room = stream_words - cw.tile_word;   // >= 1 whenever tile_base < n
+    const uint32_t last_word = room - 1u > 0x3FFFFFFFull ? 0x3FFFFFFFu : (uint32_t)(room - 1u);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t ql = j * ROW + idx;
+        const uint32_t bit = 4u * b * ql;
+        uint32_t word = bit >> 5, sh = bit & 31u;
+        if (word > last_word) {   // quad entirely past the end
+            word = last_word;
+            sh = 0u;
+        }
+        cw.word[j] = word;
+        cw.sh[j] = sh;
+    }
+    return cw;
+}
+
+template <int R, int CH>
+struct CodeRegs {
+    uint32_t lo[CH][R];
+};
+
+// Fetch the first code word of each of the lane's quads for workers [w0, min(w0 + CH, W)): one
+// aligned dword load per worker and quad, all issued before any is consumed.  Adjacent lanes read
+// the same or adjacent words, so a wave's request is one contiguous run of 32*bits bytes.
+template <int R, int CH>
+__device__ __forceinline__ void fetch_codes(const uint32_t* const (&packed)[MQG_MAX_WORKERS], uint32_t W,
+                                            uint32_t w0, const CodeWindows<R>& cw, CodeRegs<R, CH>& c) {
+#pragma unroll
+    for (int t = 0; t < CH; ++t) {
+        if (w0 + t < W) {
+            const uint32_t* __restrict__ src = packed[w0 + t] + cw.tile_word;
+#pragma unroll
+            for (int j = 0; j < R; ++j) c.lo[t][j] = __builtin_nontemporal_load(src + cw.word[j]);
+        }
+    }
+}
+
+// One worker's 4 codes of one quad, de-quantized with step d and accumulated:
+// acc <- fma((float)(2c - L), d, acc), the ordered chain of the server's sum.
+template <bool STRADDLE>
+__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32_t b, int negL,
+                                                float d, float4& acc) {
+    uint32_t v, o;
+    if (STRADDLE) {
+        // A quad that spills over its first word continues in the first word of the next lane (that
+        // lane's quad starts where this one ends), so the second word comes through a one-lane DPP
+        // shift instead of a second load.  A wave's 64 quads are 8*bits whole words, so lane 63
+        // never spills and what it reads here is never used.  Must run with all lanes active.
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, kDppWaveShl1, 0xF, 0xF, false);
+        v = __builtin_amdgcn_alignbit(hi, lo, sh);   // ({hi,lo} >> sh)[31:0]
+        o = 0u;
+    } else {
+        v = lo;
+        o = sh;
+    }
+    const int k0 = (int)__builtin_amdgcn_ubfe(v, o, b);
+    const int k1 = (int)__builtin_amdgcn_ubfe(v, o + b, b);
+    const int k2 = (int)__builtin_amdgcn_ubfe(v, o + 2u * b, b);
+    const int k3 = (int)__builtin_amdgcn_ubfe(v, o + 3u * b, b);
+    acc.x = __builtin_fmaf((float)(2 * k0 + negL), d, acc.x);
+    acc.y = __builtin_fmaf((float)(2 * k1 + negL), d, acc.y);
+    acc.z = __builtin_fmaf((float)(2 * k2 + negL), d, acc.z);
+    acc.w = __builtin_fmaf((float)(2 * k3 + negL), d, acc.w);
+}
+
+__device__ __forceinline__ float readlane_f32(float v, uint32_t lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), (int)lane));
+}
+
+}  // namespace decode
+}  // namespace mqg
