@@ -248,6 +248,62 @@ void orc_aggregate_update(const uint32_t* const* packed, const float* const* sca
     }
 }
 
+// ---- the paper's full exchange: the server sends the quantized MEAN back (Algorithm 1) ----------
+// ReceiveQGThenSendQG: g^m <- sum_p De-quantize(gbar_p) / P;  gbar^m <- Quantize(g^m, K);  send.
+// WorkerIterate:       g^m <- De-quantize(gbar^m);  w <- w - eta g^m.
+//
+// Reading: the division by P is applied to the bucket RANGE, not to every element.  A range-linear
+// grid is scale-equivariant: the codes of the sum on the grid over [-S, S], S = max|sum|, are the
+// codes of the mean on the grid over [-S/P, S/P].  So the server quantizes the fp32 sum (ordered fma
+// chain, as in orc_aggregate_update) with S, and stores S / P as the bucket scale.
+
+void orc_aggregate_sum(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                       uint64_t n, uint32_t bits, uint32_t bucket, float* sum_out) {
+    const int L = (int)((1u << bits) - 1u);
+    for (uint64_t i = 0; i < n; ++i) {
+        float acc = 0.0f;
+        for (uint32_t w = 0; w < W; ++w) {
+            uint32_t k = 0;
+            for (uint32_t t = 0; t < bits; ++t) {
+                const uint64_t pos = i * bits + t;
+                k |= ((packed[w][pos >> 5] >> (pos & 31u)) & 1u) << t;
+            }
+            const float d = scales[w][i / bucket] / (float)L;
+            acc = std::fmaf((float)(2 * (int)k - L), d, acc);
+        }
+        sum_out[i] = acc;
+    }
+}
+
+// sum_tmp: n floats of scratch; codes_tmp: n bytes of scratch.
+void orc_aggregate_requantize(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                              uint64_t n, uint32_t bits, uint32_t bucket,
+                              uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                              uint32_t* packed_out, float* scales_out, float* sum_tmp, uint8_t* codes_tmp) {
+    orc_aggregate_sum(packed, scales, W, n, bits, bucket, sum_tmp);
+    orc_bucket_scales(sum_tmp, n, bucket, 0, scales_out);                       // S = max|sum| per bucket
+    orc_quantize_codes(sum_tmp, n, bits, bucket, seed, iteration, worker, elem_base, scales_out, codes_tmp);
+    orc_pack(codes_tmp, n, bits, packed_out);
+    const uint64_t nb = orc_num_buckets(n, bucket);
+    for (uint64_t k = 0; k < nb; ++k) scales_out[k] = scales_out[k] / (float)W;   // range of the mean
+}
+
+// Worker side of the exchange: w <- w - eta * De-quantize(gbar).
+void orc_dequantize_update(const uint32_t* packed, const float* scales, uint64_t n, uint32_t bits,
+                           uint32_t bucket, float lr, float* params) {
+    const int L = (int)((1u << bits) - 1u);
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t k = 0;
+        for (uint32_t t = 0; t < bits; ++t) {
+            const uint64_t pos = i * bits + t;
+            k |= ((packed[pos >> 5] >> (pos & 31u)) & 1u) << t;
+        }
+        const float d = scales[i / bucket] / (float)L;
+        const float v = (float)(2 * (int)k - L) * d;
+        params[i] = std::fmaf(-lr, v, params[i]);
+    }
+}
+
 // The same server step evaluated from its plain definition in fp64 (no
 // ordering, no fp32 rounding until the end): used to pin the fp32 chain.
 void orc_aggregate_update_f64(const uint32_t* const* packed, const float* const* scales, uint32_t W,

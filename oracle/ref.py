@@ -54,6 +54,13 @@ def lib():
         L.orc_aggregate_update_f64.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32,
                                                C.c_uint32, C.c_double, f32p, f64p]
         L.orc_aggregate_update_f64.restype = None
+        L.orc_aggregate_sum.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, f32p]
+        L.orc_aggregate_sum.restype = None
+        L.orc_aggregate_requantize.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32,
+                                               C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, u32p, f32p, f32p, u8p]
+        L.orc_aggregate_requantize.restype = None
+        L.orc_dequantize_update.argtypes = [u32p, f32p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_float, f32p]
+        L.orc_dequantize_update.restype = None
         _lib = L
     return _lib
 
@@ -190,4 +197,38 @@ def aggregate_update_f64(packed_list, scales_list, n, bits, bucket, lr, params):
     out = np.empty(n, dtype=np.float64)
     lib().orc_aggregate_update_f64(pa, sa, W, n, bits, bucket, float(lr), _p(pin, C.c_float),
                                    _p(out, C.c_double))
+    return out
+
+
+def aggregate_sum(packed_list, scales_list, n, bits, bucket):
+    """fp32 sum over workers of the de-quantized gradients (ordered fma chain)."""
+    W = len(packed_list)
+    pk, sc, pa, sa = _ptr_arrays(packed_list, scales_list)
+    out = np.empty(n, dtype=np.float32)
+    lib().orc_aggregate_sum(pa, sa, W, n, bits, bucket, _p(out, C.c_float))
+    return out
+
+
+def aggregate_requantize(packed_list, scales_list, n, bits, bucket, seed, iteration=0, worker=0, elem_base=0):
+    """Server side of the full exchange: quantized mean.  Returns (packed uint32[words], scales float32[nb])."""
+    W = len(packed_list)
+    pk, sc, pa, sa = _ptr_arrays(packed_list, scales_list)
+    packed = np.empty(packed_words(n, bits), dtype=np.uint32)
+    scales = np.empty(num_buckets(n, bucket), dtype=np.float32)
+    tmp_f = np.empty(max(n, 1), dtype=np.float32)
+    tmp_c = np.empty(max(n, 1), dtype=np.uint8)
+    lib().orc_aggregate_requantize(pa, sa, W, n, bits, bucket, seed, iteration, worker, elem_base,
+                                   _p(packed, C.c_uint32), _p(scales, C.c_float), _p(tmp_f, C.c_float),
+                                   _p(tmp_c, C.c_uint8))
+    return packed, scales
+
+
+def dequantize_update(packed, scales, n, bits, bucket, lr, params):
+    """Worker side of the full exchange: returns params - lr * dequantize(packed, scales)."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    scales = _f32(scales)
+    out = np.array(params, dtype=np.float32, copy=True).reshape(-1)
+    assert out.size == n
+    lib().orc_dequantize_update(_p(packed, C.c_uint32), _p(scales, C.c_float), n, bits, bucket,
+                                float(np.float32(lr)), _p(out, C.c_float))
     return out

@@ -442,3 +442,77 @@ def test_any_range_can_be_quantized_in_isolation():
             assert np.array_equal(ref.unpack(pk2, n - lo, bits), whole[lo:])
         pk3, _ = ref.quantize(g, bits, bucket, 99, iteration=4, worker=6, elem_base=0)
         assert not np.array_equal(pk3, pk)
+
+
+# ---- the full exchange: server sends the quantized mean back (Algorithm 1) ----------------------
+
+def _workers(n, bits, bucket, W, seed=31):
+    rng = np.random.default_rng(seed)
+    gs = [rng.normal(0, 0.01 * (1 + w), n).astype(np.float32) for w in range(W)]
+    qs = [ref.quantize(g, bits, bucket, 7, iteration=2, worker=w) for w, g in enumerate(gs)]
+    return [q[0] for q in qs], [q[1] for q in qs]
+
+
+@pytest.mark.parametrize("bits", [1, 3, 4, 8])
+def test_aggregate_sum_matches_fp64_sum_of_dequantized(bits):
+    n, bucket, W = 3000, 96, 5
+    pk, sc = _workers(n, bits, bucket, W)
+    got = ref.aggregate_sum(pk, sc, n, bits, bucket).astype(np.float64)
+    deq = [ref.dequantize(pk[w], sc[w], n, bits, bucket).astype(np.float64) for w in range(W)]
+    want = sum(deq)
+    mag = sum(np.abs(d) for d in deq)
+    assert np.all(np.abs(got - want) <= (W + 1) * 2.0 ** -23 * mag)
+    assert np.array_equal(ref.aggregate_sum(pk[:1], sc[:1], n, bits, bucket), ref.dequantize(pk[0], sc[0], n, bits, bucket))
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_requantized_mean_is_within_one_step_of_the_mean(bits):
+    n, bucket, W = 5000, 512, 4
+    pk, sc = _workers(n, bits, bucket, W)
+    L = (1 << bits) - 1
+    mean = sum(ref.dequantize(pk[w], sc[w], n, bits, bucket).astype(np.float64) for w in range(W)) / W
+    for seed in (0, 5):
+        pk_m, sc_m = ref.aggregate_requantize(pk, sc, n, bits, bucket, seed, iteration=3, worker=W)
+        # the stored range is max|sum| / W
+        s_sum = ref.bucket_scales(ref.aggregate_sum(pk, sc, n, bits, bucket), bucket)
+        assert np.array_equal(sc_m, s_sum / np.float32(W))
+        back = ref.dequantize(pk_m, sc_m, n, bits, bucket).astype(np.float64)
+        delta = 2 * np.repeat(sc_m, bucket)[:n].astype(np.float64) / L
+        assert np.all(np.abs(back - mean) < delta * (1 + 1e-5) + 1e-12)
+    # different seeds give different codes, same scales
+    a = ref.aggregate_requantize(pk, sc, n, bits, bucket, 0, 3, W)
+    b = ref.aggregate_requantize(pk, sc, n, bits, bucket, 1, 3, W)
+    assert np.array_equal(a[1], b[1]) and (bits == 8 or not np.array_equal(a[0], b[0]))
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_requantizing_one_worker_on_exact_levels_is_the_identity(bits):
+    # W = 1 and values on the grid of s = L * 2^e: the sum is exact, its range is s, every value sits on a level
+    L = (1 << bits) - 1
+    ks = (np.arange(256) * 7) % (L + 1)
+    ks[0], ks[1] = 0, L
+    g = ((2 * ks - L) * 2.0 ** -6).astype(np.float32)
+    pk, sc = ref.quantize(g, bits, 128, 3)
+    pk2, sc2 = ref.aggregate_requantize([pk], [sc], g.size, bits, 128, 99, 5, 1)
+    assert np.array_equal(pk2, pk) and np.array_equal(sc2, sc)
+
+
+def test_dequantize_update_special_cases_and_round_trip():
+    n, bits, bucket, W, lr = 4000, 5, 256, 3, 0.25
+    pk, sc = _workers(n, bits, bucket, W)
+    rng = np.random.default_rng(1)
+    p = rng.uniform(-0.05, 0.05, n).astype(np.float32)
+    # params = 0, lr = 1: minus the de-quantized gradient; lr = 0: identity
+    assert np.array_equal(ref.dequantize_update(pk[0], sc[0], n, bits, bucket, 1.0, np.zeros(n, np.float32)),
+                          -ref.dequantize(pk[0], sc[0], n, bits, bucket))
+    assert ref.dequantize_update(pk[0], sc[0], n, bits, bucket, 0.0, p).tobytes() == p.tobytes()
+    # it is the W = 1 case of the server update
+    assert np.array_equal(ref.dequantize_update(pk[1], sc[1], n, bits, bucket, lr, p),
+                          ref.aggregate_update(pk[1:2], sc[1:2], n, bits, bucket, lr, p))
+    # exchange end to end: worker update with the re-quantized mean stays within lr * step of the direct update
+    pk_m, sc_m = ref.aggregate_requantize(pk, sc, n, bits, bucket, 4, 1, W)
+    via_exchange = ref.dequantize_update(pk_m, sc_m, n, bits, bucket, lr, p).astype(np.float64)
+    direct = ref.aggregate_update(pk, sc, n, bits, bucket, lr, p).astype(np.float64)
+    delta = 2 * np.repeat(sc_m, bucket)[:n].astype(np.float64) / ((1 << bits) - 1)
+    assert np.all(np.abs(via_exchange - direct) <= lr * delta * (1 + 1e-5) + 1e-9)
+    assert np.abs(via_exchange - direct).max() > 0
