@@ -124,6 +124,31 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
                                 uint64_t n, uint32_t bits, uint32_t bucket,
                                 float lr, float* params, void* stream);
 
+/* ---- the paper's full exchange (Algorithm 1): the server sends the quantized mean back ---------
+ *
+ * ReceiveQGThenSendQG:  g^m <- sum_p De-quantize(gbar_p) / P;  gbar^m <- Quantize(g^m, K);  send.
+ * WorkerIterate:        g^m <- De-quantize(gbar^m);  w <- w - eta g^m.
+ *
+ * mqg_aggregate_requantize is the server's half, fused: the W streams are unpacked, de-quantized and
+ * summed in worker order (the same fp32 fma chain as mqg_aggregate_update), and the sum is quantized
+ * with the same `bits` and `bucket` exactly as mqg_quantize would quantize it (max-abs range S per
+ * bucket, stochastic rounding with the stream selected by seed / iteration / worker / elem_base --
+ * give the server a `worker` id of its own, e.g. W).  The division by W is applied to the stored
+ * range: scales_out holds S / W, so that De-quantize(packed_out, scales_out) is the mean.  No fp32
+ * copy of the sum or the mean is ever written to memory.
+ *   packed, scales  HOST arrays of W device pointers, as for mqg_aggregate_update.
+ *   packed_out      device, mqg_packed_words(n, bits) words;  scales_out: mqg_num_buckets(n, bucket) floats.
+ * Errors as for mqg_quantize and mqg_aggregate_update. */
+mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                    uint64_t n, uint32_t bits, uint32_t bucket,
+                                    uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                                    uint32_t* packed_out, float* scales_out, void* stream);
+
+/* The worker's half: params[i] <- fma(-lr, (2 c_i - L) * (s_k / L), params[i]), i.e. w <- w - eta *
+ * De-quantize(gbar).  Same as mqg_aggregate_update with one worker. */
+mqg_status mqg_dequantize_update(const uint32_t* packed, const float* scales, uint64_t n, uint32_t bits,
+                                 uint32_t bucket, float lr, float* params, void* stream);
+
 /* ---- host-side agent that chooses K (Section 3.3, Algorithm 2).  No GPU involved. ---------- */
 
 typedef struct mqg_mdp mqg_mdp;

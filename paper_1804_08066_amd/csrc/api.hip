@@ -133,4 +133,52 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 
+mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                    uint64_t n, uint32_t bits, uint32_t bucket,
+                                    uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                                    uint32_t* packed_out, float* scales_out, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if ((elem_base & 7u) != 0u) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (packed == nullptr || scales == nullptr || packed_out == nullptr || scales_out == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4) || elem_base > UINT64_MAX - n) return MQG_EINVAL;
+    if (misaligned4(packed_out) || misaligned4(scales_out)) return MQG_EALIGN;
+    mqg::RequantArgs ra;
+    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
+        ra.packed[w] = nullptr;
+        ra.scales[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || misaligned4(scales[w])) return MQG_EALIGN;
+        ra.packed[w] = packed[w];
+        ra.scales[w] = scales[w];
+    }
+    ra.W = W;
+    ra.q.grad = nullptr;
+    ra.q.n = n;
+    ra.q.bits = bits;
+    ra.q.bucket = bucket;
+    ra.q.bucket_shift = log2_if_pow2(bucket);
+    ra.q.scale_mode = MQG_SCALE_MAXABS;
+    ra.q.key0 = (uint32_t)seed;
+    ra.q.key1 = (uint32_t)(seed >> 32);
+    ra.q.iteration = iteration;
+    ra.q.worker = worker;
+    ra.q.elem_base = elem_base;
+    ra.q.scales_in = nullptr;
+    ra.q.packed = packed_out;
+    ra.q.scales = scales_out;
+    const hipError_t err = mqg::launch_requantize(ra, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_dequantize_update(const uint32_t* packed, const float* scales, uint64_t n, uint32_t bits,
+                                 uint32_t bucket, float lr, float* params, void* stream) {
+    const uint32_t* pk[1] = {packed};
+    const float* sc[1] = {scales};
+    return mqg_aggregate_update(pk, sc, 1u, n, bits, bucket, lr, params, stream);
+}
+
 }  // extern "C"

@@ -1,0 +1,67 @@
+// Pieces of the quantizer (steps a2, a3 of the hot path) shared by the kernels that write packed
+// code streams: lane-exchange helpers, Philox4x32-10, and the stochastic rounding of one element.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mqg {
+namespace encode {
+
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+
+constexpr int kDppQuadSwap1 = 0xB1;       // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int kDppQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
+constexpr int kDppRowMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+// DPP reads of a switched-off lane return 0: call these with every lane of the wave active.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
+}
+
+// Philox4x32-10 (Salmon et al., SC'11).  Ten rounds of two 32x32->64 multiplies; the key is
+// bumped by the Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+    }
+    o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
+}
+
+// code of one element: floor(u) + [(h + 1/2) / 65536 < frac(u)].
+// The comparison is evaluated as  h < frac*65536 - 1/2 : the right-hand side is exact in fp32
+// whenever it is non-negative (frac*65536 < 2^16 has an ulp of at most 2^-8), and negative
+// otherwise, so both forms decide identically for every integer h in [0, 65535].
+__device__ __forceinline__ uint32_t round_code(float x, float ainv, float halfL, float Lf, uint32_t h16) {
+    float u = __builtin_fmaf(x, ainv, halfL);
+    u = __builtin_amdgcn_fmed3f(u, 0.0f, Lf);
+    const float fr = __builtin_amdgcn_fractf(u);
+    const float t = __builtin_fmaf(fr, 65536.0f, -0.5f);
+    const float hf = (float)h16;
+    return (uint32_t)u + ((hf < t) ? 1u : 0u);
+}
+
+}  // namespace encode
+}  // namespace mqg

@@ -34,7 +34,17 @@ struct AggregateArgs {
     float* params;
 };
 
+// Server side of the full exchange: quantize the sum over W workers' de-quantized gradients
+// (q.grad, q.scales_in unused; q.scale_mode max-abs); the stored bucket range is divided by W.
+struct RequantArgs {
+    QuantizeArgs q;
+    const uint32_t* packed[MQG_MAX_WORKERS];
+    const float* scales[MQG_MAX_WORKERS];
+    uint32_t W;
+};
+
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
+hipError_t launch_requantize(const RequantArgs& a, hipStream_t stream);
 bool quantize_wave_supported(const QuantizeArgs& a);          // quantize_wave.hip
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);

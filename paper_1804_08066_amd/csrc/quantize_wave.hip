@@ -19,6 +19,7 @@
 // moved off the vector ALU where possible: cross-lane exchange through LDS-pipe swizzles, per-bucket
 // values through small per-wave LDS tables, bit placement through LDS atomics.
 
+#include "encode.h"
 #include "kernels.h"
 
 namespace mqg {
@@ -26,28 +27,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
-constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
-constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
-constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
-
-constexpr int kDppQuadSwap1 = 0xB1;       // quad_perm [1,0,3,2]: lane ^ 1
-constexpr int kDppQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]: lane ^ 2
-constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
-constexpr int kDppRowMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
 constexpr int kSwizzleXor16 = 0x401F;     // bit-mode swizzle: and 0x1F, or 0, xor 0x10
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+using namespace encode;
 
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v) {
-    return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
-}
 __device__ __forceinline__ float swizzle_xor16_f32(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleXor16));
 }
@@ -70,38 +53,6 @@ __device__ __forceinline__ float segment_max(float m, uint32_t seg_lanes, uint32
     if (seg_lanes >= 32u) m = fmaxf(m, swizzle_xor16_f32(m));
     if (seg_lanes >= 64u) m = fmaxf(m, bpermute_xor32_f32(m, lane));
     return m;
-}
-
-// Philox4x32-10 (Salmon et al., SC'11).
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
-        const uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
-        c0 = n0;
-        c2 = n2;
-        k0 += kPhiloxW0;
-        k1 += kPhiloxW1;
-    }
-    o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
-}
-
-// code of one element: floor(u) + [(h + 1/2) / 65536 < frac(u)].
-// The comparison is evaluated as  h < frac*65536 - 1/2 : the right-hand side is exact in fp32
-// whenever it is non-negative (frac*65536 < 2^16 has an ulp of at most 2^-8), and negative
-// otherwise, so both forms decide identically for every integer h in [0, 65535].
-__device__ __forceinline__ uint32_t round_code(float x, float ainv, float halfL, float Lf, uint32_t h16) {
-    float u = __builtin_fmaf(x, ainv, halfL);
-    u = __builtin_amdgcn_fmed3f(u, 0.0f, Lf);
-    const float fr = __builtin_amdgcn_fractf(u);
-    const float t = __builtin_fmaf(fr, 65536.0f, -0.5f);
-    const float hf = (float)h16;
-    return (uint32_t)u + ((hf < t) ? 1u : 0u);
 }
 
 // LDS of one workgroup: everything is indexed by wave, so waves never touch each other's entries

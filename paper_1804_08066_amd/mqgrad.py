@@ -18,6 +18,7 @@ MQG_MAX_WORKERS = 64
 EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
+    "mqg_aggregate_requantize", "mqg_dequantize_update",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
 ]
@@ -62,6 +63,10 @@ def lib():
     L.mqg_quantize_with_scales.restype = C.c_int
     L.mqg_aggregate_update.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, vp]
     L.mqg_aggregate_update.restype = C.c_int
+    L.mqg_aggregate_requantize.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp]
+    L.mqg_aggregate_requantize.restype = C.c_int
+    L.mqg_dequantize_update.argtypes = [vp, vp, u64, u32, u32, f32, vp, vp]
+    L.mqg_dequantize_update.restype = C.c_int
     L.mqg_mdp_default_config.argtypes = [C.POINTER(MdpConfig)]
     L.mqg_mdp_default_config.restype = None
     L.mqg_mdp_create.argtypes = [C.POINTER(MdpConfig)]
@@ -164,6 +169,55 @@ def mqg_aggregate_update(packed, scales, n, bits, bucket, lr, params, stream=Non
     st = lib().mqg_aggregate_update(pa, sa, W, n, bits, bucket, lr, params.data_ptr(), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_update")
+    return params
+
+
+def _worker_arrays(packed, scales, n, bits, bucket):
+    W = len(packed)
+    if W != len(scales):
+        raise ValueError("packed and scales must have one entry per worker")
+    for p, s in zip(packed, scales):
+        _check(p, torch.int32, "packed[w]")
+        _check(s, torch.float32, "scales[w]")
+        if p.numel() < mqg_packed_words(n, bits) or s.numel() < mqg_num_buckets(n, bucket):
+            raise ValueError("a worker's buffers are too small for n")
+    pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    sa = (C.c_void_p * max(W, 1))(*[s.data_ptr() for s in scales])
+    return W, pa, sa
+
+
+def mqg_aggregate_requantize(packed, scales, n, bits, bucket, seed, iteration=0, worker=0, elem_base=0,
+                             packed_out=None, scales_out=None, stream=None):
+    """Server's half of the full exchange: quantized mean of the W workers' gradients.
+    Returns (packed int32[words], scales fp32[nb])."""
+    W, pa, sa = _worker_arrays(packed, scales, n, bits, bucket)
+    dev = packed[0].device if W else "cuda"
+    if packed_out is None or scales_out is None:
+        p, s = alloc_outputs(n, bits, bucket, dev)
+        packed_out = p if packed_out is None else packed_out
+        scales_out = s if scales_out is None else scales_out
+    _check(packed_out, torch.int32, "packed_out")
+    _check(scales_out, torch.float32, "scales_out")
+    if packed_out.numel() < mqg_packed_words(n, bits) or scales_out.numel() < mqg_num_buckets(n, bucket):
+        raise ValueError("output buffers too small")
+    st = lib().mqg_aggregate_requantize(pa, sa, W, n, bits, bucket, seed, iteration, worker, elem_base,
+                                        packed_out.data_ptr(), scales_out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_requantize")
+    return packed_out, scales_out
+
+
+def mqg_dequantize_update(packed, scales, n, bits, bucket, lr, params, stream=None):
+    """Worker's half of the full exchange: params <- params - lr * De-quantize(packed, scales)."""
+    _check(packed, torch.int32, "packed")
+    _check(scales, torch.float32, "scales")
+    _check(params, torch.float32, "params")
+    if params.numel() != n or packed.numel() < mqg_packed_words(n, bits) or scales.numel() < mqg_num_buckets(n, bucket):
+        raise ValueError("buffer sizes do not match n")
+    st = lib().mqg_dequantize_update(packed.data_ptr(), scales.data_ptr(), n, bits, bucket, lr,
+                                     params.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_dequantize_update")
     return params
 
 

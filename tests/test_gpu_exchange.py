@@ -1,0 +1,86 @@
+"""GPU parity for the paper's full exchange (Algorithm 1): the server re-quantizes the mean of the
+workers' gradients (mqg_aggregate_requantize), each worker de-quantizes it and updates its copy of
+the parameters (mqg_dequantize_update).  Oracle inputs are oracle outputs of generated gradients."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_1804_08066_amd import mqgrad, workloads
+from helpers import to_u32, ulp_distance
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def oracle_workers(n, bits, bucket, W, seed=0, it=1):
+    gs = [workloads.laplace(n, 1e-3 * (1 + w), 900 + 17 * seed + w, "cpu").numpy() for w in range(W)]
+    qs = [ref.quantize(g, bits, bucket, seed, it, w) for w, g in enumerate(gs)]
+    return [q[0] for q in qs], [q[1] for q in qs]
+
+
+def to_dev(pk, sc):
+    return ([torch.from_numpy(p.view(np.int32).copy()).to(DEV) for p in pk],
+            [torch.from_numpy(s.copy()).to(DEV) for s in sc])
+
+
+@pytest.mark.parametrize("bucket", [32, 96, 128, 512, 1024, 4096, 4128, 8192, 16384])
+def test_requantize_matches_oracle_all_bits(bucket):
+    for n in (1, 33, 5000, 40000 + 77):
+        for bits in range(1, 9):
+            for W in ((1, 3) if n < 40000 else (8,)):
+                pk, sc = oracle_workers(n, bits, bucket, W, seed=bits)
+                dpk, dsc = to_dev(pk, sc)
+                got_pk, got_sc = mqgrad.mqg_aggregate_requantize(dpk, dsc, n, bits, bucket, seed=77, iteration=4,
+                                                                 worker=W, elem_base=1024)
+                torch.cuda.synchronize()
+                want_pk, want_sc = ref.aggregate_requantize(pk, sc, n, bits, bucket, 77, 4, W, 1024)
+                label = "n=%d B=%d b=%d W=%d" % (n, bucket, bits, W)
+                assert np.array_equal(got_sc.cpu().numpy(), want_sc), label + " scales"
+                assert np.array_equal(to_u32(got_pk), want_pk), label + " codes"
+
+
+@pytest.mark.parametrize("W", [2, 9, 17, 64])
+def test_requantize_many_workers(W):
+    n, bucket = 20000 + 3, 512
+    for bits in (1, 3, 8):
+        pk, sc = oracle_workers(n, bits, bucket, W, seed=W)
+        dpk, dsc = to_dev(pk, sc)
+        got_pk, got_sc = mqgrad.mqg_aggregate_requantize(dpk, dsc, n, bits, bucket, seed=5, iteration=1, worker=W)
+        torch.cuda.synchronize()
+        want_pk, want_sc = ref.aggregate_requantize(pk, sc, n, bits, bucket, 5, 1, W, 0)
+        assert np.array_equal(got_sc.cpu().numpy(), want_sc) and np.array_equal(to_u32(got_pk), want_pk)
+
+
+def test_dequantize_update_matches_oracle():
+    for n, bucket in ((1, 32), (5000, 96), (100000 + 5, 1024), (70000, 16384)):
+        p0 = workloads.uniform(n, -0.05, 0.05, 3, "cpu").numpy()
+        for bits in range(1, 9):
+            pk, sc = oracle_workers(n, bits, bucket, 1, seed=bits)
+            dpk, dsc = to_dev(pk, sc)
+            p = torch.from_numpy(p0.copy()).to(DEV)
+            mqgrad.mqg_dequantize_update(dpk[0], dsc[0], n, bits, bucket, 0.3, p)
+            torch.cuda.synchronize()
+            want = ref.dequantize_update(pk[0], sc[0], n, bits, bucket, 0.3, p0)
+            assert ulp_distance(p.cpu().numpy(), want).max() == 0, "n=%d B=%d b=%d" % (n, bucket, bits)
+
+
+def test_full_exchange_iterations_stay_on_the_oracle():
+    # 10 iterations of the paper's loop on the GPU and in the oracle: W workers quantize, the server sends the
+    # quantized mean back, every worker applies it; the parameters must stay bit-equal throughout
+    n, W, bucket, lr = 300000 + 13, 4, 1024, 0.2
+    bits_seq = [2, 2, 3, 4, 4, 5, 6, 7, 8, 8]
+    params = workloads.uniform(n, -0.05, 0.05, 1, DEV)
+    p_ref = params.cpu().numpy().copy()
+    for it, bits in enumerate(bits_seq):
+        grads = [workloads.normal(n, 0.01, 50 + 10 * it + w, DEV) for w in range(W)]
+        outs = [mqgrad.mqg_quantize(g, bits, bucket, seed=9, iteration=it, worker=w) for w, g in enumerate(grads)]
+        mean_pk, mean_sc = mqgrad.mqg_aggregate_requantize([o[0] for o in outs], [o[1] for o in outs], n, bits, bucket,
+                                                           seed=9, iteration=it, worker=W)
+        mqgrad.mqg_dequantize_update(mean_pk, mean_sc, n, bits, bucket, lr, params)
+        torch.cuda.synchronize()
+        want = [ref.quantize(g.cpu().numpy(), bits, bucket, 9, it, w) for w, g in enumerate(grads)]
+        m_pk, m_sc = ref.aggregate_requantize([x[0] for x in want], [x[1] for x in want], n, bits, bucket, 9, it, W, 0)
+        assert np.array_equal(to_u32(mean_pk), m_pk) and np.array_equal(mean_sc.cpu().numpy(), m_sc), "iteration %d" % it
+        p_ref = ref.dequantize_update(m_pk, m_sc, n, bits, bucket, lr, p_ref)
+        assert ulp_distance(params.cpu().numpy(), p_ref).max() == 0, "iteration %d" % it
