@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # that was profiled has an entry; any other reports null.
 MEASURED_TRAFFIC = {
     # (n, workers, bits, bucket): (quantize bytes per launch, aggregate_update bytes per launch)
-    (100_000_000, 8, 4, 1024): (450.87e6, 1225.06e6),
+    (100_000_000, 8, 4, 1024): (450.9e6, 1225.1e6),
 }
 
 
@@ -104,6 +104,57 @@ def time_config(wl, bits, bucket, lr, steps, warmup):
     return (t1 - t0) / steps * 1e3, q_ms, a_ms
 
 
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 compute units x 64 lanes per clock x 2.4 GHz, one-lane-op units
+
+
+def time_exchange(wl, bits, bucket, lr, steps, warmup):
+    """The second leg of Algorithm 1: mqg_aggregate_requantize (server) + mqg_dequantize_update (worker).
+
+    The re-quantize kernel is bound by vector-ALU issue, not by HBM: per element it executes
+    W * 4 (bit-field extract, 2c - L, convert, fma) + about 17 (range, rounding, Philox / 8, packing)
+    vector operations while moving only (W + 1) * bits / 8 bytes."""
+    import torch
+    from paper_1804_08066_amd import mqgrad
+    n, W = wl.n, wl.W
+    outs = wl.outputs(bits, bucket)
+    pk, sc = [o[0] for o in outs], [o[1] for o in outs]
+    for w in range(W):
+        mqgrad.mqg_quantize(wl.grads[w], bits, bucket, seed=1234, iteration=0, worker=w, packed_out=pk[w], scales_out=sc[w])
+    mean_pk, mean_sc = mqgrad.alloc_outputs(n, bits, bucket, wl.device)
+    ev = []
+    for k in range(warmup + steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        mqgrad.mqg_aggregate_requantize(pk, sc, n, bits, bucket, seed=1234, iteration=k, worker=W,
+                                        packed_out=mean_pk, scales_out=mean_sc)
+        e[1].record()
+        mqgrad.mqg_dequantize_update(mean_pk, mean_sc, n, bits, bucket, lr, wl.params)
+        e[2].record()
+        if k >= warmup:
+            ev.append(e)
+    torch.cuda.synchronize()
+    r_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev)
+    d_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+    nb = (n + bucket - 1) // bucket
+    r_bytes = (W + 1) * (n * bits / 8.0 + 4.0 * nb)
+    d_bytes = n * bits / 8.0 + 4.0 * nb + 8.0 * n
+    r_ops = n * (4.0 * W + 17.0)
+    log("exchange: requantize %.1f us (%.1f T lane-ops/s, %.0f GB/s), dequantize_update %.1f us (%.0f GB/s)" %
+        (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9))
+    return {
+        "requantize": {"kernel": "requantize_pack_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
+                       "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T lane-ops/s",
+                       "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
+                       "algorithmic_ops_per_launch": r_ops, "algorithmic_bytes_per_launch": r_bytes,
+                       "hbm_gbs": r_bytes / (r_ms * 1e-3) / 1e9},
+        "dequantize_update": {"kernel": "aggregate_update_rows_kernel (W=1)", "avg_launch_us": d_ms * 1e3, "bound": "hbm",
+                              "achieved": d_bytes / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": d_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "algorithmic_bytes_per_launch": d_bytes},
+        "grad_gbs_server_leg": 4.0 * n * W / (r_ms * 1e-3) / 1e9,
+    }
+
+
 def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
     """The oracle as it stands, single thread, on a slice of the same workload (host tensors)."""
     import numpy as np
@@ -135,6 +186,8 @@ def main():
     ap.add_argument("--bucket", type=int, default=1024)
     ap.add_argument("--lr", type=float, default=0.1)
     ap.add_argument("--sweep", action="store_true", help="also time every (b, bucket) of the sweep")
+    ap.add_argument("--exchange", action="store_true",
+                    help="also time the paper's full exchange: server re-quantizes the mean, worker de-quantizes and updates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
@@ -198,6 +251,9 @@ def main():
                 log("sweep b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%)" %
                     (b, bk, q * 1e3, 100 * rows[-1]["quantize_hbm_frac"], a * 1e3, 100 * rows[-1]["aggregate_hbm_frac"]))
         out["sweep"] = rows
+
+    if args.exchange:
+        out["exchange"] = time_exchange(wl, bits, bucket, args.lr, max(10, args.steps // 4), max(5, args.warmup // 4))
 
     if args.calibrate_copy:
         dst = torch.empty_like(wl.grads[0])
