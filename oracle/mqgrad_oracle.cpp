@@ -304,6 +304,18 @@ void orc_dequantize_update(const uint32_t* packed, const float* scales, uint64_t
     }
 }
 
+// Layers that are sent uncompressed (the paper quantizes only its two large fully connected layers
+// and communicates the other parameters "without any compression", Section 4.1): the server averages
+// the raw fp32 gradients in worker order and applies the same update.
+void orc_average_update_raw(const float* const* grads, uint32_t W, uint64_t n, float lr, float* params) {
+    const float c = lr / (float)W;
+    for (uint64_t i = 0; i < n; ++i) {
+        float acc = 0.0f;
+        for (uint32_t w = 0; w < W; ++w) acc = acc + grads[w][i];
+        params[i] = std::fmaf(-c, acc, params[i]);
+    }
+}
+
 // The same server step evaluated from its plain definition in fp64 (no
 // ordering, no fp32 rounding until the end): used to pin the fp32 chain.
 void orc_aggregate_update_f64(const uint32_t* const* packed, const float* const* scales, uint32_t W,

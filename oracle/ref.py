@@ -61,6 +61,8 @@ def lib():
         L.orc_aggregate_requantize.restype = None
         L.orc_dequantize_update.argtypes = [u32p, f32p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_float, f32p]
         L.orc_dequantize_update.restype = None
+        L.orc_average_update_raw.argtypes = [pp_f32, C.c_uint32, C.c_uint64, C.c_float, f32p]
+        L.orc_average_update_raw.restype = None
         _lib = L
     return _lib
 
@@ -231,4 +233,17 @@ def dequantize_update(packed, scales, n, bits, bucket, lr, params):
     assert out.size == n
     lib().orc_dequantize_update(_p(packed, C.c_uint32), _p(scales, C.c_float), n, bits, bucket,
                                 float(np.float32(lr)), _p(out, C.c_float))
+    return out
+
+
+def average_update_raw(grads, lr, params):
+    """Uncompressed layers: params - (lr / W) * sum_w grads[w], summed in worker order in fp32."""
+    W = len(grads)
+    gs = [_f32(g).reshape(-1) for g in grads]
+    n = gs[0].size
+    f32p = C.POINTER(C.c_float)
+    ga = (f32p * W)(*[_p(g, C.c_float) for g in gs])
+    out = np.array(params, dtype=np.float32, copy=True).reshape(-1)
+    assert out.size == n and all(g.size == n for g in gs)
+    lib().orc_average_update_raw(ga, W, n, float(np.float32(lr)), _p(out, C.c_float))
     return out

@@ -516,3 +516,16 @@ def test_dequantize_update_special_cases_and_round_trip():
     delta = 2 * np.repeat(sc_m, bucket)[:n].astype(np.float64) / ((1 << bits) - 1)
     assert np.all(np.abs(via_exchange - direct) <= lr * delta * (1 + 1e-5) + 1e-9)
     assert np.abs(via_exchange - direct).max() > 0
+
+
+def test_raw_layers_are_averaged_like_plain_sgd():
+    rng = np.random.default_rng(4)
+    n, W, lr = 1000, 5, 0.3
+    gs = [rng.normal(0, 0.01, n).astype(np.float32) for _ in range(W)]
+    p = rng.uniform(-0.05, 0.05, n).astype(np.float32)
+    got = ref.average_update_raw(gs, lr, p).astype(np.float64)
+    want = p.astype(np.float64) - float(np.float32(lr)) * np.mean(np.stack(gs).astype(np.float64), axis=0)
+    mag = np.abs(p) + lr * np.mean(np.abs(np.stack(gs)), axis=0)
+    assert np.all(np.abs(got - want) <= (W + 2) * 2.0 ** -23 * mag)
+    assert np.array_equal(ref.average_update_raw(gs[:1], 1.0, np.zeros(n, np.float32)), -gs[0])
+    assert ref.average_update_raw(gs, 0.0, p).tobytes() == p.tobytes()
