@@ -149,6 +149,42 @@ mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* 
 mqg_status mqg_dequantize_update(const uint32_t* packed, const float* scales, uint64_t n, uint32_t bits,
                                  uint32_t bucket, float lr, float* params, void* stream);
 
+/* ---- several layer tensors per launch, and layers that are sent uncompressed -----------------
+ *
+ * A model is a list of layer tensors; the paper quantizes only its two large fully connected layers
+ * and communicates the other parameters without compression (Section 4.1).  Small layers are bound
+ * by launch overhead when handled one call at a time, so these entry points take up to
+ * MQG_MAX_TENSORS layers in ONE launch.  Results are bit-identical to the per-tensor calls. */
+
+#define MQG_MAX_TENSORS 32u
+#define MQG_MAX_TENSOR_POINTERS 256u  /* sum over layers of (quantized ? 2 * W : W) */
+
+typedef struct {
+    const float* grad;     /* device, n floats */
+    uint64_t n;            /* 0 is allowed (the layer is skipped) */
+    uint64_t elem_base;    /* multiple of 8: the layer's offset in the model's random stream */
+    uint32_t* packed_out;  /* device, mqg_packed_words(n, bits) words */
+    float* scales_out;     /* device, mqg_num_buckets(n, bucket) floats */
+} mqg_quantize_item;
+
+/* mqg_quantize for `count` layers of one worker.  `items` is a HOST array, read during the call. */
+mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
+                                uint64_t seed, uint32_t iteration, uint32_t worker, void* stream);
+
+typedef struct {
+    uint64_t n;
+    float* params;                   /* device, n floats, updated in place */
+    const uint32_t* const* packed;   /* HOST array of W device pointers; NULL for an uncompressed layer */
+    const float* const* scales;      /* HOST array of W device pointers; NULL for an uncompressed layer */
+    const float* const* raw;         /* uncompressed layer: HOST array of W device pointers to fp32 gradients */
+} mqg_update_item;
+
+/* mqg_aggregate_update for `count` layers.  A layer with packed == NULL is uncompressed:
+ *   params[i] <- fma(-(lr / W), sum_{w} raw[w][i], params[i])   (fp32 sum in worker order).
+ * Errors: MQG_EINVAL also for count > MQG_MAX_TENSORS or more than MQG_MAX_TENSOR_POINTERS pointers. */
+mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t count, uint32_t W,
+                                        uint32_t bits, uint32_t bucket, float lr, void* stream);
+
 /* ---- host-side agent that chooses K (Section 3.3, Algorithm 2).  No GPU involved. ---------- */
 
 typedef struct mqg_mdp mqg_mdp;

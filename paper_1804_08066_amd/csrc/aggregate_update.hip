@@ -169,63 +169,81 @@ constexpr int kLdsR = 2;
 constexpr uint32_t kLdsTile = 1024u * kLdsR;
 constexpr uint32_t kMaxBuckets = kLdsTile / 32u + 1u;   // buckets a tile can touch
 
+// One tile of kLdsTile parameters of one tensor.  packed / scales: tables of W device pointers
+// (in kernel-argument memory).  raw != nullptr: an uncompressed layer -- the W pointers are fp32
+// gradients that are summed in worker order instead of decoded.
 template <bool STRADDLE, bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const AggregateArgs a) {
+__device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed, const float* const* scales,
+                                                   const float* const* raw, uint32_t W, uint64_t n, uint32_t b,
+                                                   uint32_t bucket, int bucket_shift, float neg_c,
+                                                   float* __restrict__ params, uint64_t tile_base, float* s_step) {
     constexpr int R = kLdsR;
-    extern __shared__ float s_step[];   // [W][nbt]
-
     const uint32_t tid = threadIdx.x;
-    const uint64_t tile_base = (uint64_t)blockIdx.x * kLdsTile;
-    const uint64_t left = a.n - tile_base;
+    const uint64_t left = n - tile_base;
     const uint32_t tile_count = left < kLdsTile ? (uint32_t)left : kLdsTile;
     const bool full = tile_count == kLdsTile;
-    float* __restrict__ p = a.params + tile_base;
+    float* __restrict__ p = params + tile_base;
 
     float4 x[R];
     load_params<R, ALIGNED>(p, tile_count, full, x);
+    float4 acc[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
-    const uint32_t b = a.bits;
+    if (raw != nullptr) {
+        // uncompressed layer: plain fp32 sum in worker order
+        for (uint32_t w = 0; w < W; ++w) {
+            const float* __restrict__ g = raw[w] + tile_base;
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const uint32_t el = 4u * (j * kThreads + tid);
+                if (el + 0u < tile_count) acc[j].x = acc[j].x + g[el + 0];
+                if (el + 1u < tile_count) acc[j].y = acc[j].y + g[el + 1];
+                if (el + 2u < tile_count) acc[j].z = acc[j].z + g[el + 2];
+                if (el + 3u < tile_count) acc[j].w = acc[j].w + g[el + 3];
+            }
+        }
+        update_params<R, ALIGNED>(p, tile_count, full, neg_c, x, acc);
+        return;
+    }
+
     const int negL = -(int)((1u << b) - 1u);
     const float Lf = (float)((1u << b) - 1u);
-    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
+    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
-    decode::fetch_codes<R, kChunk>(a.packed, a.W, 0u, cw, c);   // in flight while the bucket steps are computed
+    decode::fetch_codes<R, kChunk>(packed, W, 0u, cw, c);   // in flight while the bucket steps are computed
 
-    const uint64_t kb0 = tile_base / a.bucket;
-    const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
-    const uint32_t first_off = (uint32_t)(tile_base - kb0 * a.bucket);
+    const uint64_t kb0 = tile_base / bucket;
+    const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / bucket - kb0) + 1u;   // <= kMaxBuckets
+    const uint32_t first_off = (uint32_t)(tile_base - kb0 * bucket);
     uint32_t bl[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const uint32_t eo = 4u * (j * kThreads + tid) + first_off;
-        bl[j] = a.bucket_shift >= 0 ? (eo >> a.bucket_shift) : (eo / a.bucket);
+        bl[j] = bucket_shift >= 0 ? (eo >> bucket_shift) : (eo / bucket);
         if (bl[j] >= nbt) bl[j] = nbt - 1u;   // quads past the end: any valid slot
     }
     if (tid < nbt) {
-        for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
+        for (uint32_t w0 = 0; w0 < W; w0 += kChunk) {
             float sv[kChunk];
 #pragma unroll
             for (int t = 0; t < kChunk; ++t) {
-                const uint32_t w = (w0 + t < a.W) ? w0 + t : a.W - 1u;
-                sv[t] = a.scales[w][kb0 + tid];
+                const uint32_t w = (w0 + t < W) ? w0 + t : W - 1u;
+                sv[t] = scales[w][kb0 + tid];
             }
 #pragma unroll
             for (int t = 0; t < kChunk; ++t) {
-                if (w0 + t < a.W) s_step[(w0 + t) * nbt + tid] = sv[t] / Lf;   // IEEE-correct fp32 division
+                if (w0 + t < W) s_step[(w0 + t) * nbt + tid] = sv[t] / Lf;   // IEEE-correct fp32 division
             }
         }
     }
     __syncthreads();
 
-    float4 acc[R];
-#pragma unroll
-    for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-
-    for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) decode::fetch_codes<R, kChunk>(a.packed, a.W, w0, cw, c);
+    for (uint32_t w0 = 0; w0 < W; w0 += kChunk) {
+        if (w0 > 0) decode::fetch_codes<R, kChunk>(packed, W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
-            if (w0 + t < a.W) {
+            if (w0 + t < W) {
                 const float* __restrict__ dw = s_step + (w0 + t) * nbt;
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
@@ -234,7 +252,37 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const Ag
             }
         }
     }
-    update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+    update_params<R, ALIGNED>(p, tile_count, full, neg_c, x, acc);
+}
+
+template <bool STRADDLE, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const AggregateArgs a) {
+    extern __shared__ float s_step[];   // [W][nbt]
+    aggregate_tile_lds<STRADDLE, ALIGNED>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket, a.bucket_shift,
+                                          a.neg_c, a.params, (uint64_t)blockIdx.x * kLdsTile, s_step);
+}
+
+// Several tensors of a model in one launch: block -> (tensor, tile) through the prefix table of tile
+// counts.  A tensor is either quantized (W packed + W scale pointers) or raw (W fp32 gradients).
+template <bool STRADDLE, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void aggregate_update_tensors_kernel(const BatchAggregateArgs a) {
+    extern __shared__ float s_step[];
+    uint32_t lo = 0, hi = a.count;           // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= a.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    const BatchAggregateArgs::Tensor& t = a.t[lo];
+    const uint64_t tile_base = (uint64_t)(blockIdx.x - a.tile_start[lo]) * kLdsTile;
+    const void* const* ptrs = a.ptrs + t.first_ptr;
+    if (t.raw) {
+        aggregate_tile_lds<STRADDLE, ALIGNED>(nullptr, nullptr, reinterpret_cast<const float* const*>(ptrs), a.W, t.n,
+                                              a.bits, a.bucket, a.bucket_shift, a.neg_c, t.params, tile_base, s_step);
+    } else {
+        aggregate_tile_lds<STRADDLE, ALIGNED>(reinterpret_cast<const uint32_t* const*>(ptrs),
+                                              reinterpret_cast<const float* const*>(ptrs + a.W), nullptr, a.W, t.n,
+                                              a.bits, a.bucket, a.bucket_shift, a.neg_c, t.params, tile_base, s_step);
+    }
 }
 
 template <int R, int NBR, bool STRADDLE>
@@ -267,7 +315,27 @@ hipError_t launch_lds(const AggregateArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <bool STRADDLE>
+hipError_t launch_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+    const dim3 grid(tiles), block(kThreads);
+    const size_t lds = sizeof(float) * a.W * kMaxBuckets;
+    if (aligned) {
+        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, true>), grid, block, lds, stream, a);
+    } else {
+        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, false>), grid, block, lds, stream, a);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
+
+uint32_t aggregate_batch_tile() { return kLdsTile; }
+
+hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+    if (tiles == 0) return hipSuccess;
+    const bool straddle = (32u % a.bits) != 0u;
+    return straddle ? launch_tensors<true>(a, tiles, aligned, stream) : launch_tensors<false>(a, tiles, aligned, stream);
+}
 
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;

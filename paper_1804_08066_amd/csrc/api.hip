@@ -181,4 +181,107 @@ mqg_status mqg_dequantize_update(const uint32_t* packed, const float* scales, ui
     return mqg_aggregate_update(pk, sc, 1u, n, bits, bucket, lr, params, stream);
 }
 
+mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
+                                uint64_t seed, uint32_t iteration, uint32_t worker, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (count > MQG_MAX_TENSORS) return MQG_EINVAL;
+    if (count == 0) return MQG_OK;
+    if (items == nullptr) return MQG_EINVAL;
+    mqg::BatchQuantizeArgs a;
+    a.common.grad = nullptr;
+    a.common.n = 0;
+    a.common.bits = bits;
+    a.common.bucket = bucket;
+    a.common.bucket_shift = log2_if_pow2(bucket);
+    a.common.scale_mode = MQG_SCALE_MAXABS;
+    a.common.key0 = (uint32_t)seed;
+    a.common.key1 = (uint32_t)(seed >> 32);
+    a.common.iteration = iteration;
+    a.common.worker = worker;
+    a.common.elem_base = 0;
+    a.common.scales_in = nullptr;
+    a.common.packed = nullptr;
+    a.common.scales = nullptr;
+    a.count = count;
+    a.tile_elems = mqg::quantize_batch_tile(bucket);
+    bool aligned = true;
+    uint64_t tiles = 0;
+    for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
+        a.tile_start[i] = (uint32_t)tiles;
+        mqg::BatchQuantizeArgs::Tensor& t = a.t[i];
+        t = mqg::BatchQuantizeArgs::Tensor{nullptr, 0, 0, nullptr, nullptr};
+        if (i >= count) continue;
+        const mqg_quantize_item& it = items[i];
+        if ((it.elem_base & 7u) != 0u) return MQG_EINVAL;
+        if (it.n == 0) continue;
+        if (it.grad == nullptr || it.packed_out == nullptr || it.scales_out == nullptr) return MQG_EINVAL;
+        if (it.n > (UINT64_MAX >> 4) || it.elem_base > UINT64_MAX - it.n) return MQG_EINVAL;
+        if (misaligned4(it.grad) || misaligned4(it.packed_out) || misaligned4(it.scales_out)) return MQG_EALIGN;
+        if ((reinterpret_cast<uintptr_t>(it.grad) & 15u) != 0) aligned = false;
+        t = mqg::BatchQuantizeArgs::Tensor{it.grad, it.n, it.elem_base, it.packed_out, it.scales_out};
+        tiles += (it.n + a.tile_elems - 1) / a.tile_elems;
+        if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
+    }
+    a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
+    const hipError_t err = mqg::launch_quantize_tensors(a, (uint32_t)tiles, aligned, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t count, uint32_t W,
+                                        uint32_t bits, uint32_t bucket, float lr, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (count > MQG_MAX_TENSORS) return MQG_EINVAL;
+    if (count == 0) return MQG_OK;
+    if (items == nullptr) return MQG_EINVAL;
+    mqg::BatchAggregateArgs a;
+    a.count = count;
+    a.W = W;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.neg_c = -(lr / (float)W);
+    for (uint32_t i = 0; i < mqg::kMaxBatchPointers; ++i) a.ptrs[i] = nullptr;
+    const uint32_t tile = mqg::aggregate_batch_tile();
+    bool aligned = true;
+    uint64_t tiles = 0;
+    uint32_t used = 0;
+    for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
+        a.tile_start[i] = (uint32_t)tiles;
+        a.t[i] = mqg::BatchAggregateArgs::Tensor{0, nullptr, 0, 0};
+        if (i >= count) continue;
+        const mqg_update_item& it = items[i];
+        if (it.n == 0) continue;
+        if (it.params == nullptr || it.n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+        if (misaligned4(it.params)) return MQG_EALIGN;
+        if ((reinterpret_cast<uintptr_t>(it.params) & 15u) != 0) aligned = false;
+        const bool raw = it.packed == nullptr;
+        const uint32_t need = raw ? W : 2u * W;
+        if (used + need > mqg::kMaxBatchPointers) return MQG_EINVAL;
+        if (raw) {
+            if (it.raw == nullptr) return MQG_EINVAL;
+            for (uint32_t w = 0; w < W; ++w) {
+                if (it.raw[w] == nullptr) return MQG_EINVAL;
+                if (misaligned4(it.raw[w])) return MQG_EALIGN;
+                a.ptrs[used + w] = it.raw[w];
+            }
+        } else {
+            if (it.scales == nullptr) return MQG_EINVAL;
+            for (uint32_t w = 0; w < W; ++w) {
+                if (it.packed[w] == nullptr || it.scales[w] == nullptr) return MQG_EINVAL;
+                if (misaligned4(it.packed[w]) || misaligned4(it.scales[w])) return MQG_EALIGN;
+                a.ptrs[used + w] = it.packed[w];
+                a.ptrs[used + W + w] = it.scales[w];
+            }
+        }
+        a.t[i] = mqg::BatchAggregateArgs::Tensor{it.n, it.params, used, raw ? 1u : 0u};
+        used += need;
+        tiles += (it.n + tile - 1) / tile;
+        if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
+    }
+    a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
+    const hipError_t err = mqg::launch_aggregate_tensors(a, (uint32_t)tiles, aligned, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
 }  // extern "C"

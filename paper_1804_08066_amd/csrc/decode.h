@@ -57,7 +57,7 @@ struct CodeRegs {
 // aligned dword load per worker and quad, all issued before any is consumed.  Adjacent lanes read
 // the same or adjacent words, so a wave's request is one contiguous run of 32*bits bytes.
 template <int R, int CH>
-__device__ __forceinline__ void fetch_codes(const uint32_t* const (&packed)[MQG_MAX_WORKERS], uint32_t W,
+__device__ __forceinline__ void fetch_codes(const uint32_t* const* packed, uint32_t W,
                                             uint32_t w0, const CodeWindows<R>& cw, CodeRegs<R, CH>& c) {
 #pragma unroll
     for (int t = 0; t < CH; ++t) {

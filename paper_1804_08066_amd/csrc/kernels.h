@@ -43,6 +43,45 @@ struct RequantArgs {
     uint32_t W;
 };
 
+// Several layer tensors of one model in one launch.
+constexpr uint32_t kMaxBatchTensors = 32;
+constexpr uint32_t kMaxBatchPointers = 256;   // per quantized tensor 2*W pointers, per raw tensor W
+
+struct BatchAggregateArgs {
+    struct Tensor {
+        uint64_t n;
+        float* params;
+        uint32_t first_ptr;   // index into ptrs: [W packed][W scales], or [W raw gradients]
+        uint32_t raw;         // 1: uncompressed layer
+    };
+    uint32_t count, W, bits, bucket;
+    int bucket_shift;
+    float neg_c;
+    uint32_t tile_start[kMaxBatchTensors + 1];   // prefix sums of the tensors' tile counts
+    Tensor t[kMaxBatchTensors];
+    const void* ptrs[kMaxBatchPointers];
+};
+
+struct BatchQuantizeArgs {
+    struct Tensor {
+        const float* grad;
+        uint64_t n;
+        uint64_t elem_base;
+        uint32_t* packed;
+        float* scales;
+    };
+    QuantizeArgs common;      // bits, bucket, stream selection; per-tensor fields are taken from t[]
+    uint32_t count;
+    uint32_t tile_elems;
+    uint32_t tile_start[kMaxBatchTensors + 1];
+    Tensor t[kMaxBatchTensors];
+};
+
+uint32_t aggregate_batch_tile();
+hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream);
+uint32_t quantize_batch_tile(uint32_t bucket);
+hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream);
+
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_requantize(const RequantArgs& a, hipStream_t stream);
 bool quantize_wave_supported(const QuantizeArgs& a);          // quantize_wave.hip

@@ -345,6 +345,51 @@ __global__ __launch_bounds__(kThreads) void requantize_pack_kernel(const Requant
     }
 }
 
+// Several layer tensors of one worker in one launch: block -> (tensor, tile) through the prefix table.
+template <int R, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void quantize_tensors_kernel(const BatchQuantizeArgs ba) {
+    __shared__ Shared<R> sm;
+    uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= ba.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    QuantizeArgs a = ba.common;
+    a.grad = ba.t[lo].grad;
+    a.n = ba.t[lo].n;
+    a.elem_base = ba.t[lo].elem_base;
+    a.packed = ba.t[lo].packed;
+    a.scales = ba.t[lo].scales;
+    const uint64_t tile_base = (uint64_t)(blockIdx.x - ba.tile_start[lo]) * ba.tile_elems;
+    const uint64_t left = a.n - tile_base;
+    const uint32_t tile_count = left < ba.tile_elems ? (uint32_t)left : ba.tile_elems;
+    const bool full = tile_count == Tile<R>::kCap;
+
+    GradSource<R, ALIGNED> src;
+    src.g = a.grad + tile_base;
+    src.issue(tile_count, full);
+    clear_shared<R>(sm, tile_count, a.bits);
+    __syncthreads();
+    float4 x[R];
+    src.finish(x);
+    if (full) {
+        quantize_tile<R, true>(a, tile_base, tile_count, x, 1.0f, sm);
+    } else {
+        quantize_tile<R, false>(a, tile_base, tile_count, x, 1.0f, sm);
+    }
+}
+
+template <int R>
+hipError_t launch_tensors_r(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+    const dim3 grid(tiles), block(kThreads);
+    if (aligned) {
+        hipLaunchKernelGGL((quantize_tensors_kernel<R, true>), grid, block, 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((quantize_tensors_kernel<R, false>), grid, block, 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
 template <int R>
 hipError_t launch_r(const QuantizeArgs& a, hipStream_t stream) {
     const uint32_t cap = Tile<R>::kCap;
@@ -380,6 +425,18 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
     if (a.bucket <= 4096u) return launch_r<4>(a, stream);
     if (a.bucket <= 8192u) return launch_r<8>(a, stream);
     return launch_r<16>(a, stream);
+}
+
+uint32_t quantize_batch_tile(uint32_t bucket) {
+    const uint32_t cap = bucket <= 4096u ? Tile<4>::kCap : (bucket <= 8192u ? Tile<8>::kCap : Tile<16>::kCap);
+    return (cap / bucket) * bucket;
+}
+
+hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+    if (tiles == 0) return hipSuccess;
+    if (a.common.bucket <= 4096u) return launch_tensors_r<4>(a, tiles, aligned, stream);
+    if (a.common.bucket <= 8192u) return launch_tensors_r<8>(a, tiles, aligned, stream);
+    return launch_tensors_r<16>(a, tiles, aligned, stream);
 }
 
 hipError_t launch_requantize(const RequantArgs& ra, hipStream_t stream) {

@@ -18,7 +18,7 @@ MQG_MAX_WORKERS = 64
 EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
-    "mqg_aggregate_requantize", "mqg_dequantize_update",
+    "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
 ]
@@ -36,6 +36,19 @@ class MdpConfig(C.Structure):
                 ("alpha", C.c_double), ("epsilon", C.c_double), ("eta", C.c_double),
                 ("reward_scale", C.c_double), ("discount", C.c_double)]
 
+
+class QuantizeItem(C.Structure):
+    _fields_ = [("grad", C.c_void_p), ("n", C.c_uint64), ("elem_base", C.c_uint64),
+                ("packed_out", C.c_void_p), ("scales_out", C.c_void_p)]
+
+
+class UpdateItem(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("params", C.c_void_p), ("packed", C.POINTER(C.c_void_p)),
+                ("scales", C.POINTER(C.c_void_p)), ("raw", C.POINTER(C.c_void_p))]
+
+
+MQG_MAX_TENSORS = 32
+MQG_MAX_TENSOR_POINTERS = 256
 
 _lib = None
 
@@ -67,6 +80,10 @@ def lib():
     L.mqg_aggregate_requantize.restype = C.c_int
     L.mqg_dequantize_update.argtypes = [vp, vp, u64, u32, u32, f32, vp, vp]
     L.mqg_dequantize_update.restype = C.c_int
+    L.mqg_quantize_tensors.argtypes = [C.POINTER(QuantizeItem), u32, u32, u32, u64, u32, u32, vp]
+    L.mqg_quantize_tensors.restype = C.c_int
+    L.mqg_aggregate_update_tensors.argtypes = [C.POINTER(UpdateItem), u32, u32, u32, u32, f32, vp]
+    L.mqg_aggregate_update_tensors.restype = C.c_int
     L.mqg_mdp_default_config.argtypes = [C.POINTER(MdpConfig)]
     L.mqg_mdp_default_config.restype = None
     L.mqg_mdp_create.argtypes = [C.POINTER(MdpConfig)]
@@ -219,6 +236,63 @@ def mqg_dequantize_update(packed, scales, n, bits, bucket, lr, params, stream=No
     if st != MQG_OK:
         raise MqgError(st, "mqg_dequantize_update")
     return params
+
+
+def mqg_quantize_tensors(grads, bits, bucket, seed, iteration=0, worker=0, elem_bases=None, outputs=None, stream=None):
+    """mqg_quantize for a list of layer tensors of one worker in one launch.
+    Returns a list of (packed, scales) per layer."""
+    count = len(grads)
+    if elem_bases is None:
+        elem_bases = [0] * count
+    if outputs is None:
+        outputs = [alloc_outputs(g.numel(), bits, bucket, g.device) for g in grads]
+    items = (QuantizeItem * max(count, 1))()
+    for i, g in enumerate(grads):
+        _check(g, torch.float32, "grads[%d]" % i)
+        p, s = outputs[i]
+        _check(p, torch.int32, "packed_out")
+        _check(s, torch.float32, "scales_out")
+        if p.numel() < mqg_packed_words(g.numel(), bits) or s.numel() < mqg_num_buckets(g.numel(), bucket):
+            raise ValueError("output buffers too small")
+        items[i] = QuantizeItem(g.data_ptr(), g.numel(), elem_bases[i], p.data_ptr(), s.data_ptr())
+    st = lib().mqg_quantize_tensors(items, count, bits, bucket, seed, iteration, worker, _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_quantize_tensors")
+    return outputs
+
+
+def mqg_aggregate_update_tensors(layers, W, bits, bucket, lr, stream=None):
+    """mqg_aggregate_update for a list of layers in one launch.
+
+    Each layer is a dict with "params" and either ("packed": [W tensors], "scales": [W tensors]) for a
+    quantized layer or "raw": [W fp32 gradient tensors] for a layer sent uncompressed."""
+    count = len(layers)
+    items = (UpdateItem * max(count, 1))()
+    keep = []
+    for i, layer in enumerate(layers):
+        params = layer["params"]
+        _check(params, torch.float32, "params")
+        n = params.numel()
+        if "raw" in layer:
+            raw = layer["raw"]
+            if len(raw) != W:
+                raise ValueError("raw must have one gradient per worker")
+            for g in raw:
+                _check(g, torch.float32, "raw[w]")
+                if g.numel() != n:
+                    raise ValueError("raw gradient size differs from params")
+            ra = (C.c_void_p * W)(*[g.data_ptr() for g in raw])
+            keep.append(ra)
+            items[i] = UpdateItem(n, params.data_ptr(), None, None, ra)
+        else:
+            Wn, pa, sa = _worker_arrays(layer["packed"], layer["scales"], n, bits, bucket)
+            if Wn != W:
+                raise ValueError("packed/scales must have one entry per worker")
+            keep.extend([pa, sa])
+            items[i] = UpdateItem(n, params.data_ptr(), pa, sa, None)
+    st = lib().mqg_aggregate_update_tensors(items, count, W, bits, bucket, lr, _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_update_tensors")
 
 
 class Mdp:

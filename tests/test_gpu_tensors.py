@@ -1,0 +1,90 @@
+"""GPU parity for the multi-tensor entry points: several layers per launch, uncompressed layers."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_1804_08066_amd import mqgrad, workloads
+from helpers import to_u32, ulp_distance
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("bucket", [96, 512, 8192])
+def test_batched_quantize_equals_per_tensor_and_oracle(bucket):
+    sizes = [n for _, n in workloads.SMALL_CNN_SHAPES] + [0, 1, 40000 + 3]
+    bases, run = [], 0
+    for n in sizes:
+        bases.append(run)
+        run += (n + bucket - 1) // bucket * bucket
+    assert all(b % 8 == 0 for b in bases)
+    grads = [workloads.laplace(n, 2e-3, 70 + i, DEV) if n else torch.empty(0, device=DEV) for i, n in enumerate(sizes)]
+    for bits in (1, 3, 8):
+        outs = mqgrad.mqg_quantize_tensors(grads, bits, bucket, seed=4, iteration=7, worker=2, elem_bases=bases)
+        torch.cuda.synchronize()
+        for i, g in enumerate(grads):
+            if sizes[i] == 0:
+                continue
+            pk_o, sc_o = ref.quantize(g.cpu().numpy(), bits, bucket, 4, 7, 2, bases[i])
+            assert np.array_equal(to_u32(outs[i][0]), pk_o), "layer %d b=%d" % (i, bits)
+            assert np.array_equal(outs[i][1].cpu().numpy(), sc_o), "layer %d b=%d" % (i, bits)
+
+
+def test_unaligned_layer_views_in_a_batch():
+    base = workloads.normal(30000, 0.01, 5, DEV)
+    grads = [base[1:5001], base[6000:6000 + 7000], base[14003:14003 + 999]]
+    outs = mqgrad.mqg_quantize_tensors(grads, 5, 512, seed=1, elem_bases=[0, 8192, 16384])
+    torch.cuda.synchronize()
+    for g, (pk, sc), eb in zip(grads, outs, [0, 8192, 16384]):
+        pk_o, sc_o = ref.quantize(g.cpu().numpy(), 5, 512, 1, 0, 0, eb)
+        assert np.array_equal(to_u32(pk), pk_o) and np.array_equal(sc.cpu().numpy(), sc_o)
+
+
+def test_config2_iterations_with_batched_calls_and_raw_small_layers():
+    # the paper's selective quantization: the large layers are quantized, biases and the small last
+    # layer travel uncompressed; one quantize launch per worker and one update launch per iteration
+    W, bucket, lr, iters, seed = 4, 512, 0.1, 12, 0
+    shapes = workloads.SMALL_CNN_SHAPES
+    quantized = [n >= 4096 for _, n in shapes]
+    bases = workloads.config2_elem_bases(bucket)
+    bits_seq = workloads.config2_bits_sequence(iters, seed)
+    params = workloads.config2_params(seed, DEV)
+    p_ref = [p.cpu().numpy().copy() for p in params]
+    q_idx = [i for i, q in enumerate(quantized) if q]
+    for it in range(iters):
+        bits = bits_seq[it]
+        grads = [workloads.config2_grads(it, w, seed, DEV) for w in range(W)]
+        outs = [mqgrad.mqg_quantize_tensors([grads[w][i] for i in q_idx], bits, bucket, seed=seed + w, iteration=it,
+                                            worker=w, elem_bases=[bases[i] for i in q_idx]) for w in range(W)]
+        layers = []
+        for i in range(len(shapes)):
+            if quantized[i]:
+                k = q_idx.index(i)
+                layers.append({"params": params[i], "packed": [outs[w][k][0] for w in range(W)],
+                               "scales": [outs[w][k][1] for w in range(W)]})
+            else:
+                layers.append({"params": params[i], "raw": [grads[w][i] for w in range(W)]})
+        mqgrad.mqg_aggregate_update_tensors(layers, W, bits, bucket, lr)
+        torch.cuda.synchronize()
+        for i, (_, n) in enumerate(shapes):
+            if quantized[i]:
+                want = [ref.quantize(grads[w][i].cpu().numpy(), bits, bucket, seed + w, it, w, bases[i]) for w in range(W)]
+                p_ref[i] = ref.aggregate_update([x[0] for x in want], [x[1] for x in want], n, bits, bucket, lr, p_ref[i])
+            else:
+                p_ref[i] = ref.average_update_raw([grads[w][i].cpu().numpy() for w in range(W)], lr, p_ref[i])
+            assert ulp_distance(params[i].cpu().numpy(), p_ref[i]).max() == 0, "iteration %d layer %d" % (it, i)
+
+
+def test_batch_limits_are_reported():
+    g = [workloads.normal(64, 0.01, i, DEV) for i in range(33)]
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_quantize_tensors(g, 4, 32, seed=0)
+    W = 8
+    layers = [{"params": torch.zeros(64, device=DEV), "raw": [g[0]] * W} for _ in range(32)]   # 256 pointers: fits
+    mqgrad.mqg_aggregate_update_tensors(layers, W, 4, 32, 0.1)
+    outs = mqgrad.mqg_quantize_tensors(g[:1], 4, 32, seed=0)
+    layers.append({"params": torch.zeros(64, device=DEV), "packed": [outs[0][0]] * W, "scales": [outs[0][1]] * W})
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_aggregate_update_tensors(layers, W, 4, 32, 0.1)
+    torch.cuda.synchronize()
