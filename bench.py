@@ -155,6 +155,61 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
     }
 
 
+def time_tensors(W, bits, bucket, lr, steps, warmup, device):
+    """Configuration 2 (the small CNN's ten layer tensors, about 1.07 M values per worker): one iteration
+    with one launch per layer and worker versus the multi-tensor entry points (one quantize launch per
+    worker, one update launch). The large layers are quantized, the small ones travel uncompressed."""
+    import torch
+    from paper_1804_08066_amd import mqgrad, workloads
+    shapes = workloads.SMALL_CNN_SHAPES
+    q_idx = [i for i, (_, n) in enumerate(shapes) if n >= 4096]
+    bases = workloads.config2_elem_bases(bucket)
+    grads = [workloads.config2_grads(0, w, 0, device) for w in range(W)]
+    params = workloads.config2_params(0, device)
+    outs = [[mqgrad.alloc_outputs(shapes[i][1], bits, bucket, device) for i in q_idx] for _ in range(W)]
+    layers = []
+    for i in range(len(shapes)):
+        if i in q_idx:
+            k = q_idx.index(i)
+            layers.append({"params": params[i], "packed": [outs[w][k][0] for w in range(W)],
+                           "scales": [outs[w][k][1] for w in range(W)]})
+        else:
+            layers.append({"params": params[i], "raw": [grads[w][i] for w in range(W)]})
+
+    def per_layer(it):
+        for w in range(W):
+            for k, i in enumerate(q_idx):
+                mqgrad.mqg_quantize(grads[w][i], bits, bucket, seed=w, iteration=it, worker=w, elem_base=bases[i],
+                                    packed_out=outs[w][k][0], scales_out=outs[w][k][1])
+        for k, i in enumerate(q_idx):
+            mqgrad.mqg_aggregate_update([outs[w][k][0] for w in range(W)], [outs[w][k][1] for w in range(W)],
+                                        shapes[i][1], bits, bucket, lr, params[i])
+
+    def batched(it):
+        for w in range(W):
+            mqgrad.mqg_quantize_tensors([grads[w][i] for i in q_idx], bits, bucket, seed=w, iteration=it, worker=w,
+                                        elem_bases=[bases[i] for i in q_idx], outputs=outs[w])
+        mqgrad.mqg_aggregate_update_tensors(layers, W, bits, bucket, lr)
+
+    res = {}
+    for name, fn in (("per_layer", per_layer), ("batched", batched)):
+        for it in range(warmup):
+            fn(it)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for it in range(steps):
+            fn(it)
+        torch.cuda.synchronize()
+        res[name + "_us_per_iteration"] = (time.perf_counter() - t0) / steps * 1e6
+    n_total = sum(n for _, n in shapes)
+    res["launches_per_iteration"] = {"per_layer": (W + 1) * len(q_idx), "batched": W + 1}
+    res["grad_gbs_batched"] = 4.0 * n_total * W / (res["batched_us_per_iteration"] * 1e-6) / 1e9
+    res["note"] = "host-inclusive wall clock; the per-layer variant skips the uncompressed layers' update"
+    log("tensors: per-layer %.1f us/iteration, batched %.1f us/iteration" %
+        (res["per_layer_us_per_iteration"], res["batched_us_per_iteration"]))
+    return res
+
+
 def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
     """The oracle as it stands, single thread, on a slice of the same workload (host tensors)."""
     import numpy as np
@@ -188,6 +243,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time every (b, bucket) of the sweep")
     ap.add_argument("--exchange", action="store_true",
                     help="also time the paper's full exchange: server re-quantizes the mean, worker de-quantizes and updates")
+    ap.add_argument("--tensors", action="store_true",
+                    help="also time the small CNN's layer list: one launch per layer versus the multi-tensor calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
@@ -254,6 +311,9 @@ def main():
 
     if args.exchange:
         out["exchange"] = time_exchange(wl, bits, bucket, args.lr, max(10, args.steps // 4), max(5, args.warmup // 4))
+
+    if args.tensors:
+        out["tensors"] = time_tensors(W, bits, 512, args.lr, 200, 20, wl.device)
 
     if args.calibrate_copy:
         dst = torch.empty_like(wl.grads[0])

@@ -316,6 +316,90 @@ void orc_average_update_raw(const float* const* grads, uint32_t W, uint64_t n, f
     }
 }
 
+// ---- The footnote read literally: deterministic range-linear encode over [min, max] ---------------
+// Section 3.2's footnote names a range-linear Encode / Decode: the tensor's range [min, max] is cut
+// into 2^K - 1 equal steps, a value is stored as the index of the nearest level and restored as
+// min + index * step.  No random numbers.  Here the range is taken per bucket (bucket >= n gives the
+// paper's one range per tensor); a bound that is zero is stored as +0.
+
+// ranges[2k] = min, ranges[2k+1] = max of bucket k
+void orc_minmax_ranges(const float* g, uint64_t n, uint32_t bucket, float* ranges) {
+    const uint64_t nb = (n + bucket - 1) / bucket;
+    for (uint64_t k = 0; k < nb; ++k) {
+        const uint64_t lo_i = k * bucket;
+        const uint64_t hi_i = (lo_i + bucket < n) ? lo_i + bucket : n;
+        float mn = g[lo_i], mx = g[lo_i];
+        for (uint64_t i = lo_i + 1; i < hi_i; ++i) {
+            if (g[i] < mn) mn = g[i];
+            if (g[i] > mx) mx = g[i];
+        }
+        if (mn == 0.0f) mn = 0.0f;   // -0 -> +0
+        if (mx == 0.0f) mx = 0.0f;
+        ranges[2 * k] = mn;
+        ranges[2 * k + 1] = mx;
+    }
+}
+
+// Index of the level nearest to x on the grid of 2^bits levels over [mn, mx]; ties go to the even
+// index (the default IEEE rounding of nearbyintf).  A range narrower than 2^-96 has one level.
+uint32_t orc_nearest_code(float x, float mn, float mx, uint32_t bits) {
+    const float L = (float)((1u << bits) - 1u);
+    const float r = mx - mn;
+    const float a = (r >= 0x1p-96f) ? L / r : 0.0f;
+    const float d = x - mn;
+    float u = std::nearbyintf(d * a);
+    if (!(u >= 0.0f)) u = 0.0f;
+    if (u > L) u = L;
+    return (uint32_t)u;
+}
+
+// Decode: min + index * step, step = (max - min) / (2^bits - 1), one fused multiply-add.
+float orc_minmax_level_value(uint32_t k, float mn, float mx, uint32_t bits) {
+    const float L = (float)((1u << bits) - 1u);
+    const float step = (mx - mn) / L;
+    return std::fmaf((float)k, step, mn);
+}
+
+void orc_quantize_minmax(const float* g, uint64_t n, uint32_t bits, uint32_t bucket, uint32_t* packed,
+                         float* ranges, uint8_t* codes_out) {
+    orc_minmax_ranges(g, n, bucket, ranges);
+    uint8_t* codes = codes_out ? codes_out : new uint8_t[n ? n : 1];
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint64_t k = i / bucket;
+        codes[i] = (uint8_t)orc_nearest_code(g[i], ranges[2 * k], ranges[2 * k + 1], bits);
+    }
+    orc_pack(codes, n, bits, packed);
+    if (!codes_out) delete[] codes;
+}
+
+void orc_dequantize_minmax(const uint32_t* packed, const float* ranges, uint64_t n, uint32_t bits,
+                           uint32_t bucket, float* out) {
+    uint8_t* codes = new uint8_t[n ? n : 1];
+    orc_unpack(packed, n, bits, codes);
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint64_t k = i / bucket;
+        out[i] = orc_minmax_level_value(codes[i], ranges[2 * k], ranges[2 * k + 1], bits);
+    }
+    delete[] codes;
+}
+
+// Server step for this encoding: de-quantize every worker's gradient, add them up in worker order,
+// average and update (Algorithm 1, ReceiveQGThenSendQG and the last line of WorkerIterate).
+void orc_aggregate_update_minmax(const uint32_t* const* packed, const float* const* ranges, uint32_t W,
+                                 uint64_t n, uint32_t bits, uint32_t bucket, float lr, float* params) {
+    float* sum = new float[n ? n : 1];
+    float* v = new float[n ? n : 1];
+    for (uint64_t i = 0; i < n; ++i) sum[i] = 0.0f;
+    for (uint32_t w = 0; w < W; ++w) {
+        orc_dequantize_minmax(packed[w], ranges[w], n, bits, bucket, v);
+        for (uint64_t i = 0; i < n; ++i) sum[i] = sum[i] + v[i];
+    }
+    const float c = lr / (float)W;
+    for (uint64_t i = 0; i < n; ++i) params[i] = std::fmaf(-c, sum[i], params[i]);
+    delete[] sum;
+    delete[] v;
+}
+
 // The same server step evaluated from its plain definition in fp64 (no
 // ordering, no fp32 rounding until the end): used to pin the fp32 chain.
 void orc_aggregate_update_f64(const uint32_t* const* packed, const float* const* scales, uint32_t W,

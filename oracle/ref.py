@@ -63,6 +63,19 @@ def lib():
         L.orc_dequantize_update.restype = None
         L.orc_average_update_raw.argtypes = [pp_f32, C.c_uint32, C.c_uint64, C.c_float, f32p]
         L.orc_average_update_raw.restype = None
+        L.orc_minmax_ranges.argtypes = [f32p, C.c_uint64, C.c_uint32, f32p]
+        L.orc_minmax_ranges.restype = None
+        L.orc_nearest_code.argtypes = [C.c_float, C.c_float, C.c_float, C.c_uint32]
+        L.orc_nearest_code.restype = C.c_uint32
+        L.orc_minmax_level_value.argtypes = [C.c_uint32, C.c_float, C.c_float, C.c_uint32]
+        L.orc_minmax_level_value.restype = C.c_float
+        L.orc_quantize_minmax.argtypes = [f32p, C.c_uint64, C.c_uint32, C.c_uint32, u32p, f32p, u8p]
+        L.orc_quantize_minmax.restype = None
+        L.orc_dequantize_minmax.argtypes = [u32p, f32p, C.c_uint64, C.c_uint32, C.c_uint32, f32p]
+        L.orc_dequantize_minmax.restype = None
+        L.orc_aggregate_update_minmax.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32,
+                                                  C.c_uint32, C.c_float, f32p]
+        L.orc_aggregate_update_minmax.restype = None
         _lib = L
     return _lib
 
@@ -246,4 +259,55 @@ def average_update_raw(grads, lr, params):
     out = np.array(params, dtype=np.float32, copy=True).reshape(-1)
     assert out.size == n and all(g.size == n for g in gs)
     lib().orc_average_update_raw(ga, W, n, float(np.float32(lr)), _p(out, C.c_float))
+    return out
+
+
+# ---- the footnote read literally: deterministic min/max range-linear encode ---------------------------
+
+def minmax_ranges(g, bucket):
+    """Per-bucket [min, max], interleaved: ranges[2k], ranges[2k+1]."""
+    g = _f32(g).reshape(-1)
+    out = np.zeros(2 * num_buckets(g.size, bucket), dtype=np.float32)
+    if g.size:
+        lib().orc_minmax_ranges(_p(g, C.c_float), g.size, bucket, _p(out, C.c_float))
+    return out
+
+
+def nearest_code(x, mn, mx, bits):
+    return int(lib().orc_nearest_code(float(np.float32(x)), float(np.float32(mn)), float(np.float32(mx)), bits))
+
+
+def minmax_level_value(k, mn, mx, bits):
+    return np.float32(lib().orc_minmax_level_value(int(k), float(np.float32(mn)), float(np.float32(mx)), bits))
+
+
+def quantize_minmax(g, bits, bucket, return_codes=False):
+    g = _f32(g).reshape(-1)
+    n = g.size
+    packed = np.zeros(packed_words(n, bits), dtype=np.uint32)
+    ranges = np.zeros(2 * num_buckets(n, bucket), dtype=np.float32)
+    codes = np.zeros(max(n, 1), dtype=np.uint8)
+    if n:
+        lib().orc_quantize_minmax(_p(g, C.c_float), n, bits, bucket, _p(packed, C.c_uint32), _p(ranges, C.c_float),
+                                  _p(codes, C.c_uint8))
+    if return_codes:
+        return packed, ranges, codes[:n]
+    return packed, ranges
+
+
+def dequantize_minmax(packed, ranges, n, bits, bucket):
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    ranges = _f32(ranges)
+    out = np.zeros(n, dtype=np.float32)
+    if n:
+        lib().orc_dequantize_minmax(_p(packed, C.c_uint32), _p(ranges, C.c_float), n, bits, bucket, _p(out, C.c_float))
+    return out
+
+
+def aggregate_update_minmax(packed_list, ranges_list, n, bits, bucket, lr, params):
+    pk, rg, pa, sa = _ptr_arrays(packed_list, ranges_list)
+    out = np.array(params, dtype=np.float32, copy=True).reshape(-1)
+    assert out.size == n
+    lib().orc_aggregate_update_minmax(pa, sa, len(packed_list), n, bits, bucket, float(np.float32(lr)),
+                                      _p(out, C.c_float))
     return out

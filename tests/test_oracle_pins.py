@@ -15,33 +15,13 @@ import numpy as np
 import pytest
 
 from oracle import ref
+from exact_fp32 import f32_round
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 ALL_BITS = list(range(1, 9))
 
 
 # ---- exact helpers (independent of the oracle) -------------------------------------------------
-
-def f32_round(q):
-    """Round an exact rational to the nearest fp32 (ties to even); returns a Fraction."""
-    q = Fraction(q)
-    if q == 0:
-        return Fraction(0)
-    sign = -1 if q < 0 else 1
-    a = abs(q)
-    e = a.numerator.bit_length() - a.denominator.bit_length()
-    if Fraction(2) ** e > a:
-        e -= 1
-    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1)
-    e = max(e, -126)
-    ulp = Fraction(2) ** (e - 23)
-    m = a / ulp
-    fl = m.numerator // m.denominator
-    rem = m - fl
-    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
-        fl += 1
-    return sign * fl * ulp
-
 
 def exact_grid_position(x, s, bits):
     """u of the contract, with every fp32 rounding done in exact rational arithmetic."""
