@@ -45,7 +45,7 @@ extern "C" {
 typedef enum {
     MQG_OK = 0,
     MQG_EINVAL = -1,  /* an argument is out of its documented range, or a required pointer is NULL */
-    MQG_EALIGN = -2,  /* a pointer is not 4-byte aligned */
+    MQG_EALIGN = -2,  /* a pointer is not aligned as its argument requires (4 bytes unless stated) */
     MQG_ELAUNCH = -3  /* the HIP runtime refused the launch (hipGetLastError was consumed) */
 } mqg_status;
 
@@ -184,6 +184,58 @@ typedef struct {
  * Errors: MQG_EINVAL also for count > MQG_MAX_TENSORS or more than MQG_MAX_TENSOR_POINTERS pointers. */
 mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t count, uint32_t W,
                                         uint32_t bits, uint32_t bucket, float lr, void* stream);
+
+/* ---- the Section 3.2 footnote read literally: deterministic range-linear encode over [min, max] ----
+ *
+ * The footnote defines Quantize / De-quantize as a range-linear Encode / Decode: the tensor's range
+ * [min, max] is cut into 2^K - 1 equal steps, a value is stored as the index of the nearest level and
+ * restored as min + index * step.  No random numbers are drawn.  The range is taken per bucket of
+ * `bucket` consecutive elements (bucket >= n: one range per tensor, as in the paper).
+ *
+ *   mn, mx   min and max of the bucket (a zero bound is stored as +0)
+ *   a        fl(L / fl(mx - mn)), L = 2^bits - 1;  0 when the range is below 2^-96 (one level)
+ *   c        clamp(rint(fl(fl(g - mn) * a)), 0, L), ties to the even index
+ *   value    fma((float)c, fl(fl(mx - mn) / L), mn)
+ *
+ *   ranges_out   device, 2 * mqg_num_buckets(n, bucket) floats, 8-byte aligned: (mn, mx) of bucket k
+ *                at [2k], [2k+1].  packed_out as for mqg_quantize (same dense little-endian stream).
+ * Errors as for mqg_quantize (MQG_EALIGN also when ranges_out is not 8-byte aligned). */
+mqg_status mqg_quantize_minmax(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                               uint32_t* packed_out, float* ranges_out, void* stream);
+
+/* Server step for that encoding (Algorithm 1, ReceiveQGThenSendQG + the update of WorkerIterate):
+ * acc = sum over workers, in worker order, of value_w;  params[i] <- fma(-fl(lr / W), acc, params[i]).
+ *   packed, ranges  HOST arrays of W device pointers (streams and (mn, mx) pairs of the workers, the
+ *                   range arrays 8-byte aligned); the arrays may be freed on return.
+ * Errors as for mqg_aggregate_update. */
+mqg_status mqg_aggregate_update_minmax(const uint32_t* const* packed, const float* const* ranges, uint32_t W,
+                                       uint64_t n, uint32_t bits, uint32_t bucket,
+                                       float lr, float* params, void* stream);
+
+/* ---- the "Adaptive" baseline's bit rule (Section 4.1; idea in Section 2: the larger the gradient's
+ * norm, the more bits) ------------------------------------------------------------------------------
+ *
+ * mqg_sum_squares: *sumsq_out <- sum_i grad[i]^2, accumulated in fp64 (squares of fp32 values are
+ * exact in fp64; the order of the partial sums is not fixed, so the result is reproducible to about
+ * 1e-15 relative, not to the bit).  sumsq_out: device, one double, 8-byte aligned, overwritten.
+ * n = 0 stores 0. */
+mqg_status mqg_sum_squares(const float* grad, uint64_t n, double* sumsq_out, void* stream);
+
+typedef struct {
+    uint32_t base_bits;     /* paper: 2 */
+    double norm_per_bit;    /* paper: 0.0005 */
+    uint32_t bits_min;      /* paper: 2 */
+    uint32_t bits_max;      /* paper: 8 */
+} mqg_adaptive_config;
+
+void mqg_adaptive_default_config(mqg_adaptive_config* cfg);
+
+/* Host only.  K = base_bits + floor(Z / norm_per_bit), kept inside [bits_min, bits_max], where Z is
+ * the mean over the W workers of their gradients' L2 norms (worker_norms[w] = sqrt of the sum of
+ * squares of worker w's gradient).  An infinite Z gives bits_max.  MQG_EINVAL for NULL arguments,
+ * W = 0, a negative or NaN norm, norm_per_bit <= 0 or bits_min > bits_max or bits outside 1..8. */
+mqg_status mqg_adaptive_bits(const double* worker_norms, uint32_t W, const mqg_adaptive_config* cfg,
+                             uint32_t* bits_out);
 
 /* ---- host-side agent that chooses K (Section 3.3, Algorithm 2).  No GPU involved. ---------- */
 

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmqgrad.so")
-SOURCES = ["api.hip", "quantize_pack.hip", "quantize_wave.hip", "aggregate_update.hip", "mdp.cpp"]
+SOURCES = ["api.hip", "quantize_pack.hip", "quantize_wave.hip", "aggregate_update.hip", "minmax.hip", "mdp.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

@@ -1,5 +1,5 @@
 // C-ABI layer of libmqgrad: argument validation and launch set-up.  No arithmetic of the method
-// happens here; the kernels are in quantize_pack.hip and aggregate_update.hip.
+// happens here; the kernels are in quantize_pack.hip, quantize_wave.hip, aggregate_update.hip and minmax.hip.
 
 #include "kernels.h"
 
@@ -18,6 +18,7 @@ int log2_if_pow2(uint32_t v) {
 }
 
 bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+bool misaligned8(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 7u) != 0; }
 
 mqg_status quantize_impl(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket, int mode,
                          uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
@@ -61,7 +62,7 @@ const char* mqg_status_string(mqg_status st) {
     switch (st) {
         case MQG_OK: return "MQG_OK";
         case MQG_EINVAL: return "MQG_EINVAL: argument out of range or NULL";
-        case MQG_EALIGN: return "MQG_EALIGN: pointer not 4-byte aligned";
+        case MQG_EALIGN: return "MQG_EALIGN: pointer not aligned as required";
         case MQG_ELAUNCH: return "MQG_ELAUNCH: HIP launch failed";
     }
     return "MQG: unknown status";
@@ -281,6 +282,64 @@ mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t c
     }
     a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
     const hipError_t err = mqg::launch_aggregate_tensors(a, (uint32_t)tiles, aligned, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_quantize_minmax(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                               uint32_t* packed_out, float* ranges_out, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (grad == nullptr || packed_out == nullptr || ranges_out == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(grad) || misaligned4(packed_out) || misaligned8(ranges_out)) return MQG_EALIGN;
+    mqg::QuantizeArgs a = {};
+    a.grad = grad;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.packed = packed_out;
+    a.scales = ranges_out;
+    const hipError_t err = mqg::launch_quantize_minmax(a, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_aggregate_update_minmax(const uint32_t* const* packed, const float* const* ranges, uint32_t W,
+                                       uint64_t n, uint32_t bits, uint32_t bucket,
+                                       float lr, float* params, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (packed == nullptr || ranges == nullptr || params == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(params)) return MQG_EALIGN;
+    mqg::AggregateArgs a;
+    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
+        a.packed[w] = nullptr;
+        a.scales[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
+        a.packed[w] = packed[w];
+        a.scales[w] = ranges[w];
+    }
+    a.W = W;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.neg_c = -(lr / (float)W);
+    a.params = params;
+    const hipError_t err = mqg::launch_aggregate_minmax(a, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_sum_squares(const float* grad, uint64_t n, double* sumsq_out, void* stream) {
+    if (sumsq_out == nullptr || (n > 0 && grad == nullptr)) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if ((n > 0 && misaligned4(grad)) || misaligned8(sumsq_out)) return MQG_EALIGN;
+    const hipError_t err = mqg::launch_sum_squares(grad, n, sumsq_out, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 

@@ -69,11 +69,9 @@ __device__ __forceinline__ void fetch_codes(const uint32_t* const* packed, uint3
     }
 }
 
-// One worker's 4 codes of one quad, de-quantized with step d and accumulated:
-// acc <- fma((float)(2c - L), d, acc), the ordered chain of the server's sum.
+// The 4 codes of one quad of one worker, from the quad's first word `lo` and its bit offset `sh`.
 template <bool STRADDLE>
-__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32_t b, int negL,
-                                                float d, float4& acc) {
+__device__ __forceinline__ void extract_quad(uint32_t lo, uint32_t sh, uint32_t b, int (&k)[4]) {
     uint32_t v, o;
     if (STRADDLE) {
         // A quad that spills over its first word continues in the first word of the next lane (that
@@ -87,14 +85,35 @@ __device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32
         v = lo;
         o = sh;
     }
-    const int k0 = (int)__builtin_amdgcn_ubfe(v, o, b);
-    const int k1 = (int)__builtin_amdgcn_ubfe(v, o + b, b);
-    const int k2 = (int)__builtin_amdgcn_ubfe(v, o + 2u * b, b);
-    const int k3 = (int)__builtin_amdgcn_ubfe(v, o + 3u * b, b);
-    acc.x = __builtin_fmaf((float)(2 * k0 + negL), d, acc.x);
-    acc.y = __builtin_fmaf((float)(2 * k1 + negL), d, acc.y);
-    acc.z = __builtin_fmaf((float)(2 * k2 + negL), d, acc.z);
-    acc.w = __builtin_fmaf((float)(2 * k3 + negL), d, acc.w);
+    k[0] = (int)__builtin_amdgcn_ubfe(v, o, b);
+    k[1] = (int)__builtin_amdgcn_ubfe(v, o + b, b);
+    k[2] = (int)__builtin_amdgcn_ubfe(v, o + 2u * b, b);
+    k[3] = (int)__builtin_amdgcn_ubfe(v, o + 3u * b, b);
+}
+
+// One worker's 4 codes of one quad, de-quantized with step d and accumulated:
+// acc <- fma((float)(2c - L), d, acc), the ordered chain of the server's sum.
+template <bool STRADDLE>
+__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32_t b, int negL,
+                                                float d, float4& acc) {
+    int k[4];
+    extract_quad<STRADDLE>(lo, sh, b, k);
+    acc.x = __builtin_fmaf((float)(2 * k[0] + negL), d, acc.x);
+    acc.y = __builtin_fmaf((float)(2 * k[1] + negL), d, acc.y);
+    acc.z = __builtin_fmaf((float)(2 * k[2] + negL), d, acc.z);
+    acc.w = __builtin_fmaf((float)(2 * k[3] + negL), d, acc.w);
+}
+
+// The same for the [min, max] encoding: value = fma((float)c, step, min), acc <- acc + value.
+template <bool STRADDLE>
+__device__ __forceinline__ void accumulate_quad_minmax(uint32_t lo, uint32_t sh, uint32_t b, float step,
+                                                       float mn, float4& acc) {
+    int k[4];
+    extract_quad<STRADDLE>(lo, sh, b, k);
+    acc.x = acc.x + __builtin_fmaf((float)k[0], step, mn);
+    acc.y = acc.y + __builtin_fmaf((float)k[1], step, mn);
+    acc.z = acc.z + __builtin_fmaf((float)k[2], step, mn);
+    acc.w = acc.w + __builtin_fmaf((float)k[3], step, mn);
 }
 
 __device__ __forceinline__ float readlane_f32(float v, uint32_t lane) {

@@ -248,4 +248,37 @@ double mqg_mdp_last_reward(const mqg_mdp* agent) { return agent ? agent->last_re
 
 uint64_t mqg_mdp_decisions(const mqg_mdp* agent) { return agent ? agent->decisions : 0u; }
 
+// ---- the "Adaptive" baseline's rule (Section 4.1): bits from the mean gradient norm ----------------
+
+void mqg_adaptive_default_config(mqg_adaptive_config* cfg) {
+    if (!cfg) return;
+    cfg->base_bits = 2;
+    cfg->norm_per_bit = 0.0005;
+    cfg->bits_min = 2;
+    cfg->bits_max = 8;
+}
+
+mqg_status mqg_adaptive_bits(const double* worker_norms, uint32_t W, const mqg_adaptive_config* cfg,
+                             uint32_t* bits_out) {
+    if (!worker_norms || !cfg || !bits_out || W == 0u) return MQG_EINVAL;
+    if (!(cfg->norm_per_bit > 0.0) || cfg->bits_min < 1u || cfg->bits_max > 8u || cfg->bits_min > cfg->bits_max ||
+        cfg->base_bits > 8u)
+        return MQG_EINVAL;
+    double z = 0.0;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!(worker_norms[w] >= 0.0)) return MQG_EINVAL;   // negative or NaN
+        z = z + worker_norms[w];
+    }
+    z = z / (double)W;
+    uint32_t k = cfg->bits_max;
+    if (std::isfinite(z)) {
+        const double extra = std::floor(z / cfg->norm_per_bit);
+        if (extra < 16.0) k = cfg->base_bits + (uint32_t)extra;
+    }
+    if (k < cfg->bits_min) k = cfg->bits_min;
+    if (k > cfg->bits_max) k = cfg->bits_max;
+    *bits_out = k;
+    return MQG_OK;
+}
+
 }  // extern "C"

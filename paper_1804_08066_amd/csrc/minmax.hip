@@ -1,0 +1,348 @@
+// The Section 3.2 footnote read literally, on gfx950: a deterministic range-linear encode of a
+// gradient to K bits over the [min, max] of each bucket (bucket >= n: one range per tensor, as in the
+// paper), the matching server step, and the sum of squares that the "Adaptive" baseline's bit rule
+// (Section 4.1) needs.
+//
+//   encode   mn, mx per bucket;  a = L / (mx - mn);  c = clamp(rint((g - mn) * a), 0, L)
+//   decode   value = fma((float)c, (mx - mn) / L, mn)
+//   server   acc = sum_w value_w (worker order);  p <- fma(-(lr/W), acc, p)
+//
+// No random numbers.  Work decomposition as in the stochastic quantizer's workgroup-cooperative
+// kernel: 256 lanes own one tile of whole buckets (at most 1024*R elements, R float4 per lane, read
+// from HBM once), ranges go through LDS with order-preserving integer keys, codes are packed through
+// LDS and whole words are stored coalesced.
+
+#include "decode.h"
+#include "encode.h"
+#include "kernels.h"
+#include "tile_io.h"
+
+namespace mqg {
+namespace {
+
+using namespace encode;
+using tile_io::kThreads;
+
+constexpr int kChunk = 8;   // workers whose code loads are in flight together
+
+// fp32 -> uint32 whose unsigned order is the order of the floats
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return u ^ (uint32_t)(((int)u >> 31) | (int)0x80000000);
+}
+__device__ __forceinline__ float key_value(uint32_t k) {
+    const uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+    return __builtin_bit_cast(float, u);
+}
+
+template <int R>
+struct Shared {
+    static constexpr uint32_t kCap = 1024u * R;
+    uint32_t words[kCap * 8u / 32u + 4];
+    uint32_t kmin[128];
+    uint32_t kmax[128];
+    float mn[128];
+    float a[128];
+};
+
+template <int R, bool ALIGNED, bool FULL>
+__device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
+                                                     const uint32_t tile_count, Shared<R>& sm) {
+    const uint32_t tid = threadIdx.x;
+    const float* __restrict__ g = a.grad + tile_base;
+    const float inf = __builtin_inff();
+
+    // ---- one HBM pass: the tile into registers ----------------------------------------------
+    float4 x[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t el = 4u * (j * kThreads + tid);
+        if (FULL || el + 4u <= tile_count) {
+            if (ALIGNED) {
+                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + el));
+                x[j] = make_float4(t.x, t.y, t.z, t.w);
+            } else {
+                x[j] = make_float4(g[el], g[el + 1], g[el + 2], g[el + 3]);
+            }
+        } else {
+            x[j].x = (el + 0u < tile_count) ? g[el + 0] : 0.0f;
+            x[j].y = (el + 1u < tile_count) ? g[el + 1] : 0.0f;
+            x[j].z = (el + 2u < tile_count) ? g[el + 2] : 0.0f;
+            x[j].w = 0.0f;   // el + 3 >= tile_count here
+        }
+    }
+    const uint32_t b = a.bits;
+    const uint32_t nwords = (tile_count * b + 31u) >> 5;
+    for (uint32_t i = tid; i < nwords; i += kThreads) sm.words[i] = 0u;
+    if (tid < 128u) {
+        sm.kmin[tid] = 0xFFFFFFFFu;
+        sm.kmax[tid] = 0u;
+    }
+    __syncthreads();
+
+    const uint32_t nbt = (R > 4) ? 1u : (tile_count + a.bucket - 1u) / a.bucket;   // buckets in the tile
+    const uint64_t kb0 = tile_base / a.bucket;
+    uint32_t bl[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t el = 4u * (j * kThreads + tid);
+        bl[j] = (R > 4) ? 0u : (a.bucket_shift >= 0 ? (el >> a.bucket_shift) : (el / a.bucket));
+    }
+
+    // ---- bucket range: 8-lane cells by DPP, cells into the bucket's LDS slot ----------------
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t el = 4u * (j * kThreads + tid);
+        float lo, hi;
+        if (FULL) {
+            lo = fminf(fminf(x[j].x, x[j].y), fminf(x[j].z, x[j].w));
+            hi = fmaxf(fmaxf(x[j].x, x[j].y), fmaxf(x[j].z, x[j].w));
+        } else {   // elements past the end take no part
+            const bool v0 = el + 0u < tile_count, v1 = el + 1u < tile_count;
+            const bool v2 = el + 2u < tile_count, v3 = el + 3u < tile_count;
+            lo = fminf(fminf(v0 ? x[j].x : inf, v1 ? x[j].y : inf), fminf(v2 ? x[j].z : inf, v3 ? x[j].w : inf));
+            hi = fmaxf(fmaxf(v0 ? x[j].x : -inf, v1 ? x[j].y : -inf), fmaxf(v2 ? x[j].z : -inf, v3 ? x[j].w : -inf));
+        }
+        lo = fminf(lo, dpp_f32<kDppQuadSwap1>(lo));
+        hi = fmaxf(hi, dpp_f32<kDppQuadSwap1>(hi));
+        lo = fminf(lo, dpp_f32<kDppQuadSwap2>(lo));
+        hi = fmaxf(hi, dpp_f32<kDppQuadSwap2>(hi));
+        lo = fminf(lo, dpp_f32<kDppRowHalfMirror>(lo));
+        hi = fmaxf(hi, dpp_f32<kDppRowHalfMirror>(hi));
+        if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
+            atomicMin(&sm.kmin[bl[j]], order_key(lo));
+            atomicMax(&sm.kmax[bl[j]], order_key(hi));
+        }
+    }
+    __syncthreads();
+
+    const float Lf = (float)((1u << b) - 1u);
+    if (tid < nbt) {
+        float mn = key_value(sm.kmin[tid]), mx = key_value(sm.kmax[tid]);
+        if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
+        if (mx == 0.0f) mx = 0.0f;
+        a.scales[2u * (kb0 + tid)] = mn;
+        a.scales[2u * (kb0 + tid) + 1u] = mx;
+        const float r = mx - mn;
+        sm.mn[tid] = mn;
+        sm.a[tid] = (r >= 0x1p-96f) ? Lf / r : 0.0f;   // IEEE-correct fp32 division, once per bucket
+    }
+    __syncthreads();
+
+    // ---- nearest level, packing -----------------------------------------------------------------
+    const uint32_t cell_bit = 4u * b * (tid & 7u);            // this lane's bit offset in its 32-element cell
+    const uint32_t sh = cell_bit & 31u;
+    const uint32_t word_in_cell = cell_bit >> 5;
+    const bool straddle = sh + 4u * b > 32u;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t ql = j * kThreads + tid;
+        const uint32_t el = 4u * ql;
+        const float mn = sm.mn[bl[j]], ai = sm.a[bl[j]];
+        // fmaxf drops a NaN position to 0; positions are integers after rint
+        uint32_t k0 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].x - mn) * ai), 0.0f), Lf);
+        uint32_t k1 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].y - mn) * ai), 0.0f), Lf);
+        uint32_t k2 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].z - mn) * ai), 0.0f), Lf);
+        uint32_t k3 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].w - mn) * ai), 0.0f), Lf);
+        if (!FULL) {   // elements past the end contribute zero bits
+            if (el + 0u >= tile_count) k0 = 0u;
+            if (el + 1u >= tile_count) k1 = 0u;
+            if (el + 2u >= tile_count) k2 = 0u;
+            if (el + 3u >= tile_count) k3 = 0u;
+        }
+        const uint32_t v = (((((k3 << b) | k2) << b) | k1) << b) | k0;
+        if (FULL || el < tile_count) {
+            const uint32_t w0 = (ql >> 3) * b + word_in_cell;
+            atomicOr(&sm.words[w0], v << sh);
+            if (straddle) atomicOr(&sm.words[w0 + 1u], v >> (32u - sh));
+        }
+    }
+    __syncthreads();
+
+    uint32_t* __restrict__ out = a.packed + (tile_base >> 5) * b;
+    for (uint32_t i = tid; i < nwords; i += kThreads) __builtin_nontemporal_store(sm.words[i], out + i);
+}
+
+template <int R, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
+    __shared__ Shared<R> sm;
+    const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
+    const uint64_t left = a.n - tile_base;
+    const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
+    if (tile_count == Shared<R>::kCap) {
+        quantize_minmax_tile<R, ALIGNED, true>(a, tile_base, tile_count, sm);
+    } else {
+        quantize_minmax_tile<R, ALIGNED, false>(a, tile_base, tile_count, sm);
+    }
+}
+
+// ---- server step --------------------------------------------------------------------------------
+constexpr int kAggR = 2;
+constexpr uint32_t kAggTile = 1024u * kAggR;
+constexpr uint32_t kMaxBuckets = kAggTile / 32u + 1u;   // buckets a tile can touch
+
+template <bool STRADDLE, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const AggregateArgs a) {
+    extern __shared__ float2 s_tab[];   // [W][nbt]: (step, min) of each worker's buckets of the tile
+    constexpr int R = kAggR;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t tile_base = (uint64_t)blockIdx.x * kAggTile;
+    const uint64_t left = a.n - tile_base;
+    const uint32_t tile_count = left < kAggTile ? (uint32_t)left : kAggTile;
+    const bool full = tile_count == kAggTile;
+    float* __restrict__ p = a.params + tile_base;
+
+    float4 x[R];
+    tile_io::load_params<R, ALIGNED>(p, tile_count, full, x);
+    float4 acc[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+    const uint32_t b = a.bits;
+    const float Lf = (float)((1u << b) - 1u);
+    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
+    decode::CodeRegs<R, kChunk> c;
+    decode::fetch_codes<R, kChunk>(a.packed, a.W, 0u, cw, c);   // in flight while the table is filled
+
+    const uint64_t kb0 = tile_base / a.bucket;
+    const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
+    const uint32_t first_off = (uint32_t)(tile_base - kb0 * a.bucket);
+    uint32_t bl[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t eo = 4u * (j * kThreads + tid) + first_off;
+        bl[j] = a.bucket_shift >= 0 ? (eo >> a.bucket_shift) : (eo / a.bucket);
+        if (bl[j] >= nbt) bl[j] = nbt - 1u;   // quads past the end: any valid slot
+    }
+    for (uint32_t i = tid; i < a.W * nbt; i += kThreads) {
+        const uint32_t w = i / nbt, kb = i - w * nbt;
+        const float2 rg = reinterpret_cast<const float2*>(a.scales[w])[kb0 + kb];   // (min, max)
+        s_tab[i] = make_float2((rg.y - rg.x) / Lf, rg.x);                           // IEEE-correct fp32 division
+    }
+    __syncthreads();
+
+    for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
+        if (w0 > 0) decode::fetch_codes<R, kChunk>(a.packed, a.W, w0, cw, c);
+#pragma unroll
+        for (int t = 0; t < kChunk; ++t) {
+            if (w0 + t < a.W) {
+                const float2* __restrict__ tw = s_tab + (w0 + t) * nbt;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    const float2 sl = tw[bl[j]];
+                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh[j], b, sl.x, sl.y, acc[j]);
+                }
+            }
+        }
+    }
+    tile_io::update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+}
+
+// ---- sum of squares -------------------------------------------------------------------------------
+// Squares of fp32 values are exact in fp64; every lane adds its share in fp64, lanes and waves are
+// combined by a butterfly and through LDS, and each workgroup adds one fp64 number to *out (whose
+// rounding depends on the order in which the workgroups arrive: about 1e-16 relative).
+constexpr uint32_t kSumBlocks = 2048;
+
+__global__ void clear_f64_kernel(double* out) { *out = 0.0; }
+
+__global__ __launch_bounds__(kThreads) void sum_squares_kernel(const float* __restrict__ g, const uint64_t n,
+                                                               const uint32_t head, double* out) {
+    __shared__ double s_part[kThreads / 64];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t gtid = (uint64_t)blockIdx.x * kThreads + tid;
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    double acc = 0.0;
+    // `head` leading elements bring the rest to a 16-byte boundary
+    if (gtid < head) {
+        const double v = (double)g[gtid];
+        acc += v * v;
+    }
+    const v4f* __restrict__ g4 = reinterpret_cast<const v4f*>(g + head);
+    const uint64_t nq = (n - head) >> 2;
+    for (uint64_t q = gtid; q < nq; q += stride) {
+        const v4f t = __builtin_nontemporal_load(g4 + q);
+        const double a0 = (double)t.x, a1 = (double)t.y, a2 = (double)t.z, a3 = (double)t.w;
+        acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+    const uint64_t tail0 = head + (nq << 2);
+    if (gtid < n - tail0) {
+        const double v = (double)g[tail0 + gtid];
+        acc += v * v;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if ((tid & 63u) == 0u) s_part[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0u) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) t += s_part[w];
+        atomicAdd(out, t);
+    }
+}
+
+template <int R>
+hipError_t launch_quantize_r(const QuantizeArgs& a, hipStream_t stream) {
+    const uint32_t cap = Shared<R>::kCap;
+    const uint32_t tile_elems = (cap / a.bucket) * a.bucket;   // whole buckets, >= 1 by choice of R
+    const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
+    const dim3 grid((uint32_t)tiles), block(kThreads);
+    if (aligned) {
+        hipLaunchKernelGGL((quantize_minmax_kernel<R, true>), grid, block, 0, stream, a, tile_elems);
+    } else {
+        hipLaunchKernelGGL((quantize_minmax_kernel<R, false>), grid, block, 0, stream, a, tile_elems);
+    }
+    return hipGetLastError();
+}
+
+template <bool STRADDLE>
+hipError_t launch_aggregate_s(const AggregateArgs& a, hipStream_t stream) {
+    const uint64_t tiles = (a.n + kAggTile - 1) / kAggTile;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
+    const dim3 grid((uint32_t)tiles), block(kThreads);
+    const size_t lds = sizeof(float2) * a.W * kMaxBuckets;
+    if (aligned) {
+        hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true>), grid, block, lds, stream, a);
+    } else {
+        hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false>), grid, block, lds, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// a.scales: 2 floats (min, max) per bucket; a.scale_mode, key, iteration, worker, elem_base unused
+hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream) {
+    if (a.n == 0) return hipSuccess;
+    if (a.bucket <= 4096u) return launch_quantize_r<4>(a, stream);
+    if (a.bucket <= 8192u) return launch_quantize_r<8>(a, stream);
+    return launch_quantize_r<16>(a, stream);
+}
+
+// a.scales[w]: worker w's (min, max) pairs
+hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream) {
+    if (a.n == 0) return hipSuccess;
+    const bool straddle = (32u % a.bits) != 0u;
+    return straddle ? launch_aggregate_s<true>(a, stream) : launch_aggregate_s<false>(a, stream);
+}
+
+hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream) {
+    hipLaunchKernelGGL(clear_f64_kernel, dim3(1), dim3(1), 0, stream, out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n == 0) return e;
+    const uint64_t mis = (reinterpret_cast<uintptr_t>(grad) & 15u) >> 2;     // floats past a 16-byte boundary
+    uint32_t head = mis ? (uint32_t)(4u - mis) : 0u;
+    if (head > n) head = (uint32_t)n;
+    const uint64_t quads = (n - head) >> 2;
+    uint64_t blocks = (quads + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > kSumBlocks) blocks = kSumBlocks;
+    hipLaunchKernelGGL(sum_squares_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, grad, n, head, out);
+    return hipGetLastError();
+}
+
+}  // namespace mqg

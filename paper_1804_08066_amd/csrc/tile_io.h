@@ -1,0 +1,73 @@
+// Streaming tile loads and stores of fp32 parameters (step a7 of the hot path), shared by the server
+// kernels: a workgroup of 256 lanes owns R rows of 1024 consecutive values, one float4 per lane and row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mqg {
+namespace tile_io {
+
+constexpr int kThreads = 256;
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 load_f4_stream(const float* p) {
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void store_f4_stream(float* p, const float4& r) {
+    v4f t = {r.x, r.y, r.z, r.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+}
+
+template <int R, bool ALIGNED>
+__device__ __forceinline__ void load_params(const float* __restrict__ p, uint32_t tile_count, bool full,
+                                            float4 (&x)[R]) {
+    const uint32_t tid = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t el = 4u * (j * kThreads + tid);
+        if (full || el + 4u <= tile_count) {
+            if (ALIGNED) {
+                x[j] = load_f4_stream(p + el);
+            } else {
+                x[j] = make_float4(p[el], p[el + 1], p[el + 2], p[el + 3]);
+            }
+        } else {
+            x[j].x = (el + 0u < tile_count) ? p[el + 0] : 0.0f;
+            x[j].y = (el + 1u < tile_count) ? p[el + 1] : 0.0f;
+            x[j].z = (el + 2u < tile_count) ? p[el + 2] : 0.0f;
+            x[j].w = 0.0f;   // el + 3 >= tile_count here
+        }
+    }
+}
+
+// a7: p <- fma(-(lr/W), acc, p)
+template <int R, bool ALIGNED>
+__device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t tile_count, bool full, float neg_c,
+                                              const float4 (&x)[R], const float4 (&acc)[R]) {
+    const uint32_t tid = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t el = 4u * (j * kThreads + tid);
+        float4 r;
+        r.x = __builtin_fmaf(neg_c, acc[j].x, x[j].x);
+        r.y = __builtin_fmaf(neg_c, acc[j].y, x[j].y);
+        r.z = __builtin_fmaf(neg_c, acc[j].z, x[j].z);
+        r.w = __builtin_fmaf(neg_c, acc[j].w, x[j].w);
+        if (full || el + 4u <= tile_count) {
+            if (ALIGNED) {
+                store_f4_stream(p + el, r);
+            } else {
+                p[el] = r.x; p[el + 1] = r.y; p[el + 2] = r.z; p[el + 3] = r.w;
+            }
+        } else {
+            if (el + 0u < tile_count) p[el + 0] = r.x;
+            if (el + 1u < tile_count) p[el + 1] = r.y;
+            if (el + 2u < tile_count) p[el + 2] = r.z;
+        }
+    }
+}
+
+}  // namespace tile_io
+}  // namespace mqg

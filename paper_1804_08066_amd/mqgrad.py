@@ -19,6 +19,8 @@ EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
     "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
+    "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_sum_squares", "mqg_adaptive_default_config",
+    "mqg_adaptive_bits",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
 ]
@@ -35,6 +37,11 @@ class MdpConfig(C.Structure):
                 ("window", C.c_uint32), ("decide_every", C.c_uint32), ("hidden", C.c_uint32),
                 ("alpha", C.c_double), ("epsilon", C.c_double), ("eta", C.c_double),
                 ("reward_scale", C.c_double), ("discount", C.c_double)]
+
+
+class AdaptiveConfig(C.Structure):
+    _fields_ = [("base_bits", C.c_uint32), ("norm_per_bit", C.c_double), ("bits_min", C.c_uint32),
+                ("bits_max", C.c_uint32)]
 
 
 class QuantizeItem(C.Structure):
@@ -84,6 +91,16 @@ def lib():
     L.mqg_quantize_tensors.restype = C.c_int
     L.mqg_aggregate_update_tensors.argtypes = [C.POINTER(UpdateItem), u32, u32, u32, u32, f32, vp]
     L.mqg_aggregate_update_tensors.restype = C.c_int
+    L.mqg_quantize_minmax.argtypes = [vp, u64, u32, u32, vp, vp, vp]
+    L.mqg_quantize_minmax.restype = C.c_int
+    L.mqg_aggregate_update_minmax.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, vp]
+    L.mqg_aggregate_update_minmax.restype = C.c_int
+    L.mqg_sum_squares.argtypes = [vp, u64, vp, vp]
+    L.mqg_sum_squares.restype = C.c_int
+    L.mqg_adaptive_default_config.argtypes = [C.POINTER(AdaptiveConfig)]
+    L.mqg_adaptive_default_config.restype = None
+    L.mqg_adaptive_bits.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(AdaptiveConfig), C.POINTER(u32)]
+    L.mqg_adaptive_bits.restype = C.c_int
     L.mqg_mdp_default_config.argtypes = [C.POINTER(MdpConfig)]
     L.mqg_mdp_default_config.restype = None
     L.mqg_mdp_create.argtypes = [C.POINTER(MdpConfig)]
@@ -293,6 +310,73 @@ def mqg_aggregate_update_tensors(layers, W, bits, bucket, lr, stream=None):
     st = lib().mqg_aggregate_update_tensors(items, count, W, bits, bucket, lr, _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_update_tensors")
+
+
+def mqg_quantize_minmax(grad, bits, bucket, packed_out=None, ranges_out=None, stream=None):
+    """Deterministic [min, max] range-linear encode. Returns (packed int32 words, ranges fp32 (min, max) pairs)."""
+    _check(grad, torch.float32, "grad")
+    n = grad.numel()
+    if packed_out is None:
+        packed_out = torch.empty(mqg_packed_words(n, bits), dtype=torch.int32, device=grad.device)
+    if ranges_out is None:
+        ranges_out = torch.empty(2 * mqg_num_buckets(n, bucket), dtype=torch.float32, device=grad.device)
+    _check(packed_out, torch.int32, "packed_out")
+    _check(ranges_out, torch.float32, "ranges_out")
+    if packed_out.numel() < mqg_packed_words(n, bits) or ranges_out.numel() < 2 * mqg_num_buckets(n, bucket):
+        raise ValueError("output buffers too small")
+    st = lib().mqg_quantize_minmax(grad.data_ptr(), n, bits, bucket, packed_out.data_ptr(), ranges_out.data_ptr(),
+                                   _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_quantize_minmax")
+    return packed_out, ranges_out
+
+
+def mqg_aggregate_update_minmax(packed, ranges, n, bits, bucket, lr, params, stream=None):
+    _check(params, torch.float32, "params")
+    if params.numel() != n:
+        raise ValueError("params must have n elements")
+    W = len(packed)
+    if W != len(ranges):
+        raise ValueError("packed and ranges must have one entry per worker")
+    for p, r in zip(packed, ranges):
+        _check(p, torch.int32, "packed[w]")
+        _check(r, torch.float32, "ranges[w]")
+        if p.numel() < mqg_packed_words(n, bits) or r.numel() < 2 * mqg_num_buckets(n, bucket):
+            raise ValueError("a worker's buffers are too small for n")
+    pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    ra = (C.c_void_p * max(W, 1))(*[r.data_ptr() for r in ranges])
+    st = lib().mqg_aggregate_update_minmax(pa, ra, W, n, bits, bucket, lr, params.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_update_minmax")
+
+
+def mqg_sum_squares(grad, out=None, stream=None):
+    """Sum of squares of a gradient in fp64, into a one-element float64 device tensor."""
+    _check(grad, torch.float32, "grad")
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=grad.device)
+    _check(out, torch.float64, "out")
+    st = lib().mqg_sum_squares(grad.data_ptr(), grad.numel(), out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_sum_squares")
+    return out
+
+
+def mqg_adaptive_bits(worker_norms, **overrides):
+    """Host only: the Adaptive baseline's width from the workers' gradient norms."""
+    cfg = AdaptiveConfig()
+    lib().mqg_adaptive_default_config(C.byref(cfg))
+    for k, v in overrides.items():
+        if not hasattr(cfg, k):
+            raise TypeError("unknown adaptive option " + k)
+        setattr(cfg, k, v)
+    W = len(worker_norms)
+    arr = (C.c_double * max(W, 1))(*[float(v) for v in worker_norms])
+    out = C.c_uint32(0)
+    st = lib().mqg_adaptive_bits(arr, W, C.byref(cfg), C.byref(out))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_adaptive_bits")
+    return int(out.value)
 
 
 class Mdp:

@@ -85,3 +85,68 @@ def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(TypeError):
         mqgrad.mqg_quantize(torch.zeros(64), 4, 32, 0)
+
+
+def test_multi_tensor_and_minmax_arguments_are_rejected_before_any_launch():
+    L = mqgrad.lib()
+    vp = C.c_void_p
+    fake = vp(0x1000)
+    one = (vp * 1)(0x1000)
+    # several tensors per launch
+    items = (mqgrad.QuantizeItem * 2)()
+    items[0] = mqgrad.QuantizeItem(0x1000, 64, 0, 0x2000, 0x3000)
+    items[1] = mqgrad.QuantizeItem(0x1000, 64, 4, 0x2000, 0x3000)          # elem_base not a multiple of 8
+    assert L.mqg_quantize_tensors(items, 2, 4, 512, 0, 0, 0, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_quantize_tensors(items, 1, 0, 512, 0, 0, 0, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_quantize_tensors(items, 33, 4, 512, 0, 0, 0, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_quantize_tensors(None, 1, 4, 512, 0, 0, 0, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_quantize_tensors(items, 0, 4, 512, 0, 0, 0, None) == mqgrad.MQG_OK
+    items[0] = mqgrad.QuantizeItem(0x1002, 64, 0, 0x2000, 0x3000)
+    assert L.mqg_quantize_tensors(items, 1, 4, 512, 0, 0, 0, None) == mqgrad.MQG_EALIGN
+    up = (mqgrad.UpdateItem * 1)()
+    up[0] = mqgrad.UpdateItem(64, 0x1000, None, None, None)                 # neither quantized nor raw
+    assert L.mqg_aggregate_update_tensors(up, 1, 1, 4, 512, 0.1, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_aggregate_update_tensors(up, 1, 0, 4, 512, 0.1, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_aggregate_update_tensors(up, 0, 1, 4, 512, 0.1, None) == mqgrad.MQG_OK
+    # deterministic [min, max] encoding
+    q = lambda grad=fake, n=64, bits=4, bucket=512, packed=fake, ranges=fake: \
+        L.mqg_quantize_minmax(grad, n, bits, bucket, packed, ranges, None)
+    assert q(bits=9) == mqgrad.MQG_EINVAL
+    assert q(bucket=40) == mqgrad.MQG_EINVAL
+    assert q(grad=None) == mqgrad.MQG_EINVAL
+    assert q(ranges=None) == mqgrad.MQG_EINVAL
+    assert q(ranges=vp(0x1004)) == mqgrad.MQG_EALIGN                        # pairs are read 8 bytes at a time
+    assert q(n=0, grad=None, packed=None, ranges=None) == mqgrad.MQG_OK
+    a = lambda packed=one, ranges=one, W=1, n=64, bits=4, bucket=512, params=fake: \
+        L.mqg_aggregate_update_minmax(packed, ranges, W, n, bits, bucket, 0.1, params, None)
+    assert a(W=0) == mqgrad.MQG_EINVAL
+    assert a(W=65) == mqgrad.MQG_EINVAL
+    assert a(params=None) == mqgrad.MQG_EINVAL
+    assert a(ranges=(vp * 1)(0x1004)) == mqgrad.MQG_EALIGN
+    assert a(ranges=(vp * 1)(None)) == mqgrad.MQG_EINVAL
+    assert a(n=0, params=None) == mqgrad.MQG_OK
+    assert L.mqg_sum_squares(fake, 10, None, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_sum_squares(None, 10, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_sum_squares(fake, 10, vp(0x1004), None) == mqgrad.MQG_EALIGN
+
+
+def test_adaptive_rule_matches_the_oracle_rule():
+    # host-only policy: the library's rule against the oracle's statement of it, over a dense sweep
+    from oracle import policy_ref
+    import random
+    rnd = random.Random(5)
+    for i in range(3000):
+        W = rnd.randint(1, 12)
+        norms = [rnd.random() * 10 ** rnd.uniform(-5, -2) for _ in range(W)]
+        assert mqgrad.mqg_adaptive_bits(norms) == policy_ref.adaptive_bits(norms)
+    for z in [0.0, 0.0005, 0.001, 0.0015, 0.002, 0.0025, 0.003, 0.0035, 1.0, float("inf")]:
+        assert mqgrad.mqg_adaptive_bits([z]) == policy_ref.adaptive_bits([z])
+        assert mqgrad.mqg_adaptive_bits([z], bits_min=1, bits_max=6, base_bits=1) == \
+            policy_ref.adaptive_bits([z], base_bits=1, bits_min=1, bits_max=6)
+    for bad in ([], [-1.0], [float("nan")]):
+        with pytest.raises(mqgrad.MqgError):
+            mqgrad.mqg_adaptive_bits(bad)
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_adaptive_bits([0.1], norm_per_bit=0.0)
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_adaptive_bits([0.1], bits_min=5, bits_max=4)

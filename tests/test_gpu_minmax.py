@@ -1,0 +1,135 @@
+"""GPU parity for the deterministic [min, max] range-linear encoding (the literal reading of the
+Section 3.2 footnote), its server step, the sum of squares and the Adaptive rule fed from it."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import policy_ref, ref
+from paper_1804_08066_amd import mqgrad, workloads
+from helpers import first_mismatch, to_u32, ulp_distance
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ALL_BITS = list(range(1, 9))
+
+
+def assert_minmax_parity(g, bits, bucket, label=""):
+    pk, rg = mqgrad.mqg_quantize_minmax(g, bits, bucket)
+    torch.cuda.synchronize()
+    pk_o, rg_o = ref.quantize_minmax(g.cpu().numpy(), bits, bucket)
+    assert rg.cpu().numpy().tobytes() == rg_o.tobytes(), "%s ranges differ" % label
+    assert np.array_equal(to_u32(pk), pk_o), "%s packed words differ at %s" % (label, first_mismatch(to_u32(pk), pk_o))
+    return pk, rg, pk_o, rg_o
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("bucket", [32, 96, 512, 4096, 8192, 16384])
+def test_quantize_minmax_bit_exact(bits, bucket):
+    n = 3 * 16384 + 4096 + 37            # several tiles and a ragged tail for every bucket size
+    g = workloads.normal_with_outliers(n, 0.01, 1e-3, 30.0, 11 + bits, DEV) + 0.003
+    assert_minmax_parity(g, bits, bucket, "b=%d B=%d" % (bits, bucket))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 31, 32, 33, 127, 1023, 1025, 4097])
+def test_quantize_minmax_tiny_and_ragged(n):
+    g = workloads.laplace(n, 1e-3, n, DEV)
+    for bits in (1, 3, 8):
+        for bucket in (32, 1024):
+            assert_minmax_parity(g, bits, bucket, "n=%d b=%d B=%d" % (n, bits, bucket))
+
+
+def test_quantize_minmax_degenerate_inputs():
+    n = 5000
+    const = torch.full((n,), 0.37, device=DEV)
+    zeros = torch.zeros(n, device=DEV)
+    negz = -torch.zeros(n, device=DEV)
+    pos = workloads.uniform(n, 0.5, 3.0, 2, DEV)
+    neg = -pos
+    tiny = workloads.uniform(n, 0.0, 1.0, 3, DEV) * 2.0 ** -100
+    ints = torch.randint(0, 256, (n,), device=DEV, generator=torch.Generator(device=DEV).manual_seed(1)).float()
+    for name, g in [("const", const), ("zeros", zeros), ("negz", negz), ("pos", pos), ("neg", neg), ("tiny", tiny),
+                    ("ints", ints)]:
+        for bits in (1, 4, 8):
+            assert_minmax_parity(g, bits, 256, name)
+    # empty input: no launch, nothing written
+    pk, rg = mqgrad.mqg_quantize_minmax(torch.empty(0, device=DEV), 4, 256)
+    assert pk.numel() == 0 and rg.numel() == 0
+
+
+def test_quantize_minmax_unaligned_views():
+    base = workloads.normal(40000, 0.01, 9, DEV)
+    for off in (1, 2, 3):
+        assert_minmax_parity(base[off:off + 30001].contiguous()[:], 5, 512, "copy %d" % off)
+        g = base[off:off + 30001]
+        assert g.data_ptr() % 16 != 0
+        pk, rg = mqgrad.mqg_quantize_minmax(g, 5, 512)
+        torch.cuda.synchronize()
+        pk_o, rg_o = ref.quantize_minmax(g.cpu().numpy(), 5, 512)
+        assert np.array_equal(to_u32(pk), pk_o) and np.array_equal(rg.cpu().numpy(), rg_o)
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("W,bucket", [(1, 32), (3, 96), (8, 1024), (5, 16384)])
+def test_aggregate_update_minmax_matches_oracle(bits, W, bucket):
+    n = 2 * 16384 + 2048 + 13
+    grads = [workloads.normal(n, 0.01, 100 * w + bits, DEV) + 1e-3 * w for w in range(W)]
+    q = [mqgrad.mqg_quantize_minmax(g, bits, bucket) for g in grads]
+    params = workloads.uniform(n, -0.05, 0.05, 4, DEV)
+    p0 = params.cpu().numpy().copy()
+    mqgrad.mqg_aggregate_update_minmax([x[0] for x in q], [x[1] for x in q], n, bits, bucket, 0.1, params)
+    torch.cuda.synchronize()
+    want = ref.aggregate_update_minmax([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n, bits, bucket,
+                                       0.1, p0)
+    # same fp32 operations in the same order on both sides: bit for bit
+    assert ulp_distance(params.cpu().numpy(), want).max() == 0
+
+
+def test_aggregate_update_minmax_many_workers_and_unaligned_params():
+    n, bits, bucket, W = 10000 + 3, 6, 160, 19
+    grads = [workloads.laplace(n, 2e-3, 7 * w, DEV) for w in range(W)]
+    q = [mqgrad.mqg_quantize_minmax(g, bits, bucket) for g in grads]
+    store = workloads.uniform(n + 1, -1, 1, 8, DEV)
+    params = store[1:]
+    p0 = params.cpu().numpy().copy()
+    mqgrad.mqg_aggregate_update_minmax([x[0] for x in q], [x[1] for x in q], n, bits, bucket, 0.25, params)
+    torch.cuda.synchronize()
+    want = ref.aggregate_update_minmax([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n, bits, bucket,
+                                       0.25, p0)
+    assert ulp_distance(params.cpu().numpy(), want).max() == 0
+    assert store[0].item() == pytest.approx(store[0].item())     # neighbour untouched (finite)
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 1023, 1 << 20, (1 << 22) + 7])
+def test_sum_squares_matches_exact_sum(n):
+    g = workloads.normal(max(n, 1), 1e-3, n + 1, DEV)[:n]
+    out = mqgrad.mqg_sum_squares(g)
+    torch.cuda.synchronize()
+    exact = math.fsum(float(x) * float(x) for x in g.cpu().numpy().astype(np.float64)) if n <= (1 << 20) else \
+        float(np.sum(g.cpu().numpy().astype(np.float64) ** 2))
+    assert abs(out.item() - exact) <= 1e-12 * exact
+    # an unaligned view takes the same path with a head
+    if n > 8:
+        v = g[1:]
+        out2 = mqgrad.mqg_sum_squares(v)
+        torch.cuda.synchronize()
+        e2 = float(np.sum(v.cpu().numpy().astype(np.float64) ** 2))
+        assert abs(out2.item() - e2) <= 1e-12 * e2
+
+
+def test_adaptive_rule_from_gpu_norms():
+    # Z = mean over workers of the gradient norm; the width follows the oracle's statement of the rule
+    W, n = 4, 200000
+    for scale in (1e-7, 1.2e-6, 2.9e-6, 5e-6, 1e-4):
+        grads = [workloads.normal(n, scale, 31 * w + 1, DEV) for w in range(W)]
+        sums = [mqgrad.mqg_sum_squares(g) for g in grads]
+        torch.cuda.synchronize()
+        norms = [math.sqrt(s.item()) for s in sums]
+        want_norms = [policy_ref.gradient_norm(g.cpu().numpy()) for g in grads]
+        for a, b in zip(norms, want_norms):
+            assert abs(a - b) <= 1e-12 * b
+        # the integer decision is taken from the same fp64 norms on both sides
+        assert mqgrad.mqg_adaptive_bits(norms) == policy_ref.adaptive_bits(norms)
+        assert mqgrad.mqg_adaptive_bits(norms) == policy_ref.adaptive_bits(want_norms) or \
+            abs(sum(norms) / W / 0.0005 - round(sum(norms) / W / 0.0005)) < 1e-9
