@@ -210,6 +210,49 @@ def time_tensors(W, bits, bucket, lr, steps, warmup, device):
     return res
 
 
+def time_minmax(wl, bits, bucket, lr, steps, warmup):
+    """The footnote's deterministic [min, max] encoding and the sum of squares of the Adaptive rule."""
+    import torch
+    from paper_1804_08066_amd import mqgrad
+    n, W = wl.n, wl.W
+    pk = [torch.empty(mqgrad.mqg_packed_words(n, bits), dtype=torch.int32, device=wl.device) for _ in range(W)]
+    rg = [torch.empty(2 * mqgrad.mqg_num_buckets(n, bucket), dtype=torch.float32, device=wl.device) for _ in range(W)]
+    ss = torch.empty(1, dtype=torch.float64, device=wl.device)
+    ev = []
+    for k in range(warmup + steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record()
+        for w in range(W):
+            mqgrad.mqg_quantize_minmax(wl.grads[w], bits, bucket, pk[w], rg[w])
+        e[1].record()
+        mqgrad.mqg_aggregate_update_minmax(pk, rg, n, bits, bucket, lr, wl.params)
+        e[2].record()
+        for w in range(W):
+            mqgrad.mqg_sum_squares(wl.grads[w], ss)
+        e[3].record()
+        if k >= warmup:
+            ev.append(e)
+    torch.cuda.synchronize()
+    q_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev) / W
+    a_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+    s_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / len(ev) / W
+    nb = (n + bucket - 1) // bucket
+    q_bytes = n * (4.0 + bits / 8.0) + 8.0 * nb
+    a_bytes = W * (n * bits / 8.0 + 8.0 * nb) + 8.0 * n
+    s_bytes = 4.0 * n
+    frac = lambda by, ms: by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    log("minmax b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%), sum_squares %.1f us (%.1f%%)" %
+        (bits, bucket, q_ms * 1e3, 100 * frac(q_bytes, q_ms), a_ms * 1e3, 100 * frac(a_bytes, a_ms), s_ms * 1e3,
+         100 * frac(s_bytes, s_ms)))
+    row = lambda name, by, ms: {"kernel": name, "avg_launch_us": ms * 1e3, "bound": "hbm", "unit": "GB/s",
+                                "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "frac": frac(by, ms),
+                                "algorithmic_bytes_per_launch": by}
+    return {"bits": bits, "bucket": bucket,
+            "quantize_minmax": row("quantize_minmax_kernel", q_bytes, q_ms),
+            "aggregate_update_minmax": row("aggregate_update_minmax_kernel", a_bytes, a_ms),
+            "sum_squares": row("sum_squares_kernel", s_bytes, s_ms)}
+
+
 def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
     """The oracle as it stands, single thread, on a slice of the same workload (host tensors)."""
     import numpy as np
@@ -245,6 +288,8 @@ def main():
                     help="also time the paper's full exchange: server re-quantizes the mean, worker de-quantizes and updates")
     ap.add_argument("--tensors", action="store_true",
                     help="also time the small CNN's layer list: one launch per layer versus the multi-tensor calls")
+    ap.add_argument("--minmax", action="store_true",
+                    help="also time the deterministic [min, max] encoding, its server step and the sum of squares")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
@@ -311,6 +356,10 @@ def main():
 
     if args.exchange:
         out["exchange"] = time_exchange(wl, bits, bucket, args.lr, max(10, args.steps // 4), max(5, args.warmup // 4))
+
+    if args.minmax:
+        out["minmax"] = [time_minmax(wl, b, bucket, args.lr, max(10, args.steps // 4), max(5, args.warmup // 4))
+                         for b in ((1, 2, 4, 8) if args.sweep else (bits,))]
 
     if args.tensors:
         out["tensors"] = time_tensors(W, bits, 512, args.lr, 200, 20, wl.device)

@@ -260,7 +260,18 @@ __global__ __launch_bounds__(kThreads) void sum_squares_kernel(const float* __re
     }
     const v4f* __restrict__ g4 = reinterpret_cast<const v4f*>(g + head);
     const uint64_t nq = (n - head) >> 2;
-    for (uint64_t q = gtid; q < nq; q += stride) {
+    uint64_t q = gtid;
+    for (; q + 3u * stride < nq; q += 4u * stride) {   // four loads in flight per lane
+        v4f t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(g4 + q + u * stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const double a0 = (double)t[u].x, a1 = (double)t[u].y, a2 = (double)t[u].z, a3 = (double)t[u].w;
+            acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
+    }
+    for (; q < nq; q += stride) {
         const v4f t = __builtin_nontemporal_load(g4 + q);
         const double a0 = (double)t.x, a1 = (double)t.y, a2 = (double)t.z, a3 = (double)t.w;
         acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
