@@ -30,7 +30,8 @@ def needs_build():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "kernels.h"), os.path.join(CSRC, "decode.h"), os.path.join(CSRC, "encode.h"), os.path.join(ROOT, "include", "mqgrad.h")]
+    deps = sources() + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + \
+        [os.path.join(ROOT, "include", "mqgrad.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -26,6 +26,8 @@
 #include "kernels.h"
 #include "tile_io.h"
 
+#include <type_traits>
+
 #ifndef MQG_AGG_ROWS_R
 #define MQG_AGG_ROWS_R 2
 #endif
@@ -41,7 +43,7 @@ using decode::accumulate_quad;
 using decode::readlane_f32;
 // ---- buckets that are multiples of 128: bucket steps live in the wave ---------------------------
 // NBR = buckets a 256-element row can touch: 1 when the bucket is a multiple of 256, else 2.
-template <int R, int NBR, bool STRADDLE, bool ALIGNED>
+template <int R, int NBR, bool STRADDLE, bool ALIGNED, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const AggregateArgs a) {
     constexpr uint32_t TILE = 1024u * R;
     const uint32_t tid = threadIdx.x;
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     const float Lf = (float)((1u << b) - 1u);
     const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
-    decode::fetch_codes<R, kChunk>(a.packed, a.W, 0u, cw, c);
+    decode::fetch_codes<R, kChunk, ONCE>(a.packed, a.W, 0u, cw, c);
 
     // bucket steps of this wave's rows: lane w divides worker w's scale(s)
     const uint64_t nb_total = (a.n + a.bucket - 1u) / a.bucket;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) decode::fetch_codes<R, kChunk>(a.packed, a.W, w0, cw, c);
+        if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(a.packed, a.W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {
@@ -114,7 +116,7 @@ constexpr uint32_t kMaxBuckets = kLdsTile / 32u + 1u;   // buckets a tile can to
 // One tile of kLdsTile parameters of one tensor.  packed / scales: tables of W device pointers
 // (in kernel-argument memory).  raw != nullptr: an uncompressed layer -- the W pointers are fp32
 // gradients that are summed in worker order instead of decoded.
-template <bool STRADDLE, bool ALIGNED>
+template <bool STRADDLE, bool ALIGNED, bool ONCE>
 __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed, const float* const* scales,
                                                    const float* const* raw, uint32_t W, uint64_t n, uint32_t b,
                                                    uint32_t bucket, int bucket_shift, float neg_c,
@@ -153,7 +155,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
     const float Lf = (float)((1u << b) - 1u);
     const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
-    decode::fetch_codes<R, kChunk>(packed, W, 0u, cw, c);   // in flight while the bucket steps are computed
+    decode::fetch_codes<R, kChunk, ONCE>(packed, W, 0u, cw, c);   // in flight while the bucket steps are computed
 
     const uint64_t kb0 = tile_base / bucket;
     const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / bucket - kb0) + 1u;   // <= kMaxBuckets
@@ -182,7 +184,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
     __syncthreads();
 
     for (uint32_t w0 = 0; w0 < W; w0 += kChunk) {
-        if (w0 > 0) decode::fetch_codes<R, kChunk>(packed, W, w0, cw, c);
+        if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(packed, W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < W) {
@@ -197,16 +199,16 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
     update_params<R, ALIGNED>(p, tile_count, full, neg_c, x, acc);
 }
 
-template <bool STRADDLE, bool ALIGNED>
+template <bool STRADDLE, bool ALIGNED, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const AggregateArgs a) {
     extern __shared__ float s_step[];   // [W][nbt]
-    aggregate_tile_lds<STRADDLE, ALIGNED>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket, a.bucket_shift,
+    aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket, a.bucket_shift,
                                           a.neg_c, a.params, (uint64_t)blockIdx.x * kLdsTile, s_step);
 }
 
 // Several tensors of a model in one launch: block -> (tensor, tile) through the prefix table of tile
 // counts.  A tensor is either quantized (W packed + W scale pointers) or raw (W fp32 gradients).
-template <bool STRADDLE, bool ALIGNED>
+template <bool STRADDLE, bool ALIGNED, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_tensors_kernel(const BatchAggregateArgs a) {
     extern __shared__ float s_step[];
     uint32_t lo = 0, hi = a.count;           // tile_start[lo] <= blockIdx.x < tile_start[hi]
@@ -218,12 +220,22 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_tensors_kernel(cons
     const uint64_t tile_base = (uint64_t)(blockIdx.x - a.tile_start[lo]) * kLdsTile;
     const void* const* ptrs = a.ptrs + t.first_ptr;
     if (t.raw) {
-        aggregate_tile_lds<STRADDLE, ALIGNED>(nullptr, nullptr, reinterpret_cast<const float* const*>(ptrs), a.W, t.n,
+        aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(nullptr, nullptr, reinterpret_cast<const float* const*>(ptrs), a.W, t.n,
                                               a.bits, a.bucket, a.bucket_shift, a.neg_c, t.params, tile_base, s_step);
     } else {
-        aggregate_tile_lds<STRADDLE, ALIGNED>(reinterpret_cast<const uint32_t* const*>(ptrs),
+        aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(reinterpret_cast<const uint32_t* const*>(ptrs),
                                               reinterpret_cast<const float* const*>(ptrs + a.W), nullptr, a.W, t.n,
                                               a.bits, a.bucket, a.bucket_shift, a.neg_c, t.params, tile_base, s_step);
+    }
+}
+
+// Calls f(aligned, read_once) with the two flags as compile-time constants.
+template <class F>
+void with_flags(bool aligned, bool once, F f) {
+    if (aligned) {
+        if (once) f(std::true_type{}, std::true_type{}); else f(std::true_type{}, std::false_type{});
+    } else {
+        if (once) f(std::false_type{}, std::true_type{}); else f(std::false_type{}, std::false_type{});
     }
 }
 
@@ -234,11 +246,10 @@ hipError_t launch_rows(const AggregateArgs& a, hipStream_t stream) {
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
-    if (aligned) {
-        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, true>), grid, block, 0, stream, a);
-    } else {
-        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, false>), grid, block, 0, stream, a);
-    }
+    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(al)::value, decltype(once)::value>),
+                           grid, block, 0, stream, a);
+    });
     return hipGetLastError();
 }
 
@@ -249,11 +260,10 @@ hipError_t launch_lds(const AggregateArgs& a, hipStream_t stream) {
     const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     const size_t lds = sizeof(float) * a.W * kMaxBuckets;
-    if (aligned) {
-        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, true>), grid, block, lds, stream, a);
-    } else {
-        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, false>), grid, block, lds, stream, a);
-    }
+    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
+        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, decltype(al)::value, decltype(once)::value>),
+                           grid, block, lds, stream, a);
+    });
     return hipGetLastError();
 }
 
@@ -261,11 +271,10 @@ template <bool STRADDLE>
 hipError_t launch_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
     const dim3 grid(tiles), block(kThreads);
     const size_t lds = sizeof(float) * a.W * kMaxBuckets;
-    if (aligned) {
-        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, true>), grid, block, lds, stream, a);
-    } else {
-        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, false>), grid, block, lds, stream, a);
-    }
+    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
+        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, decltype(al)::value, decltype(once)::value>),
+                           grid, block, lds, stream, a);
+    });
     return hipGetLastError();
 }
 

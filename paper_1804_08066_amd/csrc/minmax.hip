@@ -181,7 +181,7 @@ constexpr int kAggR = 2;
 constexpr uint32_t kAggTile = 1024u * kAggR;
 constexpr uint32_t kMaxBuckets = kAggTile / 32u + 1u;   // buckets a tile can touch
 
-template <bool STRADDLE, bool ALIGNED>
+template <bool STRADDLE, bool ALIGNED, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const AggregateArgs a) {
     extern __shared__ float2 s_tab[];   // [W][nbt]: (step, min) of each worker's buckets of the tile
     constexpr int R = kAggR;
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
     const float Lf = (float)((1u << b) - 1u);
     const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
-    decode::fetch_codes<R, kChunk>(a.packed, a.W, 0u, cw, c);   // in flight while the table is filled
+    decode::fetch_codes<R, kChunk, ONCE>(a.packed, a.W, 0u, cw, c);   // in flight while the table is filled
 
     const uint64_t kb0 = tile_base / a.bucket;
     const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
     __syncthreads();
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) decode::fetch_codes<R, kChunk>(a.packed, a.W, w0, cw, c);
+        if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(a.packed, a.W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {
@@ -316,10 +316,13 @@ hipError_t launch_aggregate_s(const AggregateArgs& a, hipStream_t stream) {
     const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     const size_t lds = sizeof(float2) * a.W * kMaxBuckets;
+    const bool once = decode::codes_read_once(a.bits);
     if (aligned) {
-        hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true>), grid, block, lds, stream, a);
+        if (once) hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true, true>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true, false>), grid, block, lds, stream, a);
     } else {
-        hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false>), grid, block, lds, stream, a);
+        if (once) hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false, true>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false, false>), grid, block, lds, stream, a);
     }
     return hipGetLastError();
 }

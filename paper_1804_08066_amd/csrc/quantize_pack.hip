@@ -100,7 +100,7 @@ struct GradSource {
 // ---- source: sum over workers of their de-quantized gradients -------------------------------------
 // CH workers' code words are in flight together; the per-bucket steps s_w / L of every worker go
 // through an LDS table [W][buckets of the tile] that is complete after the tile's first barrier.
-template <int R, int CH>
+template <int R, int CH, bool ONCE>
 struct DecodeSource {
     const RequantArgs& ra;
     float* s_step;                       // LDS, W * nbt floats
@@ -113,7 +113,7 @@ struct DecodeSource {
     __device__ __forceinline__ void issue(uint64_t tile_base, uint32_t tile_count) {
         const uint32_t b = ra.q.bits;
         cw = decode::code_windows<R, kThreads>(ra.q.n, tile_base, b, threadIdx.x);
-        decode::fetch_codes<R, CH>(ra.packed, ra.W, 0u, cw, c);
+        decode::fetch_codes<R, CH, ONCE>(ra.packed, ra.W, 0u, cw, c);
         nbt = (R > 4) ? 1u : (tile_count + ra.q.bucket - 1u) / ra.q.bucket;
         const uint64_t kb0 = tile_base / ra.q.bucket;
         const float Lf = (float)((1u << b) - 1u);
@@ -134,7 +134,7 @@ struct DecodeSource {
             x[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         }
         for (uint32_t w0 = 0; w0 < ra.W; w0 += CH) {
-            if (w0 > 0) decode::fetch_codes<R, CH>(ra.packed, ra.W, w0, cw, c);
+            if (w0 > 0) decode::fetch_codes<R, CH, ONCE>(ra.packed, ra.W, w0, cw, c);
 #pragma unroll
             for (int t = 0; t < CH; ++t) {
                 if (w0 + t < ra.W) {
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const QuantizeA
     }
 }
 
-template <int R, int CH>
+template <int R, int CH, bool ONCE>
 __global__ __launch_bounds__(kThreads) void requantize_pack_kernel(const RequantArgs ra, const uint32_t tile_elems) {
     __shared__ Shared<R> sm;
     extern __shared__ float s_step[];   // [W][buckets of the tile]
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(kThreads) void requantize_pack_kernel(const Requant
     const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
     const bool full = tile_count == Tile<R>::kCap;
 
-    DecodeSource<R, CH> src(ra, s_step);
+    DecodeSource<R, CH, ONCE> src(ra, s_step);
     src.issue(tile_base, tile_count);
     clear_shared<R>(sm, tile_count, a.bits);
     __syncthreads();                      // step table complete, staging clear
@@ -413,7 +413,11 @@ hipError_t launch_requant_r(const RequantArgs& ra, hipStream_t stream) {
     const uint64_t tiles = (ra.q.n + tile_elems - 1) / tile_elems;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const size_t lds = sizeof(float) * ra.W * Tile<R>::kMaxBuckets;
-    hipLaunchKernelGGL((requantize_pack_kernel<R, CH>), dim3((uint32_t)tiles), dim3(kThreads), lds, stream, ra, tile_elems);
+    if (decode::codes_read_once(ra.q.bits)) {
+        hipLaunchKernelGGL((requantize_pack_kernel<R, CH, true>), dim3((uint32_t)tiles), dim3(kThreads), lds, stream, ra, tile_elems);
+    } else {
+        hipLaunchKernelGGL((requantize_pack_kernel<R, CH, false>), dim3((uint32_t)tiles), dim3(kThreads), lds, stream, ra, tile_elems);
+    }
     return hipGetLastError();
 }
 
