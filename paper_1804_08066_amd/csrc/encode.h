@@ -30,6 +30,28 @@ __device__ __forceinline__ float dpp_f32(float v) {
     return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
 }
 
+// lane ^ 16 and lane ^ 32 exchanges on the LDS pipe (no vector-ALU issue, no LDS memory)
+constexpr int kSwizzleXor16 = 0x401F;     // bit-mode swizzle: and 0x1F, or 0, xor 0x10
+__device__ __forceinline__ float swizzle_xor16_f32(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleXor16));
+}
+__device__ __forceinline__ float bpermute_xor32_f32(float v, uint32_t lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), __builtin_bit_cast(int, v)));
+}
+
+// From values already reduced over each 8-lane group to the whole wave: every lane gets the result.
+// Call with every lane of the wave active.
+__device__ __forceinline__ float wave_max_from_cells(float m, uint32_t lane) {
+    m = fmaxf(m, dpp_f32<kDppRowMirror>(m));
+    m = fmaxf(m, swizzle_xor16_f32(m));
+    return fmaxf(m, bpermute_xor32_f32(m, lane));
+}
+__device__ __forceinline__ float wave_min_from_cells(float m, uint32_t lane) {
+    m = fminf(m, dpp_f32<kDppRowMirror>(m));
+    m = fminf(m, swizzle_xor16_f32(m));
+    return fminf(m, bpermute_xor32_f32(m, lane));
+}
+
 // a ^ b ^ c in one instruction: gfx950's three-input bitwise operation with the parity truth table
 // (bit i of 0x96 is the parity of i's three bits).
 __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {

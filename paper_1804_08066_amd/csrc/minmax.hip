@@ -8,7 +8,7 @@
 //   server   acc = sum_w value_w (worker order);  p <- fma(-(lr/W), acc, p)
 //
 // No random numbers.  Work decomposition as in the stochastic quantizer's workgroup-cooperative
-// kernel: 256 lanes own one tile of whole buckets (at most 1024*R elements, R float4 per lane, read
+// kernel: a workgroup owns one tile of whole buckets (four float4 per lane, 256 to 1024 lanes, read
 // from HBM once), ranges go through LDS with order-preserving integer keys, codes are packed through
 // LDS and whole words are stored coalesced.
 
@@ -35,9 +35,11 @@ __device__ __forceinline__ float key_value(uint32_t k) {
     return __builtin_bit_cast(float, u);
 }
 
-template <int R>
+// NT lanes own a tile of at most 4*NT*R elements
+template <int R, int NT>
 struct Shared {
-    static constexpr uint32_t kCap = 1024u * R;
+    static constexpr uint32_t kCap = 4u * NT * R;
+    static constexpr bool kOneBucket = kCap > 4096u;   // tiles above 4096 elements are chosen for one large bucket
     uint32_t words[kCap * 8u / 32u + 4];
     uint32_t kmin[128];
     uint32_t kmax[128];
@@ -45,9 +47,9 @@ struct Shared {
     float a[128];
 };
 
-template <int R, bool ALIGNED, bool FULL>
+template <int R, int NT, bool ALIGNED, bool FULL>
 __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
-                                                     const uint32_t tile_count, Shared<R>& sm) {
+                                                     const uint32_t tile_count, Shared<R, NT>& sm) {
     const uint32_t tid = threadIdx.x;
     const float* __restrict__ g = a.grad + tile_base;
     const float inf = __builtin_inff();
@@ -56,7 +58,7 @@ __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, cons
     float4 x[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const uint32_t el = 4u * (j * kThreads + tid);
+        const uint32_t el = 4u * (j * NT + tid);
         if (FULL || el + 4u <= tile_count) {
             if (ALIGNED) {
                 const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + el));
@@ -73,45 +75,72 @@ __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, cons
     }
     const uint32_t b = a.bits;
     const uint32_t nwords = (tile_count * b + 31u) >> 5;
-    for (uint32_t i = tid; i < nwords; i += kThreads) sm.words[i] = 0u;
+    for (uint32_t i = tid; i < nwords; i += NT) sm.words[i] = 0u;
     if (tid < 128u) {
         sm.kmin[tid] = 0xFFFFFFFFu;
         sm.kmax[tid] = 0u;
     }
     __syncthreads();
 
-    const uint32_t nbt = (R > 4) ? 1u : (tile_count + a.bucket - 1u) / a.bucket;   // buckets in the tile
+    const uint32_t nbt = Shared<R, NT>::kOneBucket ? 1u : (tile_count + a.bucket - 1u) / a.bucket;   // buckets in the tile
     const uint64_t kb0 = tile_base / a.bucket;
     uint32_t bl[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const uint32_t el = 4u * (j * kThreads + tid);
-        bl[j] = (R > 4) ? 0u : (a.bucket_shift >= 0 ? (el >> a.bucket_shift) : (el / a.bucket));
+        const uint32_t el = 4u * (j * NT + tid);
+        bl[j] = Shared<R, NT>::kOneBucket ? 0u : (a.bucket_shift >= 0 ? (el >> a.bucket_shift) : (el / a.bucket));
     }
 
-    // ---- bucket range: 8-lane cells by DPP, cells into the bucket's LDS slot ----------------
+    // ---- bucket range: 8-lane cells by DPP; whole waves when a wave's row lies in one bucket -------
+    // (every lane of a cell, or of a wave, then holds the same value, and one lane folds it into the
+    // bucket's LDS slot: few atomics per slot, since same-address LDS atomics serialize)
+    constexpr bool kOne = Shared<R, NT>::kOneBucket;
+    const uint32_t lane = tid & 63u;
+    const bool row_in_bucket = kOne || (a.bucket & 255u) == 0u;   // uniform over the launch
+    float lo[R], hi[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const uint32_t el = 4u * (j * kThreads + tid);
-        float lo, hi;
+        const uint32_t el = 4u * (j * NT + tid);
         if (FULL) {
-            lo = fminf(fminf(x[j].x, x[j].y), fminf(x[j].z, x[j].w));
-            hi = fmaxf(fmaxf(x[j].x, x[j].y), fmaxf(x[j].z, x[j].w));
+            lo[j] = fminf(fminf(x[j].x, x[j].y), fminf(x[j].z, x[j].w));
+            hi[j] = fmaxf(fmaxf(x[j].x, x[j].y), fmaxf(x[j].z, x[j].w));
         } else {   // elements past the end take no part
             const bool v0 = el + 0u < tile_count, v1 = el + 1u < tile_count;
             const bool v2 = el + 2u < tile_count, v3 = el + 3u < tile_count;
-            lo = fminf(fminf(v0 ? x[j].x : inf, v1 ? x[j].y : inf), fminf(v2 ? x[j].z : inf, v3 ? x[j].w : inf));
-            hi = fmaxf(fmaxf(v0 ? x[j].x : -inf, v1 ? x[j].y : -inf), fmaxf(v2 ? x[j].z : -inf, v3 ? x[j].w : -inf));
+            lo[j] = fminf(fminf(v0 ? x[j].x : inf, v1 ? x[j].y : inf), fminf(v2 ? x[j].z : inf, v3 ? x[j].w : inf));
+            hi[j] = fmaxf(fmaxf(v0 ? x[j].x : -inf, v1 ? x[j].y : -inf), fmaxf(v2 ? x[j].z : -inf, v3 ? x[j].w : -inf));
         }
-        lo = fminf(lo, dpp_f32<kDppQuadSwap1>(lo));
-        hi = fmaxf(hi, dpp_f32<kDppQuadSwap1>(hi));
-        lo = fminf(lo, dpp_f32<kDppQuadSwap2>(lo));
-        hi = fmaxf(hi, dpp_f32<kDppQuadSwap2>(hi));
-        lo = fminf(lo, dpp_f32<kDppRowHalfMirror>(lo));
-        hi = fmaxf(hi, dpp_f32<kDppRowHalfMirror>(hi));
-        if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
-            atomicMin(&sm.kmin[bl[j]], order_key(lo));
-            atomicMax(&sm.kmax[bl[j]], order_key(hi));
+    }
+    if (kOne) {   // the tile is one bucket: fold the lane's rows first
+#pragma unroll
+        for (int j = 1; j < R; ++j) {
+            lo[0] = fminf(lo[0], lo[j]);
+            hi[0] = fmaxf(hi[0], hi[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < (kOne ? 1 : R); ++j) {
+        float l = lo[j], h = hi[j];
+        l = fminf(l, dpp_f32<kDppQuadSwap1>(l));
+        h = fmaxf(h, dpp_f32<kDppQuadSwap1>(h));
+        l = fminf(l, dpp_f32<kDppQuadSwap2>(l));
+        h = fmaxf(h, dpp_f32<kDppQuadSwap2>(h));
+        l = fminf(l, dpp_f32<kDppRowHalfMirror>(l));
+        h = fmaxf(h, dpp_f32<kDppRowHalfMirror>(h));
+        if (row_in_bucket) {
+            l = wave_min_from_cells(l, lane);
+            h = wave_max_from_cells(h, lane);
+            const uint32_t row_first = 4u * (j * NT + (tid & ~63u));   // first element of the wave's row
+            if (lane == 0u && (FULL || kOne || row_first < tile_count)) {
+                atomicMin(&sm.kmin[bl[j]], order_key(l));
+                atomicMax(&sm.kmax[bl[j]], order_key(h));
+            }
+        } else {
+            const uint32_t el = 4u * (j * NT + tid);
+            if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
+                atomicMin(&sm.kmin[bl[j]], order_key(l));
+                atomicMax(&sm.kmax[bl[j]], order_key(h));
+            }
         }
     }
     __syncthreads();
@@ -136,7 +165,7 @@ __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, cons
     const bool straddle = sh + 4u * b > 32u;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const uint32_t ql = j * kThreads + tid;
+        const uint32_t ql = j * NT + tid;
         const uint32_t el = 4u * ql;
         const float mn = sm.mn[bl[j]], ai = sm.a[bl[j]];
         // fmaxf drops a NaN position to 0; positions are integers after rint
@@ -160,19 +189,19 @@ __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, cons
     __syncthreads();
 
     uint32_t* __restrict__ out = a.packed + (tile_base >> 5) * b;
-    for (uint32_t i = tid; i < nwords; i += kThreads) __builtin_nontemporal_store(sm.words[i], out + i);
+    for (uint32_t i = tid; i < nwords; i += NT) __builtin_nontemporal_store(sm.words[i], out + i);
 }
 
-template <int R, bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
-    __shared__ Shared<R> sm;
+template <int R, int NT, bool ALIGNED>
+__global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
+    __shared__ Shared<R, NT> sm;
     const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
     const uint64_t left = a.n - tile_base;
     const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
-    if (tile_count == Shared<R>::kCap) {
-        quantize_minmax_tile<R, ALIGNED, true>(a, tile_base, tile_count, sm);
+    if (tile_count == Shared<R, NT>::kCap) {
+        quantize_minmax_tile<R, NT, ALIGNED, true>(a, tile_base, tile_count, sm);
     } else {
-        quantize_minmax_tile<R, ALIGNED, false>(a, tile_base, tile_count, sm);
+        quantize_minmax_tile<R, NT, ALIGNED, false>(a, tile_base, tile_count, sm);
     }
 }
 
@@ -260,18 +289,20 @@ __global__ __launch_bounds__(kThreads) void sum_squares_kernel(const float* __re
     }
     const v4f* __restrict__ g4 = reinterpret_cast<const v4f*>(g + head);
     const uint64_t nq = (n - head) >> 2;
-    uint64_t q = gtid;
-    for (; q + 3u * stride < nq; q += 4u * stride) {   // four loads in flight per lane
+    // a workgroup reads 16 KB contiguous pieces (four float4 per lane in flight), pieces gridDim.x apart
+    const uint64_t pieces = nq >> 10;
+    for (uint64_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
+        const v4f* __restrict__ src = g4 + (pc << 10) + tid;
         v4f t[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(g4 + q + u * stride);
+        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(src + u * kThreads);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const double a0 = (double)t[u].x, a1 = (double)t[u].y, a2 = (double)t[u].z, a3 = (double)t[u].w;
             acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
         }
     }
-    for (; q < nq; q += stride) {
+    for (uint64_t q = (pieces << 10) + gtid; q < nq; q += stride) {   // fewer than 1024 quads are left
         const v4f t = __builtin_nontemporal_load(g4 + q);
         const double a0 = (double)t.x, a1 = (double)t.y, a2 = (double)t.z, a3 = (double)t.w;
         acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
@@ -293,18 +324,18 @@ __global__ __launch_bounds__(kThreads) void sum_squares_kernel(const float* __re
     }
 }
 
-template <int R>
+template <int R, int NT>
 hipError_t launch_quantize_r(const QuantizeArgs& a, hipStream_t stream) {
-    const uint32_t cap = Shared<R>::kCap;
+    const uint32_t cap = Shared<R, NT>::kCap;
     const uint32_t tile_elems = (cap / a.bucket) * a.bucket;   // whole buckets, >= 1 by choice of R
     const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
-    const dim3 grid((uint32_t)tiles), block(kThreads);
+    const dim3 grid((uint32_t)tiles), block(NT);
     if (aligned) {
-        hipLaunchKernelGGL((quantize_minmax_kernel<R, true>), grid, block, 0, stream, a, tile_elems);
+        hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true>), grid, block, 0, stream, a, tile_elems);
     } else {
-        hipLaunchKernelGGL((quantize_minmax_kernel<R, false>), grid, block, 0, stream, a, tile_elems);
+        hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false>), grid, block, 0, stream, a, tile_elems);
     }
     return hipGetLastError();
 }
@@ -332,9 +363,10 @@ hipError_t launch_aggregate_s(const AggregateArgs& a, hipStream_t stream) {
 // a.scales: 2 floats (min, max) per bucket; a.scale_mode, key, iteration, worker, elem_base unused
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
-    if (a.bucket <= 4096u) return launch_quantize_r<4>(a, stream);
-    if (a.bucket <= 8192u) return launch_quantize_r<8>(a, stream);
-    return launch_quantize_r<16>(a, stream);
+    // four float4 per lane at every bucket size; larger buckets take larger workgroups
+    if (a.bucket <= 4096u) return launch_quantize_r<4, 256>(a, stream);
+    if (a.bucket <= 8192u) return launch_quantize_r<4, 512>(a, stream);
+    return launch_quantize_r<4, 1024>(a, stream);
 }
 
 // a.scales[w]: worker w's (min, max) pairs

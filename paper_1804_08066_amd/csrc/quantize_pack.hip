@@ -180,15 +180,45 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
 
     // ---- a1: bucket range -------------------------------------------------------------------
     if (compute_scales) {
+        // 8-lane cells by DPP, and one lane per cell folds the result into the bucket's LDS slot.
+        // Same-address LDS atomics serialize: when a slot would receive more than 32 of them (buckets
+        // of 2048 elements and more) the lane's rows of one bucket are folded first and the reduction
+        // goes on over the whole wave, which leaves one atomic per wave (and row).
+        constexpr bool kOne = R > 4;                                   // the tile is one bucket
+        const bool row_in_bucket = kOne || ((a.bucket & 255u) == 0u && a.bucket >= 2048u);   // uniform over the launch
+        if (row_in_bucket) {
+            float m[R];
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            const uint32_t el = 4u * (j * kThreads + tid);
-            float m = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
-            m = fmaxf(m, dpp_f32<kDppQuadSwap1>(m));
-            m = fmaxf(m, dpp_f32<kDppQuadSwap2>(m));
-            m = fmaxf(m, dpp_f32<kDppRowHalfMirror>(m));
-            if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
-                atomicMax(&sm.bmax[bl[j]], __builtin_bit_cast(uint32_t, m));   // m >= 0: bit order = value order
+            for (int j = 0; j < R; ++j) {
+                m[j] = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
+            }
+            if (kOne) {
+#pragma unroll
+                for (int j = 1; j < R; ++j) m[0] = fmaxf(m[0], m[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < (kOne ? 1 : R); ++j) {
+                float r = m[j];
+                r = fmaxf(r, dpp_f32<kDppQuadSwap1>(r));
+                r = fmaxf(r, dpp_f32<kDppQuadSwap2>(r));
+                r = fmaxf(r, dpp_f32<kDppRowHalfMirror>(r));
+                r = wave_max_from_cells(r, tid & 63u);
+                const uint32_t row_first = 4u * (j * kThreads + (tid & ~63u));
+                if ((tid & 63u) == 0u && (FULL || kOne || row_first < tile_count)) {
+                    atomicMax(&sm.bmax[bl[j]], __builtin_bit_cast(uint32_t, r));   // r >= 0: bit order = value order
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const uint32_t el = 4u * (j * kThreads + tid);
+                float m = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
+                m = fmaxf(m, dpp_f32<kDppQuadSwap1>(m));
+                m = fmaxf(m, dpp_f32<kDppQuadSwap2>(m));
+                m = fmaxf(m, dpp_f32<kDppRowHalfMirror>(m));
+                if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
+                    atomicMax(&sm.bmax[bl[j]], __builtin_bit_cast(uint32_t, m));   // m >= 0: bit order = value order
+                }
             }
         }
         if (l2) {

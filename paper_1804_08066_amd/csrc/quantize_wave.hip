@@ -25,16 +25,7 @@
 namespace mqg {
 namespace {
 
-constexpr int kSwizzleXor16 = 0x401F;     // bit-mode swizzle: and 0x1F, or 0, xor 0x10
-
 using namespace encode;
-
-__device__ __forceinline__ float swizzle_xor16_f32(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleXor16));
-}
-__device__ __forceinline__ float bpermute_xor32_f32(float v, uint32_t lane) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), __builtin_bit_cast(int, v)));
-}
 
 // lane ^ 1 exchange on the LDS pipe (bit-mode swizzle: and 0x1F, or 0, xor 1): costs no vector-ALU issue
 __device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
