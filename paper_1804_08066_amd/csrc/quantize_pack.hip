@@ -475,6 +475,7 @@ hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, b
 
 hipError_t launch_requantize(const RequantArgs& ra, hipStream_t stream) {
     if (ra.q.n == 0) return hipSuccess;
+    if (requantize_wave_supported(ra)) return launch_requantize_wave(ra, stream);
     if (ra.q.bucket <= 4096u) return launch_requant_r<4, 8>(ra, stream);
     if (ra.q.bucket <= 8192u) return launch_requant_r<8, 4>(ra, stream);
     return launch_requant_r<16, 2>(ra, stream);

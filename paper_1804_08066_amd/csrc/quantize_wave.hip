@@ -19,6 +19,7 @@
 // moved off the vector ALU where possible: cross-lane exchange through LDS-pipe swizzles, per-bucket
 // values through small per-wave LDS tables, bit placement through LDS atomics.
 
+#include "decode.h"
 #include "encode.h"
 #include "kernels.h"
 
@@ -55,6 +56,18 @@ struct WaveShared {
 };
 
 // ---- phase 1: load the chunk, clear the wave's packing area, publish the bucket maxima -----------
+template <int R, int NW>
+__device__ __forceinline__ void clear_words(uint32_t lane, uint32_t wave, WaveShared<R, NW>& sm) {
+    for (uint32_t i = lane; i < 16u * R; i += 64u) {
+        *reinterpret_cast<v4u*>(&sm.words[wave][4u * i]) = v4u{0u, 0u, 0u, 0u};
+    }
+}
+
+template <int R, int WPB, int NW>
+__device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lane, uint32_t wave,
+                                              const uint32_t (&slot)[R], uint32_t seg_lanes, uint32_t rpb,
+                                              WaveShared<R, NW>& sm);
+
 template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const float* __restrict__ g, uint32_t count,
                                                 uint32_t lane, uint32_t wave, const uint32_t (&slot)[R],
@@ -77,12 +90,16 @@ __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const flo
         }
     }
     // clear the packing area of this wave while the loads are in flight (LDS is in order per wave)
-    for (uint32_t i = lane; i < 16u * R; i += 64u) {
-        *reinterpret_cast<v4u*>(&sm.words[wave][4u * i]) = v4u{0u, 0u, 0u, 0u};
-    }
+    clear_words<R, NW>(lane, wave, sm);
     if (a.scales_in != nullptr) return;
+    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm);
+}
 
-    // a1: bucket range
+// a1: bucket range of the values in registers
+template <int R, int WPB, int NW>
+__device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lane, uint32_t wave,
+                                              const uint32_t (&slot)[R], uint32_t seg_lanes, uint32_t rpb,
+                                              WaveShared<R, NW>& sm) {
     float m[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -111,7 +128,9 @@ __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const flo
 template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
                                                   uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
-                                                  uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm) {
+                                                  uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm,
+                                                  float range_div = 1.0f) {
+    // range_div: the stored scale is range / range_div (1 for a plain quantize, W for the server's mean)
     const uint32_t b = a.bits;
     const uint32_t shift = (uint32_t)a.bucket_shift;
     const float Lf = (float)((1u << b) - 1u);
@@ -135,7 +154,7 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
                 s = sm.smax[wave][lane];
                 if (!(s >= 0x1p-96f)) s = 0.0f;
             }
-            if (WPB == 1 || (wave & (WPB - 1)) == 0u) a.scales[kb_first + lane] = s;
+            if (WPB == 1 || (wave & (WPB - 1)) == 0u) a.scales[kb_first + lane] = (range_div == 1.0f) ? s : s / range_div;
         }
         sm.ainv[wave][lane] = (s > 0.0f) ? halfL / s : 0.0f;   // IEEE-correct fp32 division, once per bucket
     }
@@ -242,6 +261,109 @@ __global__ __launch_bounds__(64 * NW) void quantize_wave_kernel(const QuantizeAr
     }
 }
 
+// ---- the server's re-quantizing step on the same decomposition -------------------------------------
+// ReceiveQGThenSendQG of Algorithm 1: the chunk's values are not loaded but decoded -- the sum over the
+// W workers' de-quantized gradients, the ordered fma chain of the fused update -- and then quantized
+// exactly as a gradient would be; the stored range is divided by W.  Buckets of 256 elements and more:
+// a wave's 256-element row lies in one bucket, so lane w divides worker w's scale of each row once
+// and the worker loop broadcasts it with v_readlane (no LDS table, no barrier).
+template <int R, int WPB, int NW, bool STRADDLE, bool ONCE>
+__global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantArgs ra) {
+    constexpr uint32_t CH = 256u * R;
+    constexpr int kChunk = 32 / R;   // workers whose code loads are in flight together
+    static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
+    __shared__ WaveShared<R, NW> sm;
+    const QuantizeArgs& a = ra.q;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint64_t chunk = (uint64_t)blockIdx.x * NW + wave;
+    const uint64_t cb = chunk * CH;
+    const bool active = cb < a.n;
+    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
+    const bool full = count == CH;
+
+    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 8 here
+    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);
+    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (1u << (shift - 8u));    // rows per bucket
+    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);
+    uint32_t slot[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((256u * j) >> shift);   // uniform: a row lies in one bucket
+
+    float4 x[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) x[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (active) {
+        const uint32_t b = a.bits;
+        const int negL = -(int)((1u << b) - 1u);
+        const float Lf = (float)((1u << b) - 1u);
+        const decode::CodeWindows<R> cw = decode::code_windows<R, 64>(a.n, cb, b, lane);
+        decode::CodeRegs<R, kChunk> c;
+        decode::fetch_codes<R, kChunk, ONCE>(ra.packed, ra.W, 0u, cw, c);
+        clear_words<R, NW>(lane, wave, sm);   // while the loads are in flight
+        // lane w: worker w's step of each row's bucket
+        const uint64_t nb_total = (a.n + a.bucket - 1u) >> shift;
+        const float* my_scales = ra.scales[lane < ra.W ? lane : 0u];
+        float d[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            uint64_t kb = kb_first + slot[j];
+            if (kb >= nb_total) kb = nb_total - 1u;   // row past the end
+            d[j] = my_scales[kb] / Lf;                // IEEE-correct fp32 division
+        }
+        for (uint32_t w0 = 0; w0 < ra.W; w0 += kChunk) {
+            if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(ra.packed, ra.W, w0, cw, c);
+#pragma unroll
+            for (int t = 0; t < kChunk; ++t) {
+                if (w0 + t < ra.W) {
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        decode::accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], b, negL, decode::readlane_f32(d[j], w0 + t), x[j]);
+                    }
+                }
+            }
+        }
+        if (!full) {   // elements past the end decode clamped words: they must not reach the range
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const uint32_t el = 4u * (j * 64u + lane);
+                if (el + 0u >= count) x[j].x = 0.0f;
+                if (el + 1u >= count) x[j].y = 0.0f;
+                if (el + 2u >= count) x[j].z = 0.0f;
+                if (el + 3u >= count) x[j].w = 0.0f;
+            }
+        }
+    }
+    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, 64u, rpb, sm);
+    if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
+    if (!active) return;
+    const float Wf = (float)ra.W;
+    if (full) {
+        quantize_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, Wf);
+    } else {
+        quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, Wf);
+    }
+}
+
+template <int R, int WPB, int NW>
+hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
+    const uint64_t per_group = (uint64_t)NW * 256u * R;
+    const uint64_t groups = (ra.q.n + per_group - 1) / per_group;
+    if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)groups), block(64 * NW);
+    const bool straddle = (32u % ra.q.bits) != 0u;
+    const bool once = decode::codes_read_once(ra.q.bits);
+    if (straddle) {
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, true>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, false>), grid, block, 0, stream, ra);
+    } else {
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, true>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, false>), grid, block, 0, stream, ra);
+    }
+    return hipGetLastError();
+}
+
 template <int R, int WPB, int NW>
 hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
@@ -269,6 +391,20 @@ hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
         case 8192: return launch_wave<4, 8, 8>(a, stream);
         case 16384: return launch_wave<4, 16, 16>(a, stream);
         default: return launch_wave<4, 1, 4>(a, stream);   // 32 .. 1024
+    }
+}
+
+// The re-quantizing server step takes the wave-local kernel for power-of-two buckets of 256 elements
+// and more.
+bool requantize_wave_supported(const RequantArgs& ra) { return ra.q.bucket_shift >= 8; }
+
+hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
+    switch (ra.q.bucket) {   // measured choices (100 M elements, W = 8)
+        case 2048: return launch_requant_wave<4, 2, 4>(ra, stream);
+        case 4096: return launch_requant_wave<4, 4, 4>(ra, stream);
+        case 8192: return launch_requant_wave<8, 4, 4>(ra, stream);
+        case 16384: return launch_requant_wave<4, 16, 16>(ra, stream);
+        default: return launch_requant_wave<4, 1, 4>(ra, stream);   // 256 .. 1024
     }
 }
 
