@@ -152,6 +152,58 @@ def test_config4_sampled_ranges_and_global_properties():
             assert bool(((params - p0).abs() <= bound).all())
 
 
+def test_config4_exchange_and_minmax_on_sampled_ranges():
+    # the widened rows at the benchmark's full size and launch configuration: the re-quantized mean, the
+    # worker's update from it, and the deterministic [min, max] encoding with its server step
+    n, W, lr, span = 100_000_000, 8, 0.1, 16384
+    grads = [workloads.config4_grad(w, n, DEV) for w in range(W)]
+    for bucket, bits in ((1024, 4), (128, 1), (8192, 8), (1024, 5)):
+        params = workloads.uniform(n, -0.05, 0.05, 1, DEV)
+        p0 = params.clone()
+        outs = [mqgrad.mqg_quantize(grads[w], bits, bucket, seed=77, iteration=1, worker=w) for w in range(W)]
+        mean_pk, mean_sc = mqgrad.mqg_aggregate_requantize([o[0] for o in outs], [o[1] for o in outs], n, bits, bucket,
+                                                           seed=77, iteration=1, worker=W)
+        mqgrad.mqg_dequantize_update(mean_pk, mean_sc, n, bits, bucket, lr, params)
+        torch.cuda.synchronize()
+        starts = sample_starts(n, span, 2, seed=bits * 3 + bucket)
+        for lo in starts:
+            hi = min(n, lo + span)
+            want = [ref.quantize(grads[w][lo:hi].cpu().numpy(), bits, bucket, 77, 1, w, lo) for w in range(W)]
+            m_pk, m_sc = ref.aggregate_requantize([x[0] for x in want], [x[1] for x in want], hi - lo, bits, bucket,
+                                                  77, 1, W, lo)
+            w0 = lo * bits // 32
+            assert np.array_equal(mean_sc[lo // bucket: lo // bucket + m_sc.size].cpu().numpy(), m_sc)
+            assert np.array_equal(to_u32(mean_pk[w0:w0 + m_pk.size]), m_pk), "b=%d B=%d range %d" % (bits, bucket, lo)
+            p_ref = ref.dequantize_update(m_pk, m_sc, hi - lo, bits, bucket, lr, p0[lo:hi].cpu().numpy())
+            assert ulp_distance(params[lo:hi].cpu().numpy(), p_ref).max() == 0
+        del outs, mean_pk, mean_sc
+
+        params = p0.clone()
+        mm = [mqgrad.mqg_quantize_minmax(grads[w], bits, bucket) for w in range(W)]
+        mqgrad.mqg_aggregate_update_minmax([m[0] for m in mm], [m[1] for m in mm], n, bits, bucket, lr, params)
+        torch.cuda.synchronize()
+        for lo in starts:
+            hi = min(n, lo + span)
+            want = [ref.quantize_minmax(grads[w][lo:hi].cpu().numpy(), bits, bucket) for w in range(W)]
+            w0 = lo * bits // 32
+            for w in (0, W - 1):
+                assert np.array_equal(mm[w][1][2 * (lo // bucket): 2 * (lo // bucket) + want[w][1].size].cpu().numpy(), want[w][1])
+                assert np.array_equal(to_u32(mm[w][0][w0:w0 + want[w][0].size]), want[w][0])
+            p_ref = ref.aggregate_update_minmax([x[0] for x in want], [x[1] for x in want], hi - lo, bits, bucket, lr,
+                                                p0[lo:hi].cpu().numpy())
+            assert ulp_distance(params[lo:hi].cpu().numpy(), p_ref).max() == 0
+        # at full size: the stored ranges are the bucket minima and maxima
+        full = (n // bucket) * bucket
+        v = grads[0][:full].view(-1, bucket)
+        assert torch.equal(mm[0][1][0:2 * (n // bucket):2], v.amin(dim=1))
+        assert torch.equal(mm[0][1][1:2 * (n // bucket):2], v.amax(dim=1))
+        ss = mqgrad.mqg_sum_squares(grads[0])
+        torch.cuda.synchronize()
+        want_ss = float((grads[0].double() ** 2).sum().item())
+        assert abs(ss.item() - want_ss) <= 1e-11 * want_ss
+        del mm
+
+
 # ---- configuration 5: 1B parameters, W = 16, bit width chosen by the host MDP --------------------
 
 def test_config5_large_model_with_mdp_policy():
