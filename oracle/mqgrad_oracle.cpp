@@ -400,6 +400,32 @@ void orc_aggregate_update_minmax(const uint32_t* const* packed, const float* con
     delete[] v;
 }
 
+// The paper's full exchange with this encoding (Algorithm 1, ReceiveQGThenSendQG): the server adds the
+// workers' de-quantized gradients in worker order, encodes the sum over its own per-bucket [min, max]
+// and stores the range divided by W -- a range-linear grid is equivariant under positive scaling, so
+// the codes of the sum over [mn, mx] are the codes of the mean over [mn / W, mx / W].
+void orc_aggregate_sum_minmax(const uint32_t* const* packed, const float* const* ranges, uint32_t W,
+                              uint64_t n, uint32_t bits, uint32_t bucket, float* sum) {
+    float* v = new float[n ? n : 1];
+    for (uint64_t i = 0; i < n; ++i) sum[i] = 0.0f;
+    for (uint32_t w = 0; w < W; ++w) {
+        orc_dequantize_minmax(packed[w], ranges[w], n, bits, bucket, v);
+        for (uint64_t i = 0; i < n; ++i) sum[i] = sum[i] + v[i];
+    }
+    delete[] v;
+}
+
+void orc_aggregate_requantize_minmax(const uint32_t* const* packed, const float* const* ranges, uint32_t W,
+                                     uint64_t n, uint32_t bits, uint32_t bucket, uint32_t* packed_out,
+                                     float* ranges_out) {
+    float* sum = new float[n ? n : 1];
+    orc_aggregate_sum_minmax(packed, ranges, W, n, bits, bucket, sum);
+    orc_quantize_minmax(sum, n, bits, bucket, packed_out, ranges_out, nullptr);
+    const uint64_t nb = (n + bucket - 1) / bucket;
+    for (uint64_t k = 0; k < 2 * nb; ++k) ranges_out[k] = ranges_out[k] / (float)W;
+    delete[] sum;
+}
+
 // The same server step evaluated from its plain definition in fp64 (no
 // ordering, no fp32 rounding until the end): used to pin the fp32 chain.
 void orc_aggregate_update_f64(const uint32_t* const* packed, const float* const* scales, uint32_t W,

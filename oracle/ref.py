@@ -76,6 +76,11 @@ def lib():
         L.orc_aggregate_update_minmax.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32,
                                                   C.c_uint32, C.c_float, f32p]
         L.orc_aggregate_update_minmax.restype = None
+        L.orc_aggregate_sum_minmax.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, f32p]
+        L.orc_aggregate_sum_minmax.restype = None
+        L.orc_aggregate_requantize_minmax.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32,
+                                                      C.c_uint32, u32p, f32p]
+        L.orc_aggregate_requantize_minmax.restype = None
         _lib = L
     return _lib
 
@@ -311,3 +316,23 @@ def aggregate_update_minmax(packed_list, ranges_list, n, bits, bucket, lr, param
     lib().orc_aggregate_update_minmax(pa, sa, len(packed_list), n, bits, bucket, float(np.float32(lr)),
                                       _p(out, C.c_float))
     return out
+
+
+def aggregate_sum_minmax(packed_list, ranges_list, n, bits, bucket):
+    """fp32 sum, in worker order, of the workers' de-quantized gradients ([min, max] encoding)."""
+    pk, rg, pa, sa = _ptr_arrays(packed_list, ranges_list)
+    out = np.zeros(n, dtype=np.float32)
+    if n:
+        lib().orc_aggregate_sum_minmax(pa, sa, len(packed_list), n, bits, bucket, _p(out, C.c_float))
+    return out
+
+
+def aggregate_requantize_minmax(packed_list, ranges_list, n, bits, bucket):
+    """Server side of the full exchange with the [min, max] encoding: (packed, ranges) of the mean."""
+    pk, rg, pa, sa = _ptr_arrays(packed_list, ranges_list)
+    packed = np.zeros(packed_words(n, bits), dtype=np.uint32)
+    ranges = np.zeros(2 * num_buckets(n, bucket), dtype=np.float32)
+    if n:
+        lib().orc_aggregate_requantize_minmax(pa, sa, len(packed_list), n, bits, bucket, _p(packed, C.c_uint32),
+                                              _p(ranges, C.c_float))
+    return packed, ranges

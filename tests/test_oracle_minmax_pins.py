@@ -276,3 +276,49 @@ def test_gradient_norm_is_numpy_norm():
     g = rng(3).normal(0, 1e-3, 10000).astype(np.float32)
     assert abs(policy_ref.gradient_norm(g) - np.linalg.norm(g.astype(np.float64))) <= 1e-12 * np.linalg.norm(g)
     assert policy_ref.gradient_norm(np.array([3.0, 4.0], dtype=np.float32)) == 5.0
+
+
+# ---- full exchange with the [min, max] encoding ------------------------------------------------------
+
+@pytest.mark.parametrize("W,bits", [(1, 3), (4, 2), (8, 8), (3, 5)])
+def test_requantized_mean_is_within_half_a_step_of_the_mean(W, bits):
+    r = rng(W * 13 + bits)
+    n, bucket = 6000 + 5, 256
+    grads = [r.normal(2e-3 * w, 1e-2, n).astype(np.float32) for w in range(W)]
+    q = [ref.quantize_minmax(g, bits, bucket) for g in grads]
+    deq = [ref.dequantize_minmax(x[0], x[1], n, bits, bucket).astype(np.float64) for x in q]
+    s = ref.aggregate_sum_minmax([x[0] for x in q], [x[1] for x in q], n, bits, bucket)
+    mag = sum(np.abs(d) for d in deq)
+    assert np.all(np.abs(s - sum(deq)) <= W * 2.0 ** -24 * mag)            # fp32 chain against the fp64 sum
+    pk, rg = ref.aggregate_requantize_minmax([x[0] for x in q], [x[1] for x in q], n, bits, bucket)
+    # the stored range is [min, max] of the sum divided by W
+    nb = (n + bucket - 1) // bucket
+    for k in range(nb):
+        seg = s[k * bucket:(k + 1) * bucket]
+        assert rg[2 * k] == np.float32(seg.min()) / np.float32(W) and rg[2 * k + 1] == np.float32(seg.max()) / np.float32(W)
+    # the codes are those of the sum over its own range
+    pk_s, rg_s = ref.quantize_minmax(s, bits, bucket)
+    assert np.array_equal(pk, pk_s)
+    # and what the worker de-quantizes is the mean to within half a step (of the mean's grid)
+    mean = sum(deq) / W
+    got = ref.dequantize_minmax(pk, rg, n, bits, bucket).astype(np.float64)
+    L = (1 << bits) - 1
+    kk = np.arange(n) // bucket
+    half = (rg[1::2].astype(np.float64) - rg[0::2].astype(np.float64))[kk] / L / 2
+    big = np.maximum(np.abs(rg[0::2]), np.abs(rg[1::2])).astype(np.float64)[kk]
+    assert np.all(np.abs(got - mean) <= half * (1 + 1e-4) + (W + 4) * 2.0 ** -23 * (big + mag / W))
+
+
+def test_one_worker_on_the_grid_is_forwarded_unchanged():
+    # W = 1: the sum is the de-quantized gradient, whose values are grid levels -- when the grid is exact
+    # in fp32 (power-of-two step) re-encoding reproduces codes and range
+    bits = 4
+    k = rng(77).integers(0, 16, 4096)
+    k[0], k[1] = 0, 15
+    g = (-1.0 + k * 2.0 ** -6).astype(np.float32)
+    pk, rg = ref.quantize_minmax(g, bits, 1024)
+    pk2, rg2 = ref.aggregate_requantize_minmax([pk], [rg], g.size, bits, 1024)
+    assert np.array_equal(pk, pk2) and np.array_equal(rg, rg2)
+    p0 = rng(78).uniform(-1, 1, g.size).astype(np.float32)
+    p1 = ref.aggregate_update_minmax([pk2], [rg2], g.size, bits, 1024, 0.25, p0)
+    assert np.array_equal(p1, (p0.astype(np.float64) - 0.25 * g.astype(np.float64)).astype(np.float32))
