@@ -218,9 +218,11 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
     pk = [torch.empty(mqgrad.mqg_packed_words(n, bits), dtype=torch.int32, device=wl.device) for _ in range(W)]
     rg = [torch.empty(2 * mqgrad.mqg_num_buckets(n, bucket), dtype=torch.float32, device=wl.device) for _ in range(W)]
     ss = torch.empty(1, dtype=torch.float64, device=wl.device)
+    mpk = torch.empty_like(pk[0])
+    mrg = torch.empty_like(rg[0])
     ev = []
     for k in range(warmup + steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
         e[0].record()
         for w in range(W):
             mqgrad.mqg_quantize_minmax(wl.grads[w], bits, bucket, pk[w], rg[w])
@@ -230,27 +232,36 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
         for w in range(W):
             mqgrad.mqg_sum_squares(wl.grads[w], ss)
         e[3].record()
+        mqgrad.mqg_aggregate_requantize_minmax(pk, rg, n, bits, bucket, mpk, mrg)
+        e[4].record()
         if k >= warmup:
             ev.append(e)
     torch.cuda.synchronize()
     q_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev) / W
     a_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
     s_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / len(ev) / W
+    r_ms = sum(e[3].elapsed_time(e[4]) for e in ev) / len(ev)
     nb = (n + bucket - 1) // bucket
     q_bytes = n * (4.0 + bits / 8.0) + 8.0 * nb
     a_bytes = W * (n * bits / 8.0 + 8.0 * nb) + 8.0 * n
     s_bytes = 4.0 * n
     frac = lambda by, ms: by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
-    log("minmax b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%), sum_squares %.1f us (%.1f%%)" %
+    r_ops = n * (4.0 * W + 12.0)   # decode: extract, convert, fma, add per worker; encode about 12
+    log("minmax b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%), sum_squares %.1f us (%.1f%%), "
+        "requantize %.1f us (%.1f T lane-ops/s)" %
         (bits, bucket, q_ms * 1e3, 100 * frac(q_bytes, q_ms), a_ms * 1e3, 100 * frac(a_bytes, a_ms), s_ms * 1e3,
-         100 * frac(s_bytes, s_ms)))
+         100 * frac(s_bytes, s_ms), r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12))
     row = lambda name, by, ms: {"kernel": name, "avg_launch_us": ms * 1e3, "bound": "hbm", "unit": "GB/s",
                                 "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "frac": frac(by, ms),
                                 "algorithmic_bytes_per_launch": by}
     return {"bits": bits, "bucket": bucket,
             "quantize_minmax": row("quantize_minmax_kernel", q_bytes, q_ms),
             "aggregate_update_minmax": row("aggregate_update_minmax_kernel", a_bytes, a_ms),
-            "sum_squares": row("sum_squares_kernel", s_bytes, s_ms)}
+            "sum_squares": row("sum_squares_kernel", s_bytes, s_ms),
+            "requantize_minmax": {"kernel": "requantize_minmax_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
+                                  "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
+                                  "unit": "T lane-ops/s", "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
+                                  "algorithmic_ops_per_launch": r_ops}}
 
 
 def cpu_baseline(bits, bucket, W, lr, sample_n, steps):

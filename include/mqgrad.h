@@ -212,6 +212,18 @@ mqg_status mqg_aggregate_update_minmax(const uint32_t* const* packed, const floa
                                        uint64_t n, uint32_t bits, uint32_t bucket,
                                        float lr, float* params, void* stream);
 
+/* The paper's full exchange with that encoding.  Server (ReceiveQGThenSendQG): the W streams are
+ * de-quantized and added in worker order (the chain of mqg_aggregate_update_minmax), the sum is encoded
+ * over its own per-bucket [mn, mx] exactly as mqg_quantize_minmax would encode it, and the stored range
+ * is (mn / W, mx / W): a range-linear grid is equivariant under positive scaling, so what the worker
+ * de-quantizes is the mean.  No fp32 copy of the sum or the mean is written to memory.
+ *   packed, ranges          HOST arrays of W device pointers, as for mqg_aggregate_update_minmax.
+ *   packed_out, ranges_out  device, as for mqg_quantize_minmax.
+ * The worker's half, w <- w - eta De-quantize(gbar), is mqg_aggregate_update_minmax with W = 1. */
+mqg_status mqg_aggregate_requantize_minmax(const uint32_t* const* packed, const float* const* ranges, uint32_t W,
+                                           uint64_t n, uint32_t bits, uint32_t bucket,
+                                           uint32_t* packed_out, float* ranges_out, void* stream);
+
 /* ---- the "Adaptive" baseline's bit rule (Section 4.1; idea in Section 2: the larger the gradient's
  * norm, the more bits) ------------------------------------------------------------------------------
  *

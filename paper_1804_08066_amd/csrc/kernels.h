@@ -93,6 +93,7 @@ hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);
 // minmax.hip: deterministic [min, max] encoding; `scales` holds (min, max) pairs, 2 floats per bucket
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream);
+hipError_t launch_requantize_minmax(const RequantArgs& a, hipStream_t stream);
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream);
 
 }  // namespace mqg

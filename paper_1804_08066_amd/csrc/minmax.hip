@@ -47,15 +47,10 @@ struct Shared {
     float a[128];
 };
 
+// one HBM pass: the tile of the gradient into registers
 template <int R, int NT, bool ALIGNED, bool FULL>
-__device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
-                                                     const uint32_t tile_count, Shared<R, NT>& sm) {
+__device__ __forceinline__ void load_grad_tile(const float* __restrict__ g, const uint32_t tile_count, float4 (&x)[R]) {
     const uint32_t tid = threadIdx.x;
-    const float* __restrict__ g = a.grad + tile_base;
-    const float inf = __builtin_inff();
-
-    // ---- one HBM pass: the tile into registers ----------------------------------------------
-    float4 x[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const uint32_t el = 4u * (j * NT + tid);
@@ -73,14 +68,30 @@ __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, cons
             x[j].w = 0.0f;   // el + 3 >= tile_count here
         }
     }
-    const uint32_t b = a.bits;
+}
+
+template <int R, int NT>
+__device__ __forceinline__ void clear_shared(Shared<R, NT>& sm, uint32_t tile_count, uint32_t b) {
+    const uint32_t tid = threadIdx.x;
     const uint32_t nwords = (tile_count * b + 31u) >> 5;
     for (uint32_t i = tid; i < nwords; i += NT) sm.words[i] = 0u;
     if (tid < 128u) {
         sm.kmin[tid] = 0xFFFFFFFFu;
         sm.kmax[tid] = 0u;
     }
-    __syncthreads();
+}
+
+// The tile, once its values are in registers; enters right after the barrier that follows
+// clear_shared.  range_div: the stored range is [mn, mx] / range_div (1 for a plain encode, W for the
+// server's mean).
+template <int R, int NT, bool FULL>
+__device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
+                                                   const uint32_t tile_count, const float4 (&x)[R],
+                                                   const float range_div, Shared<R, NT>& sm) {
+    const uint32_t tid = threadIdx.x;
+    const float inf = __builtin_inff();
+    const uint32_t b = a.bits;
+    const uint32_t nwords = (tile_count * b + 31u) >> 5;
 
     const uint32_t nbt = Shared<R, NT>::kOneBucket ? 1u : (tile_count + a.bucket - 1u) / a.bucket;   // buckets in the tile
     const uint64_t kb0 = tile_base / a.bucket;
@@ -150,8 +161,8 @@ __device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, cons
         float mn = key_value(sm.kmin[tid]), mx = key_value(sm.kmax[tid]);
         if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
         if (mx == 0.0f) mx = 0.0f;
-        a.scales[2u * (kb0 + tid)] = mn;
-        a.scales[2u * (kb0 + tid) + 1u] = mx;
+        a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
+        a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
         const float r = mx - mn;
         sm.mn[tid] = mn;
         sm.a[tid] = (r >= 0x1p-96f) ? Lf / r : 0.0f;   // IEEE-correct fp32 division, once per bucket
@@ -198,10 +209,79 @@ __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs 
     const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
     const uint64_t left = a.n - tile_base;
     const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
+    float4 x[R];
     if (tile_count == Shared<R, NT>::kCap) {
-        quantize_minmax_tile<R, NT, ALIGNED, true>(a, tile_base, tile_count, sm);
+        load_grad_tile<R, NT, ALIGNED, true>(a.grad + tile_base, tile_count, x);
+        clear_shared<R, NT>(sm, tile_count, a.bits);   // while the loads are in flight
+        __syncthreads();
+        encode_minmax_tile<R, NT, true>(a, tile_base, tile_count, x, 1.0f, sm);
     } else {
-        quantize_minmax_tile<R, NT, ALIGNED, false>(a, tile_base, tile_count, sm);
+        load_grad_tile<R, NT, ALIGNED, false>(a.grad + tile_base, tile_count, x);
+        clear_shared<R, NT>(sm, tile_count, a.bits);
+        __syncthreads();
+        encode_minmax_tile<R, NT, false>(a, tile_base, tile_count, x, 1.0f, sm);
+    }
+}
+
+// The server's re-encoding step of the full exchange (ReceiveQGThenSendQG): the tile's values are the
+// sum over the W workers' de-quantized gradients, decoded from their streams in worker order; the
+// stored range is divided by W.  (step, min) of every worker's buckets of the tile sit in an LDS table.
+template <int NT, bool STRADDLE, bool ONCE>
+__global__ __launch_bounds__(NT) void requantize_minmax_kernel(const RequantArgs ra, const uint32_t tile_elems) {
+    constexpr int R = 4;
+    constexpr int CH = 8;   // workers whose code loads are in flight together
+    __shared__ Shared<R, NT> sm;
+    extern __shared__ float2 s_tab[];   // [W][buckets of the tile]
+    const QuantizeArgs& a = ra.q;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
+    const uint64_t left = a.n - tile_base;
+    const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
+    const bool full = tile_count == Shared<R, NT>::kCap;
+    const uint32_t b = a.bits;
+    const float Lf = (float)((1u << b) - 1u);
+
+    const decode::CodeWindows<R> cw = decode::code_windows<R, NT>(a.n, tile_base, b, tid);
+    decode::CodeRegs<R, CH> c;
+    decode::fetch_codes<R, CH, ONCE>(ra.packed, ra.W, 0u, cw, c);   // in flight while the table is filled
+    const uint32_t nbt = Shared<R, NT>::kOneBucket ? 1u : (tile_count + a.bucket - 1u) / a.bucket;
+    const uint64_t kb0 = tile_base / a.bucket;
+    for (uint32_t i = tid; i < ra.W * nbt; i += NT) {
+        const uint32_t w = i / nbt, kb = i - w * nbt;
+        const float2 rg = reinterpret_cast<const float2*>(ra.scales[w])[kb0 + kb];   // (min, max)
+        s_tab[i] = make_float2((rg.y - rg.x) / Lf, rg.x);                            // IEEE-correct fp32 division
+    }
+    clear_shared<R, NT>(sm, tile_count, b);
+    __syncthreads();
+
+    uint32_t bl[R];
+    float4 x[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t el = 4u * (j * NT + tid);
+        bl[j] = Shared<R, NT>::kOneBucket ? 0u : (a.bucket_shift >= 0 ? (el >> a.bucket_shift) : (el / a.bucket));
+        if (bl[j] >= nbt) bl[j] = nbt - 1u;   // quads past the end: any valid slot
+        x[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    for (uint32_t w0 = 0; w0 < ra.W; w0 += CH) {
+        if (w0 > 0) decode::fetch_codes<R, CH, ONCE>(ra.packed, ra.W, w0, cw, c);
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            if (w0 + t < ra.W) {
+                const float2* __restrict__ tw = s_tab + (w0 + t) * nbt;
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    const float2 sl = tw[bl[j]];
+                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh[j], b, sl.x, sl.y, x[j]);
+                }
+            }
+        }
+    }
+    const float Wf = (float)ra.W;
+    if (full) {
+        encode_minmax_tile<R, NT, true>(a, tile_base, tile_count, x, Wf, sm);
+    } else {
+        encode_minmax_tile<R, NT, false>(a, tile_base, tile_count, x, Wf, sm);   // ignores elements past the end
     }
 }
 
@@ -358,7 +438,39 @@ hipError_t launch_aggregate_s(const AggregateArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <int NT>
+hipError_t launch_requant_nt(const RequantArgs& ra, hipStream_t stream) {
+    const uint32_t cap = Shared<4, NT>::kCap;
+    // whole buckets per tile, and at most 4096 table entries (32 KB of LDS)
+    uint32_t nb_tile = cap / ra.q.bucket;
+    const uint32_t max_nb = 4096u / ra.W;   // >= 64
+    if (nb_tile > max_nb) nb_tile = max_nb;
+    const uint32_t tile_elems = nb_tile * ra.q.bucket;
+    const uint64_t tiles = (ra.q.n + tile_elems - 1) / tile_elems;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)tiles), block(NT);
+    const size_t lds = sizeof(float2) * ra.W * nb_tile;
+    const bool straddle = (32u % ra.q.bits) != 0u;
+    const bool once = decode::codes_read_once(ra.q.bits);
+    if (straddle) {
+        if (once) hipLaunchKernelGGL((requantize_minmax_kernel<NT, true, true>), grid, block, lds, stream, ra, tile_elems);
+        else hipLaunchKernelGGL((requantize_minmax_kernel<NT, true, false>), grid, block, lds, stream, ra, tile_elems);
+    } else {
+        if (once) hipLaunchKernelGGL((requantize_minmax_kernel<NT, false, true>), grid, block, lds, stream, ra, tile_elems);
+        else hipLaunchKernelGGL((requantize_minmax_kernel<NT, false, false>), grid, block, lds, stream, ra, tile_elems);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// ra.scales[w]: worker w's (min, max) pairs; ra.q.scales: (min, max) pairs of the mean
+hipError_t launch_requantize_minmax(const RequantArgs& ra, hipStream_t stream) {
+    if (ra.q.n == 0) return hipSuccess;
+    if (ra.q.bucket <= 4096u) return launch_requant_nt<256>(ra, stream);
+    if (ra.q.bucket <= 8192u) return launch_requant_nt<512>(ra, stream);
+    return launch_requant_nt<1024>(ra, stream);
+}
 
 // a.scales: 2 floats (min, max) per bucket; a.scale_mode, key, iteration, worker, elem_base unused
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream) {

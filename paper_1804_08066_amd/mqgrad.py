@@ -19,7 +19,7 @@ EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
     "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
-    "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_sum_squares", "mqg_adaptive_default_config",
+    "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax", "mqg_sum_squares", "mqg_adaptive_default_config",
     "mqg_adaptive_bits",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
@@ -95,6 +95,8 @@ def lib():
     L.mqg_quantize_minmax.restype = C.c_int
     L.mqg_aggregate_update_minmax.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, vp]
     L.mqg_aggregate_update_minmax.restype = C.c_int
+    L.mqg_aggregate_requantize_minmax.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, vp, vp, vp]
+    L.mqg_aggregate_requantize_minmax.restype = C.c_int
     L.mqg_sum_squares.argtypes = [vp, u64, vp, vp]
     L.mqg_sum_squares.restype = C.c_int
     L.mqg_adaptive_default_config.argtypes = [C.POINTER(AdaptiveConfig)]
@@ -348,6 +350,34 @@ def mqg_aggregate_update_minmax(packed, ranges, n, bits, bucket, lr, params, str
     st = lib().mqg_aggregate_update_minmax(pa, ra, W, n, bits, bucket, lr, params.data_ptr(), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_update_minmax")
+
+
+def mqg_aggregate_requantize_minmax(packed, ranges, n, bits, bucket, packed_out=None, ranges_out=None, stream=None):
+    """Server side of the full exchange with the [min, max] encoding. Returns (packed, ranges) of the mean."""
+    W = len(packed)
+    if W != len(ranges):
+        raise ValueError("packed and ranges must have one entry per worker")
+    for p, r in zip(packed, ranges):
+        _check(p, torch.int32, "packed[w]")
+        _check(r, torch.float32, "ranges[w]")
+        if p.numel() < mqg_packed_words(n, bits) or r.numel() < 2 * mqg_num_buckets(n, bucket):
+            raise ValueError("a worker's buffers are too small for n")
+    dev = packed[0].device
+    if packed_out is None:
+        packed_out = torch.empty(mqg_packed_words(n, bits), dtype=torch.int32, device=dev)
+    if ranges_out is None:
+        ranges_out = torch.empty(2 * mqg_num_buckets(n, bucket), dtype=torch.float32, device=dev)
+    _check(packed_out, torch.int32, "packed_out")
+    _check(ranges_out, torch.float32, "ranges_out")
+    if packed_out.numel() < mqg_packed_words(n, bits) or ranges_out.numel() < 2 * mqg_num_buckets(n, bucket):
+        raise ValueError("output buffers too small")
+    pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    ra = (C.c_void_p * max(W, 1))(*[r.data_ptr() for r in ranges])
+    st = lib().mqg_aggregate_requantize_minmax(pa, ra, W, n, bits, bucket, packed_out.data_ptr(),
+                                               ranges_out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_requantize_minmax")
+    return packed_out, ranges_out
 
 
 def mqg_sum_squares(grad, out=None, stream=None):

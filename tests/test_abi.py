@@ -125,6 +125,14 @@ def test_multi_tensor_and_minmax_arguments_are_rejected_before_any_launch():
     assert a(ranges=(vp * 1)(0x1004)) == mqgrad.MQG_EALIGN
     assert a(ranges=(vp * 1)(None)) == mqgrad.MQG_EINVAL
     assert a(n=0, params=None) == mqgrad.MQG_OK
+    r = lambda packed=one, ranges=one, W=1, n=64, bits=4, bucket=512, po=fake, ro=fake: \
+        L.mqg_aggregate_requantize_minmax(packed, ranges, W, n, bits, bucket, po, ro, None)
+    assert r(W=0) == mqgrad.MQG_EINVAL
+    assert r(bits=0) == mqgrad.MQG_EINVAL
+    assert r(po=None) == mqgrad.MQG_EINVAL
+    assert r(ro=vp(0x1004)) == mqgrad.MQG_EALIGN
+    assert r(ranges=(vp * 1)(0x1004)) == mqgrad.MQG_EALIGN
+    assert r(n=0, po=None, ro=None) == mqgrad.MQG_OK
     assert L.mqg_sum_squares(fake, 10, None, None) == mqgrad.MQG_EINVAL
     assert L.mqg_sum_squares(None, 10, fake, None) == mqgrad.MQG_EINVAL
     assert L.mqg_sum_squares(fake, 10, vp(0x1004), None) == mqgrad.MQG_EALIGN

@@ -133,3 +133,36 @@ def test_adaptive_rule_from_gpu_norms():
         assert mqgrad.mqg_adaptive_bits(norms) == policy_ref.adaptive_bits(norms)
         assert mqgrad.mqg_adaptive_bits(norms) == policy_ref.adaptive_bits(want_norms) or \
             abs(sum(norms) / W / 0.0005 - round(sum(norms) / W / 0.0005)) < 1e-9
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("W,bucket", [(1, 32), (3, 96), (8, 1024), (4, 4096), (5, 8192), (2, 16384), (64, 32), (40, 64)])
+def test_requantize_minmax_matches_oracle(bits, W, bucket):
+    n = 2 * 16384 + 2048 + 13
+    grads = [workloads.normal(n, 0.01, 100 * w + bits, DEV) + 1e-3 * w for w in range(W)]
+    q = [mqgrad.mqg_quantize_minmax(g, bits, bucket) for g in grads]
+    pk, rg = mqgrad.mqg_aggregate_requantize_minmax([x[0] for x in q], [x[1] for x in q], n, bits, bucket)
+    torch.cuda.synchronize()
+    want_pk, want_rg = ref.aggregate_requantize_minmax([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n,
+                                                       bits, bucket)
+    assert rg.cpu().numpy().tobytes() == want_rg.tobytes()
+    assert np.array_equal(to_u32(pk), want_pk), first_mismatch(to_u32(pk), want_pk)
+
+
+def test_full_exchange_with_minmax_encoding_stays_on_the_oracle():
+    # Algorithm 1 with the footnote's encoder, several iterations: workers encode, the server re-encodes
+    # the mean, workers de-quantize and update
+    n, W, bucket, lr = 50000 + 7, 4, 512, 0.2
+    params = workloads.uniform(n, -0.05, 0.05, 1, DEV)
+    p_ref = params.cpu().numpy().copy()
+    for it, bits in enumerate((8, 2, 5, 1, 4)):
+        grads = [workloads.laplace(n, 1e-3, 10 * it + w, DEV) for w in range(W)]
+        q = [mqgrad.mqg_quantize_minmax(g, bits, bucket) for g in grads]
+        pk, rg = mqgrad.mqg_aggregate_requantize_minmax([x[0] for x in q], [x[1] for x in q], n, bits, bucket)
+        mqgrad.mqg_aggregate_update_minmax([pk], [rg], n, bits, bucket, lr, params)
+        torch.cuda.synchronize()
+        want = [ref.quantize_minmax(g.cpu().numpy(), bits, bucket) for g in grads]
+        m_pk, m_rg = ref.aggregate_requantize_minmax([x[0] for x in want], [x[1] for x in want], n, bits, bucket)
+        p_ref = ref.aggregate_update_minmax([m_pk], [m_rg], n, bits, bucket, lr, p_ref)
+        assert np.array_equal(to_u32(pk), m_pk)
+        assert ulp_distance(params.cpu().numpy(), p_ref).max() == 0, "iteration %d" % it

@@ -68,6 +68,11 @@ def test_random_case_matches_oracle(case):
     for w in range(W):
         assert qm[w][1].cpu().numpy().tobytes() == wm[w][1].tobytes(), "ranges of worker %d" % w
         assert np.array_equal(to_u32(qm[w][0]), wm[w][0])
+    mpk, mrg = mqgrad.mqg_aggregate_requantize_minmax([x[0] for x in qm], [x[1] for x in qm], n, bits, bucket)
+    torch.cuda.synchronize()
+    w_pk, w_rg = ref.aggregate_requantize_minmax([x[0] for x in wm], [x[1] for x in wm], n, bits, bucket)
+    assert mrg.cpu().numpy().tobytes() == w_rg.tobytes()
+    assert np.array_equal(to_u32(mpk), w_pk)
     mqgrad.mqg_aggregate_update_minmax([x[0] for x in qm], [x[1] for x in qm], n, bits, bucket, lr, params2)
     torch.cuda.synchronize()
     p1 = ref.aggregate_update_minmax([x[0] for x in wm], [x[1] for x in wm], n, bits, bucket, lr, p0)
