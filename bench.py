@@ -306,7 +306,7 @@ def main():
                     help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
                          "the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--cpu-sample", type=int, default=16_000_000)
-    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--cpu-steps", type=int, default=6)
     args = ap.parse_args()
 
     if args.gpus != 1:

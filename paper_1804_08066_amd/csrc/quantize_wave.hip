@@ -4,6 +4,7 @@
 // workgroup-cooperative kernel in quantize_pack.hip; both produce the same bits.)
 //
 //   a1  per-bucket range  s = max |g|           DPP / swizzle butterfly inside the wave
+//       (or the bucket's L2 norm: quad squares in fp32, a fp64 butterfly above them)
 //   a2  position on the 2^K-level grid          u = clamp(fma(g, (L/2)/s, L/2), 0, L)
 //   a3  stochastic rounding, Philox4x32-10      c = floor(u) + [(h + 1/2)/65536 < frac(u)]
 //   a4  dense little-endian bit packing         LDS-staged per wave, 128-bit stores
@@ -53,6 +54,8 @@ struct WaveShared {
     float smax[NW][8 * R];            // per-bucket max |g| of the chunk (<= CH/32 buckets)
     float ainv[NW][8 * R];            // per-bucket (L/2)/s
     float wave_max[NW];               // chunk maximum, for buckets that span several waves
+    double ssq[NW][8 * R];            // per-bucket sum of squares of the chunk (L2 scale only)
+    double wave_ssq[NW];
 };
 
 // ---- phase 1: load the chunk, clear the wave's packing area, publish the bucket maxima -----------
@@ -66,7 +69,7 @@ __device__ __forceinline__ void clear_words(uint32_t lane, uint32_t wave, WaveSh
 template <int R, int WPB, int NW>
 __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lane, uint32_t wave,
                                               const uint32_t (&slot)[R], uint32_t seg_lanes, uint32_t rpb,
-                                              WaveShared<R, NW>& sm);
+                                              WaveShared<R, NW>& sm, bool l2 = false);
 
 template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const float* __restrict__ g, uint32_t count,
@@ -92,14 +95,38 @@ __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const flo
     // clear the packing area of this wave while the loads are in flight (LDS is in order per wave)
     clear_words<R, NW>(lane, wave, sm);
     if (a.scales_in != nullptr) return;
-    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm);
+    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm, a.scale_mode == MQG_SCALE_L2);
 }
 
 // a1: bucket range of the values in registers
 template <int R, int WPB, int NW>
 __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lane, uint32_t wave,
                                               const uint32_t (&slot)[R], uint32_t seg_lanes, uint32_t rpb,
-                                              WaveShared<R, NW>& sm) {
+                                              WaveShared<R, NW>& sm, bool l2) {
+    if (l2) {
+        // L2 scale: squares of a quad in fp32, everything above in fp64, in a fixed order
+        double q[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            q[j] = (double)((x[j].x * x[j].x + x[j].y * x[j].y) + (x[j].z * x[j].z + x[j].w * x[j].w));
+        }
+#pragma unroll
+        for (int step = 1; step < R; step <<= 1) {
+            if (rpb > (uint32_t)step) {
+#pragma unroll
+                for (int j = 0; j + step < R; j += 2 * step) q[j] += q[j + step];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (((uint32_t)j & (rpb - 1u)) == 0u) {
+                double r = q[j];
+                for (uint32_t m = 1; m < seg_lanes; m <<= 1) r += __shfl_xor(r, (int)m, 64);   // uniform trip count
+                if ((lane & (seg_lanes - 1u)) == 0u) sm.ssq[wave][slot[j]] = r;
+            }
+        }
+        if (WPB > 1 && lane == 0u) sm.wave_ssq[wave] = sm.ssq[wave][0];
+    }
     float m[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -142,6 +169,12 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
 #pragma unroll
         for (int t = 1; t < WPB; ++t) r = fmaxf(r, sm.wave_max[w0 + t]);
         sm.smax[wave][0] = r;
+        if (a.scale_mode == MQG_SCALE_L2) {
+            double t = sm.wave_ssq[w0];
+#pragma unroll
+            for (int u = 1; u < WPB; ++u) t += sm.wave_ssq[w0 + u];
+            sm.ssq[wave][0] = t;
+        }
     }
     // one lane per bucket: floor, store the scale, divide once
     if (lane < nbc) {
@@ -152,6 +185,10 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
                 s = a.scales_in[kb_first + lane];
             } else {
                 s = sm.smax[wave][lane];
+                if (a.scale_mode == MQG_SCALE_L2) {   // the norm, raised to max |g| if rounding left it below
+                    const float norm = (float)__builtin_sqrt(sm.ssq[wave][lane]);
+                    s = norm < s ? s : norm;
+                }
                 if (!(s >= 0x1p-96f)) s = 0.0f;
             }
             if (WPB == 1 || (wave & (WPB - 1)) == 0u) a.scales[kb_first + lane] = (range_div == 1.0f) ? s : s / range_div;
@@ -375,10 +412,10 @@ hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-// True when the wave-local kernel covers this call: max-abs or injected scales, power-of-two bucket,
+// True when the wave-local kernel covers this call: power-of-two bucket,
 // 16-byte aligned gradient.
 bool quantize_wave_supported(const QuantizeArgs& a) {
-    return a.bucket_shift >= 5 && a.scale_mode == MQG_SCALE_MAXABS &&
+    return a.bucket_shift >= 5 &&
            (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
 }
 
