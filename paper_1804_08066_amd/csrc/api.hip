@@ -204,8 +204,11 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
     a.common.packed = nullptr;
     a.common.scales = nullptr;
     a.count = count;
-    a.tile_elems = mqg::quantize_batch_tile(bucket);
     bool aligned = true;
+    for (uint32_t i = 0; i < count; ++i) {
+        if (items[i].n != 0 && (reinterpret_cast<uintptr_t>(items[i].grad) & 15u) != 0) aligned = false;
+    }
+    a.tile_elems = mqg::quantize_batch_tile(bucket, a.common.bucket_shift, aligned);
     uint64_t tiles = 0;
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
         a.tile_start[i] = (uint32_t)tiles;
@@ -218,7 +221,6 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
         if (it.grad == nullptr || it.packed_out == nullptr || it.scales_out == nullptr) return MQG_EINVAL;
         if (it.n > (UINT64_MAX >> 4) || it.elem_base > UINT64_MAX - it.n) return MQG_EINVAL;
         if (misaligned4(it.grad) || misaligned4(it.packed_out) || misaligned4(it.scales_out)) return MQG_EALIGN;
-        if ((reinterpret_cast<uintptr_t>(it.grad) & 15u) != 0) aligned = false;
         t = mqg::BatchQuantizeArgs::Tensor{it.grad, it.n, it.elem_base, it.packed_out, it.scales_out};
         tiles += (it.n + a.tile_elems - 1) / a.tile_elems;
         if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;

@@ -461,13 +461,18 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
     return launch_r<16>(a, stream);
 }
 
-uint32_t quantize_batch_tile(uint32_t bucket) {
+// Power-of-two buckets on 16-byte aligned gradients take the wave-local kernel, like single calls.
+static bool batch_takes_wave_kernel(int bucket_shift, bool aligned) { return aligned && bucket_shift >= 5; }
+
+uint32_t quantize_batch_tile(uint32_t bucket, int bucket_shift, bool aligned) {
+    if (batch_takes_wave_kernel(bucket_shift, aligned)) return quantize_wave_block_elems(bucket);
     const uint32_t cap = bucket <= 4096u ? Tile<4>::kCap : (bucket <= 8192u ? Tile<8>::kCap : Tile<16>::kCap);
     return (cap / bucket) * bucket;
 }
 
 hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
     if (tiles == 0) return hipSuccess;
+    if (batch_takes_wave_kernel(a.common.bucket_shift, aligned)) return launch_quantize_tensors_wave(a, tiles, stream);
     if (a.common.bucket <= 4096u) return launch_tensors_r<4>(a, tiles, aligned, stream);
     if (a.common.bucket <= 8192u) return launch_tensors_r<8>(a, tiles, aligned, stream);
     return launch_tensors_r<16>(a, tiles, aligned, stream);

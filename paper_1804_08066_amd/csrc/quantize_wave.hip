@@ -259,14 +259,13 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
 // R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; otherwise bucket = WPB*CH);
 // NW: waves per workgroup, a multiple of WPB
 template <int R, int WPB, int NW>
-__global__ __launch_bounds__(64 * NW) void quantize_wave_kernel(const QuantizeArgs a) {
+__device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const uint64_t block, WaveShared<R, NW>& sm) {
     constexpr uint32_t CH = 256u * R;
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
-    __shared__ WaveShared<R, NW> sm;
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u, wave = tid >> 6;
-    const uint64_t chunk = (uint64_t)blockIdx.x * NW + wave;
+    const uint64_t chunk = block * NW + wave;
     const uint64_t cb = chunk * CH;                 // first element of the chunk
     const bool active = cb < a.n;                   // waves past the end only keep the barrier company
     const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
@@ -296,6 +295,31 @@ __global__ __launch_bounds__(64 * NW) void quantize_wave_kernel(const QuantizeAr
     } else {
         quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm);
     }
+}
+
+template <int R, int WPB, int NW>
+__global__ __launch_bounds__(64 * NW) void quantize_wave_kernel(const QuantizeArgs a) {
+    __shared__ WaveShared<R, NW> sm;
+    quantize_wave_block<R, WPB, NW>(a, blockIdx.x, sm);
+}
+
+// Several layer tensors of one worker in one launch: workgroup -> (tensor, block of the tensor) through
+// the prefix table of block counts.
+template <int R, int WPB, int NW>
+__global__ __launch_bounds__(64 * NW) void quantize_tensors_wave_kernel(const BatchQuantizeArgs ba) {
+    __shared__ WaveShared<R, NW> sm;
+    uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= ba.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    QuantizeArgs a = ba.common;
+    a.grad = ba.t[lo].grad;
+    a.n = ba.t[lo].n;
+    a.elem_base = ba.t[lo].elem_base;
+    a.packed = ba.t[lo].packed;
+    a.scales = ba.t[lo].scales;
+    quantize_wave_block<R, WPB, NW>(a, blockIdx.x - ba.tile_start[lo], sm);
 }
 
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
@@ -417,6 +441,21 @@ hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
 bool quantize_wave_supported(const QuantizeArgs& a) {
     return a.bucket_shift >= 5 &&
            (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
+}
+
+// elements per workgroup of the wave-local kernel at this bucket size
+uint32_t quantize_wave_block_elems(uint32_t bucket) { return bucket <= 4096u ? 4096u : bucket; }
+
+hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
+    const dim3 grid(blocks);
+    switch (a.common.bucket) {
+        case 2048: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 2, 4>), grid, dim3(256), 0, stream, a); break;
+        case 4096: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 4, 4>), grid, dim3(256), 0, stream, a); break;
+        case 8192: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 8, 8>), grid, dim3(512), 0, stream, a); break;
+        case 16384: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 16, 16>), grid, dim3(1024), 0, stream, a); break;
+        default: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 1, 4>), grid, dim3(256), 0, stream, a); break;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {

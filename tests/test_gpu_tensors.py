@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("bucket", [96, 512, 8192])
+@pytest.mark.parametrize("bucket", [96, 512, 2048, 8192, 16384])
 def test_batched_quantize_equals_per_tensor_and_oracle(bucket):
     sizes = [n for _, n in workloads.SMALL_CNN_SHAPES] + [0, 1, 40000 + 3]
     bases, run = [], 0
