@@ -99,9 +99,30 @@ def time_config(wl, bits, bucket, lr, steps, warmup):
     run_steps(wl, bits, bucket, lr, steps, warmup, events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    q_ms = sum(e[0].elapsed_time(e[1]) for e in events) / (steps * wl.W)     # per quantize launch
-    a_ms = sum(e[1].elapsed_time(e[2]) for e in events) / steps              # per aggregate launch
+    q_all = sorted(e[0].elapsed_time(e[1]) / wl.W for e in events)           # per quantize launch, one value per step
+    a_all = sorted(e[1].elapsed_time(e[2]) for e in events)                  # per aggregate launch
+    q_ms, a_ms = sum(q_all) / steps, sum(a_all) / steps
+    time_config.last = {"quantize_us_median": q_all[steps // 2] * 1e3, "quantize_us_min": q_all[0] * 1e3,
+                        "aggregate_us_median": a_all[steps // 2] * 1e3, "aggregate_us_min": a_all[0] * 1e3}
     return (t1 - t0) / steps * 1e3, q_ms, a_ms
+
+
+def copy_ceiling(wl, reps=30):
+    """A plain device copy of one gradient buffer (4n bytes read + 4n written): what this machine's HBM
+    delivers to the simplest streaming kernel, the practical ceiling beside the 8 TB/s peak."""
+    import torch
+    dst = torch.empty_like(wl.grads[0])
+    for k in range(10):
+        dst.copy_(wl.grads[k % wl.W])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    ev[0].record()
+    for k in range(reps):
+        dst.copy_(wl.grads[k % wl.W])
+        ev[k + 1].record()
+    torch.cuda.synchronize()
+    ts = sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(reps))
+    del dst
+    return 8.0 * wl.n / (ts[reps // 2] * 1e-3) / 1e9
 
 
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 compute units x 64 lanes per clock x 2.4 GHz, one-lane-op units
@@ -278,9 +299,34 @@ def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
         params = ref.aggregate_update([o[0] for o in outs], [o[1] for o in outs], sample_n, bits, bucket, lr, params)
     dt = time.perf_counter() - t0
     gbs = 4.0 * sample_n * W * steps / dt / 1e9
-    return {"value": gbs, "unit": "GB/s fp32 gradient", "cores": 1, "kind": "oracle",
-            "sample": "%d-element slice of the same workload, W=%d, b=%d, bucket=%d, %d step(s), %.1f s"
-                      % (sample_n, W, bits, bucket, steps, dt)}
+    res = {"value": gbs, "unit": "GB/s fp32 gradient", "cores": 1, "kind": "oracle",
+           "sample": "%d-element slice of the same workload, W=%d, b=%d, bucket=%d, %d step(s), %.1f s"
+                     % (sample_n, W, bits, bucket, steps, dt)}
+
+    # the same single-threaded functions called over disjoint bucket ranges from one thread per core
+    # (the random stream is counter based: a range is evaluated in isolation with elem_base = its start)
+    from concurrent.futures import ThreadPoolExecutor
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    span = ((sample_n + cores - 1) // cores + bucket * 32 - 1) // (bucket * 32) * (bucket * 32)
+    ranges = [(lo, min(sample_n, lo + span)) for lo in range(0, sample_n, span)]
+    params = workloads.uniform(sample_n, -0.05, 0.05, 1, "cpu").numpy()
+
+    def one_range(args):
+        k, lo, hi = args
+        outs = [ref.quantize(grads[w][lo:hi], bits, bucket, 1234, k, w, lo) for w in range(W)]
+        params[lo:hi] = ref.aggregate_update([o[0] for o in outs], [o[1] for o in outs], hi - lo, bits, bucket, lr,
+                                             params[lo:hi])
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        for k in range(steps):
+            list(pool.map(one_range, [(k, lo, hi) for lo, hi in ranges]))
+    dt = time.perf_counter() - t0
+    res["all_cores"] = {"value": 4.0 * sample_n * W * steps / dt / 1e9, "unit": "GB/s fp32 gradient",
+                        "cores": min(cores, len(ranges)), "kind": "oracle over disjoint bucket ranges, one thread per range",
+                        "sample": "same slice, %d step(s), %.1f s" % (steps, dt)}
+    log("cpu baseline: 1 core %.3f GB/s, %d cores %.3f GB/s" % (gbs, res["all_cores"]["cores"], res["all_cores"]["value"]))
+    return res
 
 
 def main():
@@ -332,6 +378,10 @@ def main():
     log("step %.3f ms | quantize %.1f us/launch %.0f GB/s | aggregate %.1f us %.0f GB/s" %
         (ms_step, q_ms * 1e3, q_gbs, a_ms * 1e3, a_gbs))
 
+    spread = dict(time_config.last)
+    copy_gbs = copy_ceiling(wl)
+    log("plain copy (torch copy_) of one gradient buffer: %.0f GB/s = %.1f%% of peak" % (copy_gbs, 100 * copy_gbs / HBM_PEAK_GBS))
+
     q_traffic, a_traffic = MEASURED_TRAFFIC.get((n, W, bits, bucket), (None, None))
     out = {
         "metric": "GB/s fp32 gradient quantize+pack and unpack+aggregate+update; % HBM peak",
@@ -345,11 +395,16 @@ def main():
         # the quantize kernel runs W times per step and is the dominant kernel by time
         "roofline": {"bound": "hbm", "kernel": "quantize_wave_kernel", "achieved": q_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": q_gbs / HBM_PEAK_GBS, "traffic": q_traffic,
-                     "algorithmic_bytes_per_launch": qb, "avg_launch_us": q_ms * 1e3},
+                     "algorithmic_bytes_per_launch": qb, "avg_launch_us": q_ms * 1e3,
+                     "median_launch_us": spread["quantize_us_median"], "min_launch_us": spread["quantize_us_min"],
+                     "frac_of_copy_ceiling": q_gbs / copy_gbs},
         "roofline_aggregate": {"bound": "hbm", "kernel": "aggregate_update_rows_kernel", "achieved": a_gbs,
                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a_gbs / HBM_PEAK_GBS, "traffic": a_traffic,
-                               "algorithmic_bytes_per_launch": ab, "avg_launch_us": a_ms * 1e3},
+                               "algorithmic_bytes_per_launch": ab, "avg_launch_us": a_ms * 1e3,
+                               "median_launch_us": spread["aggregate_us_median"], "min_launch_us": spread["aggregate_us_min"],
+                               "frac_of_copy_ceiling": a_gbs / copy_gbs},
         "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "copy_ceiling": {"kernel": "torch copy_ of one gradient buffer", "gbs": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS},
     }
 
     if args.sweep:
