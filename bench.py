@@ -159,7 +159,7 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
     nb = (n + bucket - 1) // bucket
     r_bytes = (W + 1) * (n * bits / 8.0 + 4.0 * nb)
     d_bytes = n * bits / 8.0 + 4.0 * nb + 8.0 * n
-    r_ops = n * (4.0 * W + 17.0)
+    r_ops = n * ((3.0 if bits in (1, 8) else 4.0) * W + 17.0)   # 1 and 8 bits decode in three operations
     log("exchange: requantize %.1f us (%.1f T lane-ops/s, %.0f GB/s), dequantize_update %.1f us (%.0f GB/s)" %
         (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9))
     return {

@@ -43,7 +43,7 @@ using decode::accumulate_quad;
 using decode::readlane_f32;
 // ---- buckets that are multiples of 128: bucket steps live in the wave ---------------------------
 // NBR = buckets a 256-element row can touch: 1 when the bucket is a multiple of 256, else 2.
-template <int R, int NBR, bool STRADDLE, bool ALIGNED, bool ONCE>
+template <int R, int NBR, bool STRADDLE, bool ALIGNED, bool ONCE, int WIDTH>
 __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const AggregateArgs a) {
     constexpr uint32_t TILE = 1024u * R;
     const uint32_t tid = threadIdx.x;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
                 for (int j = 0; j < R; ++j) {
                     float dw = readlane_f32(d[j][0], w0 + t);
                     if (NBR > 1) dw = second[j] ? readlane_f32(d[j][NBR - 1], w0 + t) : dw;
-                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], b, negL, dw, acc[j]);
+                    decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], b, negL, dw, acc[j]);
                 }
             }
         }
@@ -246,8 +246,18 @@ hipError_t launch_rows(const AggregateArgs& a, hipStream_t stream) {
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
+    if (a.bits == 1u || a.bits == 8u) {   // three-operation decodes; neither width straddles words
+        if (a.bits == 1u) {
+            if (aligned) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, true, false, 1>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, false, 1>), grid, block, 0, stream, a);
+        } else {
+            if (aligned) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, true, true, 8>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, true, 8>), grid, block, 0, stream, a);
+        }
+        return hipGetLastError();
+    }
     with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
-        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(al)::value, decltype(once)::value>),
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(al)::value, decltype(once)::value, 0>),
                            grid, block, 0, stream, a);
     });
     return hipGetLastError();

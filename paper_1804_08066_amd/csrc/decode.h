@@ -114,6 +114,47 @@ __device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32
     acc.w = __builtin_fmaf((float)(2 * k[3] + negL), d, acc.w);
 }
 
+// One-bit codes: (2c - L) is +1 or -1, so the fma of the chain is an exactly rounded add or subtract
+// of d.  The code bit is shifted to the sign position and XOR-ed into d with one three-input bitwise
+// operation ((a & b) ^ c has the truth table 0x6A for a = 0xF0, b = 0xCC, c = 0xAA); what is
+// subtracted is -d for a set bit and +d for a clear one: three vector operations per element
+// instead of four, bit-identical results.
+__device__ __forceinline__ float minus_signed_step(uint32_t word, uint32_t shl, float d) {
+    const uint32_t t = word << shl;   // code bit at bit 31
+    const int r = __builtin_amdgcn_bitop3_b32((int)t, (int)0x80000000u, __builtin_bit_cast(int, d), 0x6A);
+    return __builtin_bit_cast(float, r);
+}
+__device__ __forceinline__ void accumulate_quad_onebit(uint32_t lo, uint32_t sh, float d, float4& acc) {
+    acc.x = acc.x - minus_signed_step(lo, 31u - sh, d);
+    acc.y = acc.y - minus_signed_step(lo, 30u - sh, d);
+    acc.z = acc.z - minus_signed_step(lo, 29u - sh, d);
+    acc.w = acc.w - minus_signed_step(lo, 28u - sh, d);
+}
+
+// Eight-bit codes: a quad is the four bytes of one word, and a byte converts to fp32 in one
+// instruction (v_cvt_f32_ubyte0..3); 2c - 255 is then one exact fma, so the chain's fma sees the same
+// multiplier as in the general path: three vector operations per element instead of four.
+__device__ __forceinline__ void accumulate_quad_bytes(uint32_t lo, float d, float4& acc) {
+    const float k0 = (float)(lo & 0xFFu), k1 = (float)((lo >> 8) & 0xFFu);
+    const float k2 = (float)((lo >> 16) & 0xFFu), k3 = (float)(lo >> 24);
+    acc.x = __builtin_fmaf(__builtin_fmaf(k0, 2.0f, -255.0f), d, acc.x);
+    acc.y = __builtin_fmaf(__builtin_fmaf(k1, 2.0f, -255.0f), d, acc.y);
+    acc.z = __builtin_fmaf(__builtin_fmaf(k2, 2.0f, -255.0f), d, acc.z);
+    acc.w = __builtin_fmaf(__builtin_fmaf(k3, 2.0f, -255.0f), d, acc.w);
+}
+
+// Dispatch on the width class: WIDTH = 1 or 8 select the three-operation forms above, 0 the general one.
+template <bool STRADDLE, int WIDTH>
+__device__ __forceinline__ void accumulate_quad_w(uint32_t lo, uint32_t sh, uint32_t b, int negL, float d, float4& acc) {
+    if (WIDTH == 1) {
+        accumulate_quad_onebit(lo, sh, d, acc);
+    } else if (WIDTH == 8) {
+        accumulate_quad_bytes(lo, d, acc);
+    } else {
+        accumulate_quad<STRADDLE>(lo, sh, b, negL, d, acc);
+    }
+}
+
 // The same for the [min, max] encoding: value = fma((float)c, step, min), acc <- acc + value.
 template <bool STRADDLE>
 __device__ __forceinline__ void accumulate_quad_minmax(uint32_t lo, uint32_t sh, uint32_t b, float step,

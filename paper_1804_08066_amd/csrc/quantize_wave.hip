@@ -328,7 +328,7 @@ __global__ __launch_bounds__(64 * NW) void quantize_tensors_wave_kernel(const Ba
 // exactly as a gradient would be; the stored range is divided by W.  Buckets of 256 elements and more:
 // a wave's 256-element row lies in one bucket, so lane w divides worker w's scale of each row once
 // and the worker loop broadcasts it with v_readlane (no LDS table, no barrier).
-template <int R, int WPB, int NW, bool STRADDLE, bool ONCE>
+template <int R, int WPB, int NW, bool STRADDLE, bool ONCE, int WIDTH>
 __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantArgs ra) {
     constexpr uint32_t CH = 256u * R;
     constexpr int kChunk = 32 / R;   // workers whose code loads are in flight together
@@ -380,7 +380,8 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
                 if (w0 + t < ra.W) {
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
-                        decode::accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], b, negL, decode::readlane_f32(d[j], w0 + t), x[j]);
+                        const float dw = decode::readlane_f32(d[j], w0 + t);
+                        decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], b, negL, dw, x[j]);
                     }
                 }
             }
@@ -415,12 +416,16 @@ hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     const dim3 grid((uint32_t)groups), block(64 * NW);
     const bool straddle = (32u % ra.q.bits) != 0u;
     const bool once = decode::codes_read_once(ra.q.bits);
-    if (straddle) {
-        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, true>), grid, block, 0, stream, ra);
-        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, false>), grid, block, 0, stream, ra);
+    if (ra.q.bits == 1u) {          // three-operation decodes at 1 and 8 bits
+        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, false, 1>), grid, block, 0, stream, ra);
+    } else if (ra.q.bits == 8u) {
+        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, true, 8>), grid, block, 0, stream, ra);
+    } else if (straddle) {
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, true, 0>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, false, 0>), grid, block, 0, stream, ra);
     } else {
-        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, true>), grid, block, 0, stream, ra);
-        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, false>), grid, block, 0, stream, ra);
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, true, 0>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, false, 0>), grid, block, 0, stream, ra);
     }
     return hipGetLastError();
 }
