@@ -261,9 +261,10 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
     ss = torch.empty(1, dtype=torch.float64, device=wl.device)
     mpk = torch.empty_like(pk[0])
     mrg = torch.empty_like(rg[0])
+    trg = torch.zeros(2, dtype=torch.float32, device=wl.device)
     ev = []
     for k in range(warmup + steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
         e[0].record()
         for w in range(W):
             mqgrad.mqg_quantize_minmax(wl.grads[w], bits, bucket, pk[w], rg[w])
@@ -275,6 +276,8 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
         e[3].record()
         mqgrad.mqg_aggregate_requantize_minmax(pk, rg, n, bits, bucket, mpk, mrg)
         e[4].record()
+        mqgrad.mqg_quantize_minmax_tensor(wl.grads[k % W], bits, mpk, trg)
+        e[5].record()
         if k >= warmup:
             ev.append(e)
     torch.cuda.synchronize()
@@ -282,16 +285,18 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
     a_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
     s_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / len(ev) / W
     r_ms = sum(e[3].elapsed_time(e[4]) for e in ev) / len(ev)
+    t_ms = sum(e[4].elapsed_time(e[5]) for e in ev) / len(ev)
     nb = (n + bucket - 1) // bucket
     q_bytes = n * (4.0 + bits / 8.0) + 8.0 * nb
     a_bytes = W * (n * bits / 8.0 + 8.0 * nb) + 8.0 * n
     s_bytes = 4.0 * n
+    t_bytes = n * (8.0 + bits / 8.0)   # two passes over the gradient (range, then encode)
     frac = lambda by, ms: by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
     r_ops = n * (4.0 * W + 12.0)   # decode: extract, convert, fma, add per worker; encode about 12
     log("minmax b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%), sum_squares %.1f us (%.1f%%), "
-        "requantize %.1f us (%.1f T lane-ops/s)" %
+        "requantize %.1f us (%.1f T lane-ops/s), whole-tensor range + encode %.1f us (%.1f%%)" %
         (bits, bucket, q_ms * 1e3, 100 * frac(q_bytes, q_ms), a_ms * 1e3, 100 * frac(a_bytes, a_ms), s_ms * 1e3,
-         100 * frac(s_bytes, s_ms), r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12))
+         100 * frac(s_bytes, s_ms), r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, t_ms * 1e3, 100 * frac(t_bytes, t_ms)))
     row = lambda name, by, ms: {"kernel": name, "avg_launch_us": ms * 1e3, "bound": "hbm", "unit": "GB/s",
                                 "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "frac": frac(by, ms),
                                 "algorithmic_bytes_per_launch": by}
@@ -299,6 +304,7 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
             "quantize_minmax": row("quantize_minmax_kernel", q_bytes, q_ms),
             "aggregate_update_minmax": row("aggregate_update_minmax_kernel", a_bytes, a_ms),
             "sum_squares": row("sum_squares_kernel", s_bytes, s_ms),
+            "quantize_minmax_tensor": row("tensor_range_kernel + quantize_minmax_kernel", t_bytes, t_ms),
             "requantize_minmax": {"kernel": "requantize_minmax_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
                                   "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
                                   "unit": "T lane-ops/s", "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,

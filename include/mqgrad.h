@@ -224,6 +224,23 @@ mqg_status mqg_aggregate_requantize_minmax(const uint32_t* const* packed, const 
                                            uint64_t n, uint32_t bits, uint32_t bucket,
                                            uint32_t* packed_out, float* ranges_out, void* stream);
 
+/* One range for the whole tensor, as the paper encodes (any n; the bucketed calls above stop at buckets
+ * of MQG_MAX_BUCKET elements).
+ *
+ * mqg_tensor_range: range_out[0] = min, range_out[1] = max of grad[0..n) (a zero bound as +0).
+ *   range_out  device, 2 floats, 8-byte aligned.  n = 0 leaves it untouched.
+ * mqg_quantize_minmax_tensor: mqg_tensor_range followed by the encode of mqg_quantize_minmax with that
+ *   one (mn, mx) for every element -- two passes over the gradient, on the same stream.
+ * mqg_aggregate_update_minmax_tensor: the server step with one (mn, mx) pair per worker.
+ *   ranges  HOST array of W device pointers, each to 2 floats (8-byte aligned).
+ * Arithmetic, packed layout and errors as for the bucketed calls. */
+mqg_status mqg_tensor_range(const float* grad, uint64_t n, float* range_out, void* stream);
+mqg_status mqg_quantize_minmax_tensor(const float* grad, uint64_t n, uint32_t bits,
+                                      uint32_t* packed_out, float* range_out, void* stream);
+mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, const float* const* ranges,
+                                              uint32_t W, uint64_t n, uint32_t bits,
+                                              float lr, float* params, void* stream);
+
 /* ---- the "Adaptive" baseline's bit rule (Section 4.1; idea in Section 2: the larger the gradient's
  * norm, the more bits) ------------------------------------------------------------------------------
  *

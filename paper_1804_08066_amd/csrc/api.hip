@@ -130,6 +130,7 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
     a.bucket_shift = log2_if_pow2(bucket);
     a.neg_c = -(lr / (float)W);
     a.params = params;
+    a.per_tensor = 0u;
     const hipError_t err = mqg::launch_aggregate(a, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
@@ -333,6 +334,7 @@ mqg_status mqg_aggregate_update_minmax(const uint32_t* const* packed, const floa
     a.bucket_shift = log2_if_pow2(bucket);
     a.neg_c = -(lr / (float)W);
     a.params = params;
+    a.per_tensor = 0u;
     const hipError_t err = mqg::launch_aggregate_minmax(a, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
@@ -361,6 +363,69 @@ mqg_status mqg_aggregate_requantize_minmax(const uint32_t* const* packed, const 
     ra.q.packed = packed_out;
     ra.q.scales = ranges_out;
     const hipError_t err = mqg::launch_requantize_minmax(ra, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_tensor_range(const float* grad, uint64_t n, float* range_out, void* stream) {
+    if (n == 0) return MQG_OK;
+    if (grad == nullptr || range_out == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(grad) || misaligned8(range_out)) return MQG_EALIGN;
+    const hipError_t err = mqg::launch_tensor_range(grad, n, range_out, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_quantize_minmax_tensor(const float* grad, uint64_t n, uint32_t bits,
+                                      uint32_t* packed_out, float* range_out, void* stream) {
+    if (bits < 1u || bits > 8u) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (grad == nullptr || packed_out == nullptr || range_out == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(grad) || misaligned4(packed_out) || misaligned8(range_out)) return MQG_EALIGN;
+    hipError_t err = mqg::launch_tensor_range(grad, n, range_out, static_cast<hipStream_t>(stream));
+    if (err != hipSuccess) return MQG_ELAUNCH;
+    mqg::QuantizeArgs a = {};
+    a.grad = grad;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = 4096u;            // tiling only: every tile takes the one range in scales_in
+    a.bucket_shift = 12;
+    a.scales_in = range_out;
+    a.packed = packed_out;
+    a.scales = nullptr;          // not written when the range is given
+    err = mqg::launch_quantize_minmax(a, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, const float* const* ranges,
+                                              uint32_t W, uint64_t n, uint32_t bits,
+                                              float lr, float* params, void* stream) {
+    if (bits < 1u || bits > 8u) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (packed == nullptr || ranges == nullptr || params == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(params)) return MQG_EALIGN;
+    mqg::AggregateArgs a;
+    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
+        a.packed[w] = nullptr;
+        a.scales[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
+        a.packed[w] = packed[w];
+        a.scales[w] = ranges[w];
+    }
+    a.W = W;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = 1024u;            // tiling only: one (min, max) pair per worker
+    a.bucket_shift = 10;
+    a.neg_c = -(lr / (float)W);
+    a.params = params;
+    a.per_tensor = 1u;
+    const hipError_t err = mqg::launch_aggregate_minmax(a, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 

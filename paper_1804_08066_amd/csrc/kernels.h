@@ -17,7 +17,8 @@ struct QuantizeArgs {
     uint32_t key0, key1;     // Philox key = seed
     uint32_t iteration, worker;
     uint64_t elem_base;      // multiple of 8
-    const float* scales_in;  // nullable: when set, scales are read, not computed
+    const float* scales_in;  // nullable: when set, scales are read, not computed ([min, max] encoding: ONE
+                             // (min, max) pair that holds for the whole tensor)
     uint32_t* packed;        // ceil(n*bits/32) words
     float* scales;           // ceil(n/bucket) floats
 };
@@ -32,6 +33,7 @@ struct AggregateArgs {
     int bucket_shift;
     float neg_c;             // -(lr / W)
     float* params;
+    uint32_t per_tensor;     // [min, max] encoding only: every worker has ONE (min, max) pair for the whole tensor
 };
 
 // Server side of the full exchange: quantize the sum over W workers' de-quantized gradients
@@ -96,6 +98,7 @@ hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream);
 hipError_t launch_requantize_minmax(const RequantArgs& a, hipStream_t stream);
+hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, hipStream_t stream);
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream);
 
 }  // namespace mqg

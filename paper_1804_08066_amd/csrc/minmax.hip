@@ -24,6 +24,7 @@ using namespace encode;
 using tile_io::kThreads;
 
 constexpr int kChunk = 8;   // workers whose code loads are in flight together
+constexpr uint32_t kSumBlocks = 2048;   // workgroups of the whole-tensor reductions (8 per compute unit)
 
 // fp32 -> uint32 whose unsigned order is the order of the floats
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -84,7 +85,7 @@ __device__ __forceinline__ void clear_shared(Shared<R, NT>& sm, uint32_t tile_co
 // The tile, once its values are in registers; enters right after the barrier that follows
 // clear_shared.  range_div: the stored range is [mn, mx] / range_div (1 for a plain encode, W for the
 // server's mean).
-template <int R, int NT, bool FULL>
+template <int R, int NT, bool FULL, bool GIVEN = false>
 __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
                                                    const uint32_t tile_count, const float4 (&x)[R],
                                                    const float range_div, Shared<R, NT>& sm) {
@@ -108,6 +109,8 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
     constexpr bool kOne = Shared<R, NT>::kOneBucket;
     const uint32_t lane = tid & 63u;
     const bool row_in_bucket = kOne || (a.bucket & 255u) == 0u;   // uniform over the launch
+    constexpr bool given = GIVEN;                                 // one range for the whole tensor, computed before
+    if (!given) {
     float lo[R], hi[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -154,15 +157,23 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
             }
         }
     }
+    }   // !given
     __syncthreads();
 
     const float Lf = (float)((1u << b) - 1u);
     if (tid < nbt) {
-        float mn = key_value(sm.kmin[tid]), mx = key_value(sm.kmax[tid]);
-        if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
-        if (mx == 0.0f) mx = 0.0f;
-        a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
-        a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
+        float mn, mx;
+        if (given) {
+            mn = a.scales_in[0];
+            mx = a.scales_in[1];
+        } else {
+            mn = key_value(sm.kmin[tid]);
+            mx = key_value(sm.kmax[tid]);
+            if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
+            if (mx == 0.0f) mx = 0.0f;
+            a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
+            a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
+        }
         const float r = mx - mn;
         sm.mn[tid] = mn;
         sm.a[tid] = (r >= 0x1p-96f) ? Lf / r : 0.0f;   // IEEE-correct fp32 division, once per bucket
@@ -203,7 +214,8 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
     for (uint32_t i = tid; i < nwords; i += NT) __builtin_nontemporal_store(sm.words[i], out + i);
 }
 
-template <int R, int NT, bool ALIGNED>
+// GIVEN: the range is read from a.scales_in (one pair for the whole tensor) instead of computed per bucket
+template <int R, int NT, bool ALIGNED, bool GIVEN>
 __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
     __shared__ Shared<R, NT> sm;
     const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
@@ -214,12 +226,12 @@ __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs 
         load_grad_tile<R, NT, ALIGNED, true>(a.grad + tile_base, tile_count, x);
         clear_shared<R, NT>(sm, tile_count, a.bits);   // while the loads are in flight
         __syncthreads();
-        encode_minmax_tile<R, NT, true>(a, tile_base, tile_count, x, 1.0f, sm);
+        encode_minmax_tile<R, NT, true, GIVEN>(a, tile_base, tile_count, x, 1.0f, sm);
     } else {
         load_grad_tile<R, NT, ALIGNED, false>(a.grad + tile_base, tile_count, x);
         clear_shared<R, NT>(sm, tile_count, a.bits);
         __syncthreads();
-        encode_minmax_tile<R, NT, false>(a, tile_base, tile_count, x, 1.0f, sm);
+        encode_minmax_tile<R, NT, false, GIVEN>(a, tile_base, tile_count, x, 1.0f, sm);
     }
 }
 
@@ -325,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
     }
     for (uint32_t i = tid; i < a.W * nbt; i += kThreads) {
         const uint32_t w = i / nbt, kb = i - w * nbt;
-        const float2 rg = reinterpret_cast<const float2*>(a.scales[w])[kb0 + kb];   // (min, max)
+        const float2 rg = reinterpret_cast<const float2*>(a.scales[w])[a.per_tensor ? 0u : kb0 + kb];   // (min, max)
         s_tab[i] = make_float2((rg.y - rg.x) / Lf, rg.x);                           // IEEE-correct fp32 division
     }
     __syncthreads();
@@ -347,11 +359,87 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
     tile_io::update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
 }
 
+// ---- whole-tensor range ---------------------------------------------------------------------------
+// The paper encodes a tensor over ONE range.  Three launches on the stream: a one-thread kernel
+// primes range[0..1] with the identity keys, the reduction folds every workgroup's min / max into them
+// with integer atomics on order-preserving keys (exact and order-independent), a one-thread kernel
+// turns the keys back into floats (a zero bound as +0).
+__global__ void range_init_kernel(uint32_t* keys) {
+    keys[0] = 0xFFFFFFFFu;
+    keys[1] = 0u;
+}
+
+__global__ void range_finish_kernel(uint32_t* keys) {
+    float mn = key_value(keys[0]), mx = key_value(keys[1]);
+    if (mn == 0.0f) mn = 0.0f;
+    if (mx == 0.0f) mx = 0.0f;
+    keys[0] = __builtin_bit_cast(uint32_t, mn);
+    keys[1] = __builtin_bit_cast(uint32_t, mx);
+}
+
+__global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __restrict__ g, const uint64_t n,
+                                                                const uint32_t head, uint32_t* keys) {
+    __shared__ float s_lo[kThreads / 64], s_hi[kThreads / 64];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t gtid = (uint64_t)blockIdx.x * kThreads + tid;
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    if (gtid < head) {   // `head` leading elements bring the rest to a 16-byte boundary
+        lo = hi = g[gtid];
+    }
+    const v4f* __restrict__ g4 = reinterpret_cast<const v4f*>(g + head);
+    const uint64_t nq = (n - head) >> 2;
+    const uint64_t pieces = nq >> 10;   // contiguous 16 KB pieces, four float4 per lane in flight
+    for (uint64_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
+        const v4f* __restrict__ src = g4 + (pc << 10) + tid;
+        v4f t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(src + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            lo = fminf(lo, fminf(fminf(t[u].x, t[u].y), fminf(t[u].z, t[u].w)));
+            hi = fmaxf(hi, fmaxf(fmaxf(t[u].x, t[u].y), fmaxf(t[u].z, t[u].w)));
+        }
+    }
+    for (uint64_t q = (pieces << 10) + gtid; q < nq; q += stride) {
+        const v4f t = g4[q];
+        lo = fminf(lo, fminf(fminf(t.x, t.y), fminf(t.z, t.w)));
+        hi = fmaxf(hi, fmaxf(fmaxf(t.x, t.y), fmaxf(t.z, t.w)));
+    }
+    const uint64_t tail0 = head + (nq << 2);
+    if (gtid < n - tail0) {
+        const float v = g[tail0 + gtid];
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    }
+    lo = fminf(lo, dpp_f32<kDppQuadSwap1>(lo));
+    hi = fmaxf(hi, dpp_f32<kDppQuadSwap1>(hi));
+    lo = fminf(lo, dpp_f32<kDppQuadSwap2>(lo));
+    hi = fmaxf(hi, dpp_f32<kDppQuadSwap2>(hi));
+    lo = fminf(lo, dpp_f32<kDppRowHalfMirror>(lo));
+    hi = fmaxf(hi, dpp_f32<kDppRowHalfMirror>(hi));
+    lo = wave_min_from_cells(lo, tid & 63u);
+    hi = wave_max_from_cells(hi, tid & 63u);
+    if ((tid & 63u) == 0u) {
+        s_lo[tid >> 6] = lo;
+        s_hi[tid >> 6] = hi;
+    }
+    __syncthreads();
+    if (tid == 0u) {
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) {
+            lo = fminf(lo, s_lo[w]);
+            hi = fmaxf(hi, s_hi[w]);
+        }
+        atomicMin(&keys[0], order_key(lo));
+        atomicMax(&keys[1], order_key(hi));
+    }
+}
+
 // ---- sum of squares -------------------------------------------------------------------------------
 // Squares of fp32 values are exact in fp64; every lane adds its share in fp64, lanes and waves are
 // combined by a butterfly and through LDS, and each workgroup adds one fp64 number to *out (whose
 // rounding depends on the order in which the workgroups arrive: about 1e-16 relative).
-constexpr uint32_t kSumBlocks = 2048;
 
 __global__ void clear_f64_kernel(double* out) { *out = 0.0; }
 
@@ -412,10 +500,12 @@ hipError_t launch_quantize_r(const QuantizeArgs& a, hipStream_t stream) {
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(NT);
-    if (aligned) {
-        hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true>), grid, block, 0, stream, a, tile_elems);
+    if (a.scales_in != nullptr) {
+        if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, true>), grid, block, 0, stream, a, tile_elems);
+        else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, true>), grid, block, 0, stream, a, tile_elems);
     } else {
-        hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false>), grid, block, 0, stream, a, tile_elems);
+        if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, false>), grid, block, 0, stream, a, tile_elems);
+        else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, false>), grid, block, 0, stream, a, tile_elems);
     }
     return hipGetLastError();
 }
@@ -486,6 +576,22 @@ hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
     const bool straddle = (32u % a.bits) != 0u;
     return straddle ? launch_aggregate_s<true>(a, stream) : launch_aggregate_s<false>(a, stream);
+}
+
+hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    uint32_t* keys = reinterpret_cast<uint32_t*>(range_out);
+    hipLaunchKernelGGL(range_init_kernel, dim3(1), dim3(1), 0, stream, keys);
+    const uint64_t mis = (reinterpret_cast<uintptr_t>(grad) & 15u) >> 2;
+    uint32_t head = mis ? (uint32_t)(4u - mis) : 0u;
+    if (head > n) head = (uint32_t)n;
+    const uint64_t quads = (n - head) >> 2;
+    uint64_t blocks = (quads + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > kSumBlocks) blocks = kSumBlocks;
+    hipLaunchKernelGGL(tensor_range_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, grad, n, head, keys);
+    hipLaunchKernelGGL(range_finish_kernel, dim3(1), dim3(1), 0, stream, keys);
+    return hipGetLastError();
 }
 
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream) {

@@ -19,7 +19,8 @@ EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
     "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
-    "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax", "mqg_sum_squares", "mqg_adaptive_default_config",
+    "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax",
+    "mqg_tensor_range", "mqg_quantize_minmax_tensor", "mqg_aggregate_update_minmax_tensor", "mqg_sum_squares", "mqg_adaptive_default_config",
     "mqg_adaptive_bits",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
@@ -97,6 +98,12 @@ def lib():
     L.mqg_aggregate_update_minmax.restype = C.c_int
     L.mqg_aggregate_requantize_minmax.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, vp, vp, vp]
     L.mqg_aggregate_requantize_minmax.restype = C.c_int
+    L.mqg_tensor_range.argtypes = [vp, u64, vp, vp]
+    L.mqg_tensor_range.restype = C.c_int
+    L.mqg_quantize_minmax_tensor.argtypes = [vp, u64, u32, vp, vp, vp]
+    L.mqg_quantize_minmax_tensor.restype = C.c_int
+    L.mqg_aggregate_update_minmax_tensor.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, f32, vp, vp]
+    L.mqg_aggregate_update_minmax_tensor.restype = C.c_int
     L.mqg_sum_squares.argtypes = [vp, u64, vp, vp]
     L.mqg_sum_squares.restype = C.c_int
     L.mqg_adaptive_default_config.argtypes = [C.POINTER(AdaptiveConfig)]
@@ -378,6 +385,56 @@ def mqg_aggregate_requantize_minmax(packed, ranges, n, bits, bucket, packed_out=
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_requantize_minmax")
     return packed_out, ranges_out
+
+
+def mqg_tensor_range(grad, range_out=None, stream=None):
+    """(min, max) of the whole tensor into a two-element float32 device tensor."""
+    _check(grad, torch.float32, "grad")
+    if range_out is None:
+        range_out = torch.zeros(2, dtype=torch.float32, device=grad.device)
+    _check(range_out, torch.float32, "range_out")
+    st = lib().mqg_tensor_range(grad.data_ptr(), grad.numel(), range_out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_tensor_range")
+    return range_out
+
+
+def mqg_quantize_minmax_tensor(grad, bits, packed_out=None, range_out=None, stream=None):
+    """The paper's encoder: one [min, max] for the whole tensor. Returns (packed, range)."""
+    _check(grad, torch.float32, "grad")
+    n = grad.numel()
+    if packed_out is None:
+        packed_out = torch.empty(mqg_packed_words(n, bits), dtype=torch.int32, device=grad.device)
+    if range_out is None:
+        range_out = torch.zeros(2, dtype=torch.float32, device=grad.device)
+    _check(packed_out, torch.int32, "packed_out")
+    _check(range_out, torch.float32, "range_out")
+    if packed_out.numel() < mqg_packed_words(n, bits) or range_out.numel() < 2:
+        raise ValueError("output buffers too small")
+    st = lib().mqg_quantize_minmax_tensor(grad.data_ptr(), n, bits, packed_out.data_ptr(), range_out.data_ptr(),
+                                          _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_quantize_minmax_tensor")
+    return packed_out, range_out
+
+
+def mqg_aggregate_update_minmax_tensor(packed, ranges, n, bits, lr, params, stream=None):
+    _check(params, torch.float32, "params")
+    if params.numel() != n:
+        raise ValueError("params must have n elements")
+    W = len(packed)
+    if W != len(ranges):
+        raise ValueError("packed and ranges must have one entry per worker")
+    for p, r in zip(packed, ranges):
+        _check(p, torch.int32, "packed[w]")
+        _check(r, torch.float32, "ranges[w]")
+        if p.numel() < mqg_packed_words(n, bits) or r.numel() < 2:
+            raise ValueError("a worker's buffers are too small for n")
+    pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    ra = (C.c_void_p * max(W, 1))(*[r.data_ptr() for r in ranges])
+    st = lib().mqg_aggregate_update_minmax_tensor(pa, ra, W, n, bits, lr, params.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_update_minmax_tensor")
 
 
 def mqg_sum_squares(grad, out=None, stream=None):

@@ -166,3 +166,45 @@ def test_full_exchange_with_minmax_encoding_stays_on_the_oracle():
         p_ref = ref.aggregate_update_minmax([m_pk], [m_rg], n, bits, bucket, lr, p_ref)
         assert np.array_equal(to_u32(pk), m_pk)
         assert ulp_distance(params.cpu().numpy(), p_ref).max() == 0, "iteration %d" % it
+
+
+# ---- one range for the whole tensor, as the paper encodes ----------------------------------------
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 31, 4096, 4097, 100003, 3 * (1 << 20) + 11])
+def test_tensor_range_is_the_min_and_max(n):
+    g = workloads.laplace(n + 3, 1e-2, n, DEV)
+    for off in (0, 1, 3):
+        v = g[off:off + n]
+        r = mqgrad.mqg_tensor_range(v)
+        torch.cuda.synchronize()
+        assert r[0].item() == v.min().item() and r[1].item() == v.max().item()
+    z = mqgrad.mqg_tensor_range(-torch.zeros(n, device=DEV))
+    torch.cuda.synchronize()
+    assert z.cpu().numpy().view(np.uint32).tolist() == [0, 0]            # a zero bound is +0
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("n,W", [(7, 1), (5000, 3), (100003, 2), (2 * (1 << 20) + 5, 4)])
+def test_per_tensor_encoding_matches_oracle(bits, n, W):
+    # the oracle with one bucket that covers the tensor is the paper's per-tensor encoder
+    grads = [workloads.normal_with_outliers(n, 0.01, 1e-3, 25.0, 7 * w + bits, DEV) + 2e-3 * w for w in range(W)]
+    q = [mqgrad.mqg_quantize_minmax_tensor(g, bits) for g in grads]
+    params = workloads.uniform(n, -0.05, 0.05, 4, DEV)
+    p0 = params.cpu().numpy().copy()
+    mqgrad.mqg_aggregate_update_minmax_tensor([x[0] for x in q], [x[1] for x in q], n, bits, 0.1, params)
+    torch.cuda.synchronize()
+    want = [ref.quantize_minmax(g.cpu().numpy(), bits, n) for g in grads]
+    for w in range(W):
+        assert q[w][1].cpu().numpy().tobytes() == want[w][1].tobytes(), "range of worker %d" % w
+        assert np.array_equal(to_u32(q[w][0]), want[w][0]), first_mismatch(to_u32(q[w][0]), want[w][0])
+    p1 = ref.aggregate_update_minmax([x[0] for x in want], [x[1] for x in want], n, bits, n, 0.1, p0)
+    assert ulp_distance(params.cpu().numpy(), p1).max() == 0
+
+
+def test_per_tensor_encoding_of_an_unaligned_view():
+    base = workloads.normal(50000, 0.01, 3, DEV)
+    g = base[3:3 + 40001]
+    pk, rg = mqgrad.mqg_quantize_minmax_tensor(g, 6)
+    torch.cuda.synchronize()
+    want_pk, want_rg = ref.quantize_minmax(g.cpu().numpy(), 6, g.numel())
+    assert np.array_equal(rg.cpu().numpy(), want_rg) and np.array_equal(to_u32(pk), want_pk)
