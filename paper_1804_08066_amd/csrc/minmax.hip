@@ -431,8 +431,12 @@ __global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __r
             lo = fminf(lo, s_lo[w]);
             hi = fmaxf(hi, s_hi[w]);
         }
-        atomicMin(&keys[0], order_key(lo));
-        atomicMax(&keys[1], order_key(hi));
+        // Same-address atomics serialize in L2, and after the first workgroups almost none improves the
+        // bounds: look first.  The keys only ever move one way, so a stale read can cause a needless
+        // atomic but never a wrong skip.
+        const uint32_t kl = order_key(lo), kh = order_key(hi);
+        if (kl < __atomic_load_n(&keys[0], __ATOMIC_RELAXED)) atomicMin(&keys[0], kl);
+        if (kh > __atomic_load_n(&keys[1], __ATOMIC_RELAXED)) atomicMax(&keys[1], kh);
     }
 }
 
