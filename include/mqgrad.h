@@ -11,6 +11,9 @@
  *   mqg_aggregate_update  server side: unpack, de-quantize, mean over W workers, SGD update
  *                         (the paper's De-quantize + average + w <- w - eta g)
  *   mqg_mdp_*             the host-side agent that picks K  (the paper's MQGrad-SARSA)
+ * and, further down: the server's re-quantizing step of the printed Algorithm 1 with the worker's
+ * de-quantizing update, several layer tensors per launch, the footnote's deterministic [min, max]
+ * encoder (per bucket or per tensor), and the Adaptive baseline's bit rule.
  *
  * Conventions
  *   - Plain C ABI.  No function throws, aborts or allocates device memory.
@@ -90,8 +93,9 @@ mqg_status mqg_quantize(const float* grad, uint64_t n, uint32_t bits, uint32_t b
 
 /* Same, with the bucket range taken as the L2 norm of the bucket when mode == MQG_SCALE_L2
  * (the norm scaling of the QSGD family the paper cites in Section 2).  mode == MQG_SCALE_MAXABS
- * is exactly mqg_quantize.  The L2 scale is accumulated in fp32 in a fixed tree order, so it is
- * reproducible but only close (about 1e-6 relative) to a scale summed in another order. */
+ * is exactly mqg_quantize.  The sum of squares is accumulated in a fixed order (groups of four squares
+ * in fp32, everything above in fp64), so the scale is reproducible, but only close (about 1e-7
+ * relative) to a scale summed in another order; it is raised to max |g_i| if rounding left it below. */
 mqg_status mqg_quantize_mode(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
                              mqg_scale_mode mode,
                              uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
