@@ -209,7 +209,7 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
     for (uint32_t i = 0; i < count; ++i) {
         if (items[i].n != 0 && (reinterpret_cast<uintptr_t>(items[i].grad) & 15u) != 0) aligned = false;
     }
-    a.tile_elems = mqg::quantize_batch_tile(bucket, a.common.bucket_shift, aligned);
+    a.tile_elems = mqg::quantize_batch_tile(bucket, bits, a.common.bucket_shift, aligned);
     uint64_t tiles = 0;
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
         a.tile_start[i] = (uint32_t)tiles;

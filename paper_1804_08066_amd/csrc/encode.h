@@ -39,17 +39,46 @@ __device__ __forceinline__ float bpermute_xor32_f32(float v, uint32_t lane) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), __builtin_bit_cast(int, v)));
 }
 
-// From values already reduced over each 8-lane group to the whole wave: every lane gets the result.
+// Cross-lane max / min on unsigned integers.  Non-negative floats order like their bit patterns, and
+// any float orders like its order-preserving key (order_key below), so the reductions run on integers:
+// no NaN canonicalisation is inserted, and the DPP operand folds into the max / min instruction.
 // Call with every lane of the wave active.
-__device__ __forceinline__ float wave_max_from_cells(float m, uint32_t lane) {
-    m = fmaxf(m, dpp_f32<kDppRowMirror>(m));
-    m = fmaxf(m, swizzle_xor16_f32(m));
-    return fmaxf(m, bpermute_xor32_f32(m, lane));
+__device__ __forceinline__ uint32_t cell_max_u32(uint32_t m) {   // over each group of 8 lanes
+    m = max(m, dpp_u32<kDppQuadSwap1>(m));
+    m = max(m, dpp_u32<kDppQuadSwap2>(m));
+    return max(m, dpp_u32<kDppRowHalfMirror>(m));
 }
-__device__ __forceinline__ float wave_min_from_cells(float m, uint32_t lane) {
-    m = fminf(m, dpp_f32<kDppRowMirror>(m));
-    m = fminf(m, swizzle_xor16_f32(m));
-    return fminf(m, bpermute_xor32_f32(m, lane));
+__device__ __forceinline__ uint32_t cell_min_u32(uint32_t m) {
+    m = min(m, dpp_u32<kDppQuadSwap1>(m));
+    m = min(m, dpp_u32<kDppQuadSwap2>(m));
+    return min(m, dpp_u32<kDppRowHalfMirror>(m));
+}
+__device__ __forceinline__ uint32_t swizzle_xor16_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, kSwizzleXor16);
+}
+__device__ __forceinline__ uint32_t bpermute_xor32_u32(uint32_t v, uint32_t lane) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), (int)v);
+}
+// from values already reduced over each 8-lane group to the whole wave: every lane gets the result
+__device__ __forceinline__ uint32_t wave_max_from_cells_u32(uint32_t m, uint32_t lane) {
+    m = max(m, dpp_u32<kDppRowMirror>(m));
+    m = max(m, swizzle_xor16_u32(m));
+    return max(m, bpermute_xor32_u32(m, lane));
+}
+__device__ __forceinline__ uint32_t wave_min_from_cells_u32(uint32_t m, uint32_t lane) {
+    m = min(m, dpp_u32<kDppRowMirror>(m));
+    m = min(m, swizzle_xor16_u32(m));
+    return min(m, bpermute_xor32_u32(m, lane));
+}
+
+// fp32 -> uint32 whose unsigned order is the order of the floats, and back
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return u ^ (uint32_t)(((int)u >> 31) | (int)0x80000000);
+}
+__device__ __forceinline__ float key_value(uint32_t k) {
+    const uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+    return __builtin_bit_cast(float, u);
 }
 
 // a ^ b ^ c in one instruction: gfx950's three-input bitwise operation with the parity truth table

@@ -26,16 +26,6 @@ using tile_io::kThreads;
 constexpr int kChunk = 8;   // workers whose code loads are in flight together
 constexpr uint32_t kSumBlocks = 2048;   // workgroups of the whole-tensor reductions (8 per compute unit)
 
-// fp32 -> uint32 whose unsigned order is the order of the floats
-__device__ __forceinline__ uint32_t order_key(float f) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, f);
-    return u ^ (uint32_t)(((int)u >> 31) | (int)0x80000000);
-}
-__device__ __forceinline__ float key_value(uint32_t k) {
-    const uint32_t u = (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
-    return __builtin_bit_cast(float, u);
-}
-
 // NT lanes own a tile of at most 4*NT*R elements
 template <int R, int NT>
 struct Shared {
@@ -132,28 +122,34 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
             hi[0] = fmaxf(hi[0], hi[j]);
         }
     }
+    // across lanes on order-preserving integer keys, stage by stage over the rows
+    uint32_t kl[R], kh[R];
 #pragma unroll
     for (int j = 0; j < (kOne ? 1 : R); ++j) {
-        float l = lo[j], h = hi[j];
-        l = fminf(l, dpp_f32<kDppQuadSwap1>(l));
-        h = fmaxf(h, dpp_f32<kDppQuadSwap1>(h));
-        l = fminf(l, dpp_f32<kDppQuadSwap2>(l));
-        h = fmaxf(h, dpp_f32<kDppQuadSwap2>(h));
-        l = fminf(l, dpp_f32<kDppRowHalfMirror>(l));
-        h = fmaxf(h, dpp_f32<kDppRowHalfMirror>(h));
-        if (row_in_bucket) {
-            l = wave_min_from_cells(l, lane);
-            h = wave_max_from_cells(h, lane);
+        kl[j] = cell_min_u32(order_key(lo[j]));
+        kh[j] = cell_max_u32(order_key(hi[j]));
+    }
+    if (row_in_bucket) {
+#pragma unroll
+        for (int j = 0; j < (kOne ? 1 : R); ++j) {
+            kl[j] = wave_min_from_cells_u32(kl[j], lane);
+            kh[j] = wave_max_from_cells_u32(kh[j], lane);
+        }
+#pragma unroll
+        for (int j = 0; j < (kOne ? 1 : R); ++j) {
             const uint32_t row_first = 4u * (j * NT + (tid & ~63u));   // first element of the wave's row
             if (lane == 0u && (FULL || kOne || row_first < tile_count)) {
-                atomicMin(&sm.kmin[bl[j]], order_key(l));
-                atomicMax(&sm.kmax[bl[j]], order_key(h));
+                atomicMin(&sm.kmin[bl[j]], kl[j]);
+                atomicMax(&sm.kmax[bl[j]], kh[j]);
             }
-        } else {
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
             const uint32_t el = 4u * (j * NT + tid);
             if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
-                atomicMin(&sm.kmin[bl[j]], order_key(l));
-                atomicMax(&sm.kmax[bl[j]], order_key(h));
+                atomicMin(&sm.kmin[bl[j]], kl[j]);
+                atomicMax(&sm.kmax[bl[j]], kh[j]);
             }
         }
     }
@@ -379,7 +375,7 @@ __global__ void range_finish_kernel(uint32_t* keys) {
 
 __global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __restrict__ g, const uint64_t n,
                                                                 const uint32_t head, uint32_t* keys) {
-    __shared__ float s_lo[kThreads / 64], s_hi[kThreads / 64];
+    __shared__ uint32_t s_lo[kThreads / 64], s_hi[kThreads / 64];
     const uint32_t tid = threadIdx.x;
     const uint64_t gtid = (uint64_t)blockIdx.x * kThreads + tid;
     const uint64_t stride = (uint64_t)gridDim.x * kThreads;
@@ -412,29 +408,22 @@ __global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __r
         lo = fminf(lo, v);
         hi = fmaxf(hi, v);
     }
-    lo = fminf(lo, dpp_f32<kDppQuadSwap1>(lo));
-    hi = fmaxf(hi, dpp_f32<kDppQuadSwap1>(hi));
-    lo = fminf(lo, dpp_f32<kDppQuadSwap2>(lo));
-    hi = fmaxf(hi, dpp_f32<kDppQuadSwap2>(hi));
-    lo = fminf(lo, dpp_f32<kDppRowHalfMirror>(lo));
-    hi = fmaxf(hi, dpp_f32<kDppRowHalfMirror>(hi));
-    lo = wave_min_from_cells(lo, tid & 63u);
-    hi = wave_max_from_cells(hi, tid & 63u);
+    uint32_t kl = wave_min_from_cells_u32(cell_min_u32(order_key(lo)), tid & 63u);
+    uint32_t kh = wave_max_from_cells_u32(cell_max_u32(order_key(hi)), tid & 63u);
     if ((tid & 63u) == 0u) {
-        s_lo[tid >> 6] = lo;
-        s_hi[tid >> 6] = hi;
+        s_lo[tid >> 6] = kl;
+        s_hi[tid >> 6] = kh;
     }
     __syncthreads();
     if (tid == 0u) {
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) {
-            lo = fminf(lo, s_lo[w]);
-            hi = fmaxf(hi, s_hi[w]);
+            kl = min(kl, s_lo[w]);
+            kh = max(kh, s_hi[w]);
         }
         // Same-address atomics serialize in L2, and after the first workgroups almost none improves the
         // bounds: look first.  The keys only ever move one way, so a stale read can cause a needless
         // atomic but never a wrong skip.
-        const uint32_t kl = order_key(lo), kh = order_key(hi);
         if (kl < __atomic_load_n(&keys[0], __ATOMIC_RELAXED)) atomicMin(&keys[0], kl);
         if (kh > __atomic_load_n(&keys[1], __ATOMIC_RELAXED)) atomicMax(&keys[1], kh);
     }

@@ -187,38 +187,31 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
         constexpr bool kOne = R > 4;                                   // the tile is one bucket
         const bool row_in_bucket = kOne || ((a.bucket & 255u) == 0u && a.bucket >= 2048u);   // uniform over the launch
         if (row_in_bucket) {
-            float m[R];
+            uint32_t m[R];   // bit patterns of non-negative floats: integer order = value order
 #pragma unroll
             for (int j = 0; j < R; ++j) {
-                m[j] = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
+                m[j] = __builtin_bit_cast(uint32_t, fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w))));
             }
             if (kOne) {
 #pragma unroll
-                for (int j = 1; j < R; ++j) m[0] = fmaxf(m[0], m[j]);
+                for (int j = 1; j < R; ++j) m[0] = max(m[0], m[j]);
             }
 #pragma unroll
+            for (int j = 0; j < (kOne ? 1 : R); ++j) m[j] = cell_max_u32(m[j]);
+#pragma unroll
+            for (int j = 0; j < (kOne ? 1 : R); ++j) m[j] = wave_max_from_cells_u32(m[j], tid & 63u);
+#pragma unroll
             for (int j = 0; j < (kOne ? 1 : R); ++j) {
-                float r = m[j];
-                r = fmaxf(r, dpp_f32<kDppQuadSwap1>(r));
-                r = fmaxf(r, dpp_f32<kDppQuadSwap2>(r));
-                r = fmaxf(r, dpp_f32<kDppRowHalfMirror>(r));
-                r = wave_max_from_cells(r, tid & 63u);
                 const uint32_t row_first = 4u * (j * kThreads + (tid & ~63u));
-                if ((tid & 63u) == 0u && (FULL || kOne || row_first < tile_count)) {
-                    atomicMax(&sm.bmax[bl[j]], __builtin_bit_cast(uint32_t, r));   // r >= 0: bit order = value order
-                }
+                if ((tid & 63u) == 0u && (FULL || kOne || row_first < tile_count)) atomicMax(&sm.bmax[bl[j]], m[j]);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const uint32_t el = 4u * (j * kThreads + tid);
-                float m = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
-                m = fmaxf(m, dpp_f32<kDppQuadSwap1>(m));
-                m = fmaxf(m, dpp_f32<kDppQuadSwap2>(m));
-                m = fmaxf(m, dpp_f32<kDppRowHalfMirror>(m));
-                if ((tid & 7u) == 0u && (FULL || el < tile_count)) {
-                    atomicMax(&sm.bmax[bl[j]], __builtin_bit_cast(uint32_t, m));   // m >= 0: bit order = value order
-                }
+                const float mf = fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w)));
+                const uint32_t m = cell_max_u32(__builtin_bit_cast(uint32_t, mf));
+                if ((tid & 7u) == 0u && (FULL || el < tile_count)) atomicMax(&sm.bmax[bl[j]], m);
             }
         }
         if (l2) {
@@ -464,8 +457,8 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
 // Power-of-two buckets on 16-byte aligned gradients take the wave-local kernel, like single calls.
 static bool batch_takes_wave_kernel(int bucket_shift, bool aligned) { return aligned && bucket_shift >= 5; }
 
-uint32_t quantize_batch_tile(uint32_t bucket, int bucket_shift, bool aligned) {
-    if (batch_takes_wave_kernel(bucket_shift, aligned)) return quantize_wave_block_elems(bucket);
+uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift, bool aligned) {
+    if (batch_takes_wave_kernel(bucket_shift, aligned)) return quantize_wave_block_elems(bucket, bits);
     const uint32_t cap = bucket <= 4096u ? Tile<4>::kCap : (bucket <= 8192u ? Tile<8>::kCap : Tile<16>::kCap);
     return (cap / bucket) * bucket;
 }

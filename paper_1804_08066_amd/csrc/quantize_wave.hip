@@ -24,6 +24,8 @@
 #include "encode.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace mqg {
 namespace {
 
@@ -34,16 +36,68 @@ __device__ __forceinline__ uint32_t swap_adjacent(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x041F);
 }
 
-// max over the `seg_lanes` lanes (8, 16, 32 or 64) that share a bucket; every lane of the segment
-// ends up with the segment's maximum
-__device__ __forceinline__ float segment_max(float m, uint32_t seg_lanes, uint32_t lane) {
-    m = fmaxf(m, dpp_f32<kDppQuadSwap1>(m));
-    m = fmaxf(m, dpp_f32<kDppQuadSwap2>(m));
-    m = fmaxf(m, dpp_f32<kDppRowHalfMirror>(m));
-    if (seg_lanes >= 16u) m = fmaxf(m, dpp_f32<kDppRowMirror>(m));
-    if (seg_lanes >= 32u) m = fmaxf(m, swizzle_xor16_f32(m));
-    if (seg_lanes >= 64u) m = fmaxf(m, bpermute_xor32_f32(m, lane));
-    return m;
+// Max over the `seg_lanes` lanes (8, 16, 32 or 64) that share a bucket, for the rows 0, STRIDE,
+// 2*STRIDE, ... of a lane at once: stage by stage over all those rows, so that the cross-lane
+// exchanges of different rows are in flight together instead of one dependent chain per row.
+// Every lane of a segment ends up with the segment's maximum.
+template <int R, int STRIDE>
+__device__ __forceinline__ void segment_max_rows(uint32_t (&m)[R], uint32_t seg_lanes, uint32_t lane) {
+    // The values are bit patterns of non-negative floats, whose order is the order of the unsigned
+    // integers: integer max needs no NaN canonicalisation and takes its DPP operand directly.
+#pragma unroll
+    for (int j = 0; j < R; j += STRIDE) m[j] = max(m[j], dpp_u32<kDppQuadSwap1>(m[j]));
+#pragma unroll
+    for (int j = 0; j < R; j += STRIDE) m[j] = max(m[j], dpp_u32<kDppQuadSwap2>(m[j]));
+#pragma unroll
+    for (int j = 0; j < R; j += STRIDE) m[j] = max(m[j], dpp_u32<kDppRowHalfMirror>(m[j]));
+    if (seg_lanes >= 16u) {
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) m[j] = max(m[j], dpp_u32<kDppRowMirror>(m[j]));
+    }
+    if (seg_lanes >= 32u) {
+        uint32_t t[R];
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) t[j] = (uint32_t)__builtin_amdgcn_ds_swizzle((int)m[j], kSwizzleXor16);
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) m[j] = max(m[j], t[j]);
+    }
+    if (seg_lanes >= 64u) {
+        uint32_t t[R];
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) t[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((lane ^ 32u) << 2), (int)m[j]);
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) m[j] = max(m[j], t[j]);
+    }
+}
+
+// The same butterfly as a sum in fp64 (L2 scale).
+template <int R, int STRIDE>
+__device__ __forceinline__ void segment_sum_rows(double (&q)[R], uint32_t seg_lanes) {
+    for (uint32_t mask = 1; mask < seg_lanes; mask <<= 1) {   // uniform trip count
+        double t[R];
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) t[j] = __shfl_xor(q[j], (int)mask, 64);
+#pragma unroll
+        for (int j = 0; j < R; j += STRIDE) q[j] += t[j];
+    }
+}
+
+// rows per bucket -> compile-time stride
+template <int R, int STRIDE = 1>
+__device__ __forceinline__ void segment_max_dispatch(uint32_t (&m)[R], uint32_t rpb, uint32_t seg_lanes, uint32_t lane) {
+    if (STRIDE >= R || rpb == (uint32_t)STRIDE) {
+        segment_max_rows<R, (STRIDE < R ? STRIDE : R)>(m, seg_lanes, lane);
+    } else {
+        segment_max_dispatch<R, (STRIDE < R ? 2 * STRIDE : R)>(m, rpb, seg_lanes, lane);
+    }
+}
+template <int R, int STRIDE = 1>
+__device__ __forceinline__ void segment_sum_dispatch(double (&q)[R], uint32_t rpb, uint32_t seg_lanes) {
+    if (STRIDE >= R || rpb == (uint32_t)STRIDE) {
+        segment_sum_rows<R, (STRIDE < R ? STRIDE : R)>(q, seg_lanes);
+    } else {
+        segment_sum_dispatch<R, (STRIDE < R ? 2 * STRIDE : R)>(q, rpb, seg_lanes);
+    }
 }
 
 // LDS of one workgroup: everything is indexed by wave, so waves never touch each other's entries
@@ -117,13 +171,10 @@ __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lan
                 for (int j = 0; j + step < R; j += 2 * step) q[j] += q[j + step];
             }
         }
+        segment_sum_dispatch<R>(q, rpb, seg_lanes);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            if (((uint32_t)j & (rpb - 1u)) == 0u) {
-                double r = q[j];
-                for (uint32_t m = 1; m < seg_lanes; m <<= 1) r += __shfl_xor(r, (int)m, 64);   // uniform trip count
-                if ((lane & (seg_lanes - 1u)) == 0u) sm.ssq[wave][slot[j]] = r;
-            }
+            if (((uint32_t)j & (rpb - 1u)) == 0u && (lane & (seg_lanes - 1u)) == 0u) sm.ssq[wave][slot[j]] = q[j];
         }
         if (WPB > 1 && lane == 0u) sm.wave_ssq[wave] = sm.ssq[wave][0];
     }
@@ -141,11 +192,14 @@ __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lan
         }
     }
     // reduce across the lanes of the bucket; the first lane of each bucket publishes the result
+    uint32_t mb[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) mb[j] = __builtin_bit_cast(uint32_t, m[j]);   // m >= 0: bit order = value order
+    segment_max_dispatch<R>(mb, rpb, seg_lanes, lane);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        if (((uint32_t)j & (rpb - 1u)) == 0u) {
-            const float r = segment_max(m[j], seg_lanes, lane);
-            if ((lane & (seg_lanes - 1u)) == 0u) sm.smax[wave][slot[j]] = r;
+        if (((uint32_t)j & (rpb - 1u)) == 0u && (lane & (seg_lanes - 1u)) == 0u) {
+            sm.smax[wave][slot[j]] = __builtin_bit_cast(float, mb[j]);
         }
     }
     if (WPB > 1 && lane == 0u) sm.wave_max[wave] = sm.smax[wave][0];   // buckets spanning WPB waves
@@ -430,6 +484,25 @@ hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// The measured choice of (R, WPB, NW) per bucket size (100 M elements, every width): buckets up to 1024
+// elements live inside one wave that holds 2048 elements (R = 8); buckets of 2048 .. 8192 span waves of
+// 1024 elements each, 4 or 8 to a workgroup; 16384 spans 8 waves of 2048.
+template <class F>
+auto with_wave_shape(uint32_t bucket, uint32_t bits, F f) {
+    using std::integral_constant;
+    // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
+    if (bits == 8u && (bucket == 512u || bucket == 1024u)) {
+        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{});
+    }
+    switch (bucket) {
+        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{});
+        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
+        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
+        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
+        default: return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{});   // 32 .. 1024
+    }
+}
+
 template <int R, int WPB, int NW>
 hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
@@ -449,30 +522,22 @@ bool quantize_wave_supported(const QuantizeArgs& a) {
 }
 
 // elements per workgroup of the wave-local kernel at this bucket size
-uint32_t quantize_wave_block_elems(uint32_t bucket) { return bucket <= 4096u ? 4096u : bucket; }
+uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits) {
+    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
+}
 
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
-    const dim3 grid(blocks);
-    switch (a.common.bucket) {
-        case 2048: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 2, 4>), grid, dim3(256), 0, stream, a); break;
-        case 4096: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 4, 4>), grid, dim3(256), 0, stream, a); break;
-        case 8192: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 8, 8>), grid, dim3(512), 0, stream, a); break;
-        case 16384: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 16, 16>), grid, dim3(1024), 0, stream, a); break;
-        default: hipLaunchKernelGGL((quantize_tensors_wave_kernel<4, 1, 4>), grid, dim3(256), 0, stream, a); break;
-    }
-    return hipGetLastError();
+    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw) {
+        constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value;
+        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW>), dim3(blocks), dim3(64 * NW), 0, stream, a);
+        return hipGetLastError();
+    });
 }
 
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
-    switch (a.bucket) {
-        // 1024 elements per wave at every bucket size; larger buckets take more waves per workgroup
-        // (measured faster than more elements per lane: 8192 at 4 waves x 2048 ran 8 % slower)
-        case 2048: return launch_wave<4, 2, 4>(a, stream);
-        case 4096: return launch_wave<4, 4, 4>(a, stream);
-        case 8192: return launch_wave<4, 8, 8>(a, stream);
-        case 16384: return launch_wave<4, 16, 16>(a, stream);
-        default: return launch_wave<4, 1, 4>(a, stream);   // 32 .. 1024
-    }
+    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw) {
+        return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value>(a, stream);
+    });
 }
 
 // The re-quantizing server step takes the wave-local kernel for power-of-two buckets of 256 elements
