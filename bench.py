@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # that was profiled has an entry; any other reports null.
 MEASURED_TRAFFIC = {
     # (n, workers, bits, bucket): (quantize bytes per launch, aggregate_update bytes per launch)
-    (100_000_000, 8, 4, 1024): (450.9e6, 1225.1e6),
+    (100_000_000, 8, 4, 1024): (450.6e6, 1225.1e6),
 }
 
 
