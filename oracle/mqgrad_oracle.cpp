@@ -304,6 +304,15 @@ void orc_dequantize_update(const uint32_t* packed, const float* scales, uint64_t
     }
 }
 
+// The server's mean gradient itself (Algorithm 1, ReceiveQGThenSendQG: g^m <- sum_p De-quantize / P),
+// for callers whose optimizer is not the paper's plain SGD step: the worker-order fma chain of
+// orc_aggregate_update, divided by W with one IEEE fp32 division.  W = 1 is De-quantize.
+void orc_aggregate_mean(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                        uint64_t n, uint32_t bits, uint32_t bucket, float* mean_out) {
+    orc_aggregate_sum(packed, scales, W, n, bits, bucket, mean_out);
+    for (uint64_t i = 0; i < n; ++i) mean_out[i] = mean_out[i] / (float)W;
+}
+
 // Layers that are sent uncompressed (the paper quantizes only its two large fully connected layers
 // and communicates the other parameters "without any compression", Section 4.1): the server averages
 // the raw fp32 gradients in worker order and applies the same update.

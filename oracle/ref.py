@@ -61,6 +61,8 @@ def lib():
         L.orc_aggregate_requantize.restype = None
         L.orc_dequantize_update.argtypes = [u32p, f32p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_float, f32p]
         L.orc_dequantize_update.restype = None
+        L.orc_aggregate_mean.argtypes = [pp_u32, pp_f32, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, f32p]
+        L.orc_aggregate_mean.restype = None
         L.orc_average_update_raw.argtypes = [pp_f32, C.c_uint32, C.c_uint64, C.c_float, f32p]
         L.orc_average_update_raw.restype = None
         L.orc_minmax_ranges.argtypes = [f32p, C.c_uint64, C.c_uint32, f32p]
@@ -336,3 +338,12 @@ def aggregate_requantize_minmax(packed_list, ranges_list, n, bits, bucket):
         lib().orc_aggregate_requantize_minmax(pa, sa, len(packed_list), n, bits, bucket, _p(packed, C.c_uint32),
                                               _p(ranges, C.c_float))
     return packed, ranges
+
+
+def aggregate_mean(packed_list, scales_list, n, bits, bucket):
+    """Mean over the workers of their de-quantized gradients (fp32 chain in worker order, one division)."""
+    pk, sc, pa, sa = _ptr_arrays(packed_list, scales_list)
+    out = np.zeros(n, dtype=np.float32)
+    if n:
+        lib().orc_aggregate_mean(pa, sa, len(packed_list), n, bits, bucket, _p(out, C.c_float))
+    return out

@@ -509,3 +509,28 @@ def test_raw_layers_are_averaged_like_plain_sgd():
     assert np.all(np.abs(got - want) <= (W + 2) * 2.0 ** -23 * mag)
     assert np.array_equal(ref.average_update_raw(gs[:1], 1.0, np.zeros(n, np.float32)), -gs[0])
     assert ref.average_update_raw(gs, 0.0, p).tobytes() == p.tobytes()
+
+
+# ---- the mean gradient as an output ---------------------------------------------------------------
+
+@pytest.mark.parametrize("W,bits", [(1, 4), (3, 2), (8, 8), (7, 5)])
+def test_mean_gradient_output(W, bits):
+    rng = np.random.default_rng(W * 31 + bits)
+    n, bucket = 4000 + 9, 256
+    grads = [rng.normal(1e-3 * w, 1e-2, n).astype(np.float32) for w in range(W)]
+    q = [ref.quantize(g, bits, bucket, 17, 2, w) for w, g in enumerate(grads)]
+    mean = ref.aggregate_mean([x[0] for x in q], [x[1] for x in q], n, bits, bucket)
+    deq = [ref.dequantize(x[0], x[1], n, bits, bucket).astype(np.float64) for x in q]
+    want = sum(deq) / W
+    mag = sum(np.abs(d) for d in deq) / W
+    assert np.all(np.abs(mean - want) <= (W + 2) * 2.0 ** -24 * mag)
+    if W == 1:
+        assert np.array_equal(mean, ref.dequantize(q[0][0], q[0][1], n, bits, bucket))     # W = 1 is De-quantize
+    # the division is a correctly rounded fp32 division of the fp32 sum
+    s = ref.aggregate_sum([x[0] for x in q], [x[1] for x in q], n, bits, bucket)
+    for i in range(0, n, 37):
+        assert Fraction(float(mean[i])) == f32_round(Fraction(float(s[i])) / W)
+    # consistency with the update: p - lr * mean agrees with the fused update to rounding
+    p0 = rng.uniform(-0.05, 0.05, n).astype(np.float32)
+    p1 = ref.aggregate_update([x[0] for x in q], [x[1] for x in q], n, bits, bucket, 0.1, p0)
+    assert np.all(np.abs(p1 - (p0.astype(np.float64) - 0.1 * mean.astype(np.float64))) <= 4 * 2.0 ** -24 * np.maximum(np.abs(p0), 0.1 * mag))
