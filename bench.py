@@ -142,26 +142,33 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
     for w in range(W):
         mqgrad.mqg_quantize(wl.grads[w], bits, bucket, seed=1234, iteration=0, worker=w, packed_out=pk[w], scales_out=sc[w])
     mean_pk, mean_sc = mqgrad.alloc_outputs(n, bits, bucket, wl.device)
+    mean_out = torch.empty(n, dtype=torch.float32, device=wl.device)
     ev = []
     for k in range(warmup + steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         e[0].record()
         mqgrad.mqg_aggregate_requantize(pk, sc, n, bits, bucket, seed=1234, iteration=k, worker=W,
                                         packed_out=mean_pk, scales_out=mean_sc)
         e[1].record()
         mqgrad.mqg_dequantize_update(mean_pk, mean_sc, n, bits, bucket, lr, wl.params)
         e[2].record()
+        mqgrad.mqg_aggregate_mean(pk, sc, n, bits, bucket, mean_out)
+        e[3].record()
         if k >= warmup:
             ev.append(e)
     torch.cuda.synchronize()
     r_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev)
     d_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+    m_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / len(ev)
     nb = (n + bucket - 1) // bucket
+    m_bytes = W * (n * bits / 8.0 + 4.0 * nb) + 4.0 * n
     r_bytes = (W + 1) * (n * bits / 8.0 + 4.0 * nb)
     d_bytes = n * bits / 8.0 + 4.0 * nb + 8.0 * n
     r_ops = n * ((3.0 if bits in (1, 8) else 4.0) * W + 17.0)   # 1 and 8 bits decode in three operations
-    log("exchange: requantize %.1f us (%.1f T lane-ops/s, %.0f GB/s), dequantize_update %.1f us (%.0f GB/s)" %
-        (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9))
+    log("exchange: requantize %.1f us (%.1f T lane-ops/s, %.0f GB/s), dequantize_update %.1f us (%.0f GB/s), "
+        "aggregate_mean %.1f us (%.0f GB/s)" %
+        (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9,
+         m_ms * 1e3, m_bytes / (m_ms * 1e-3) / 1e9))
     return {
         "requantize": {"kernel": "requantize_pack_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
                        "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T lane-ops/s",
@@ -172,6 +179,9 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
                               "achieved": d_bytes / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": d_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "algorithmic_bytes_per_launch": d_bytes},
+        "aggregate_mean": {"kernel": "aggregate_mean_kernel", "avg_launch_us": m_ms * 1e3, "bound": "hbm",
+                           "achieved": m_bytes / (m_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": m_bytes / (m_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": m_bytes},
         "grad_gbs_server_leg": 4.0 * n * W / (r_ms * 1e-3) / 1e9,
     }
 

@@ -128,6 +128,15 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
                                 uint64_t n, uint32_t bits, uint32_t bucket,
                                 float lr, float* params, void* stream);
 
+/* The server's mean gradient itself, for callers whose optimizer is not the plain SGD step of the
+ * paper: mean_out[i] <- (sum over workers, in worker order, of the de-quantized values -- the chain of
+ * mqg_aggregate_update) / W, one IEEE fp32 division per element.  With W = 1 this is De-quantize.
+ *   mean_out  device, n floats, fully overwritten.  Other arguments and errors as for
+ *   mqg_aggregate_update. */
+mqg_status mqg_aggregate_mean(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                              uint64_t n, uint32_t bits, uint32_t bucket,
+                              float* mean_out, void* stream);
+
 /* ---- the paper's full exchange (Algorithm 1): the server sends the quantized mean back ---------
  *
  * ReceiveQGThenSendQG:  g^m <- sum_p De-quantize(gbar_p) / P;  gbar^m <- Quantize(g^m, K);  send.

@@ -39,11 +39,37 @@ constexpr int kChunk = 8;   // workers whose code loads are in flight together
 
 using namespace tile_io;
 
+// acc <- acc / W with one IEEE fp32 division per element; for a power of two, multiplying by 1/W is
+// the same correctly rounded scaling in one operation
+template <int R>
+__device__ __forceinline__ void scale_to_mean(float4 (&acc)[R], uint32_t W) {
+    const float Wf = (float)W;
+    if ((W & (W - 1u)) == 0u) {
+        const float inv = 1.0f / Wf;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            acc[j].x = acc[j].x * inv;
+            acc[j].y = acc[j].y * inv;
+            acc[j].z = acc[j].z * inv;
+            acc[j].w = acc[j].w * inv;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            acc[j].x = acc[j].x / Wf;
+            acc[j].y = acc[j].y / Wf;
+            acc[j].z = acc[j].z / Wf;
+            acc[j].w = acc[j].w / Wf;
+        }
+    }
+}
+
 using decode::accumulate_quad;
 using decode::readlane_f32;
 // ---- buckets that are multiples of 128: bucket steps live in the wave ---------------------------
 // NBR = buckets a 256-element row can touch: 1 when the bucket is a multiple of 256, else 2.
-template <int R, int NBR, bool STRADDLE, bool ALIGNED, bool ONCE, int WIDTH>
+// MEAN: a.params is an output that receives acc / W (the mean gradient) instead of being updated.
+template <int R, int NBR, bool STRADDLE, bool ALIGNED, bool ONCE, int WIDTH, bool MEAN = false>
 __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const AggregateArgs a) {
     constexpr uint32_t TILE = 1024u * R;
     const uint32_t tid = threadIdx.x;
@@ -58,7 +84,12 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     const float* my_scales = a.scales[lane < a.W ? lane : 0u];
 
     float4 x[R];
-    load_params<R, ALIGNED>(p, tile_count, full, x);
+    if (MEAN) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) x[j] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);   // fma(1, v, -0) = v for every v
+    } else {
+        load_params<R, ALIGNED>(p, tile_count, full, x);
+    }
 
     const uint32_t b = a.bits;
     const int negL = -(int)((1u << b) - 1u);
@@ -105,7 +136,12 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
             }
         }
     }
-    update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+    if (MEAN) {
+        scale_to_mean<R>(acc, a.W);
+        update_params<R, ALIGNED>(p, tile_count, full, 1.0f, x, acc);
+    } else {
+        update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+    }
 }
 
 // ---- any other bucket size: bucket steps shared through LDS -------------------------------------
@@ -116,7 +152,8 @@ constexpr uint32_t kMaxBuckets = kLdsTile / 32u + 1u;   // buckets a tile can to
 // One tile of kLdsTile parameters of one tensor.  packed / scales: tables of W device pointers
 // (in kernel-argument memory).  raw != nullptr: an uncompressed layer -- the W pointers are fp32
 // gradients that are summed in worker order instead of decoded.
-template <bool STRADDLE, bool ALIGNED, bool ONCE>
+// MEAN: `params` is an output that receives acc / W (the mean gradient) instead of being updated.
+template <bool STRADDLE, bool ALIGNED, bool ONCE, bool MEAN = false>
 __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed, const float* const* scales,
                                                    const float* const* raw, uint32_t W, uint64_t n, uint32_t b,
                                                    uint32_t bucket, int bucket_shift, float neg_c,
@@ -129,7 +166,12 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
     float* __restrict__ p = params + tile_base;
 
     float4 x[R];
-    load_params<R, ALIGNED>(p, tile_count, full, x);
+    if (MEAN) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) x[j] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);   // fma(1, v, -0) = v for every v
+    } else {
+        load_params<R, ALIGNED>(p, tile_count, full, x);
+    }
     float4 acc[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -196,6 +238,12 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
             }
         }
     }
+    if (MEAN) {
+        // mean = acc / W with one IEEE fp32 division per element; x = -0, so the store's fma(1, mean, -0) is mean
+        scale_to_mean<R>(acc, W);
+        update_params<R, ALIGNED>(p, tile_count, full, 1.0f, x, acc);
+        return;
+    }
     update_params<R, ALIGNED>(p, tile_count, full, neg_c, x, acc);
 }
 
@@ -204,6 +252,13 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const Ag
     extern __shared__ float s_step[];   // [W][nbt]
     aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket, a.bucket_shift,
                                           a.neg_c, a.params, (uint64_t)blockIdx.x * kLdsTile, s_step);
+}
+
+template <bool STRADDLE, bool ALIGNED, bool ONCE>
+__global__ __launch_bounds__(kThreads) void aggregate_mean_kernel(const AggregateArgs a) {
+    extern __shared__ float s_step[];   // [W][nbt]
+    aggregate_tile_lds<STRADDLE, ALIGNED, ONCE, true>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket,
+                                                      a.bucket_shift, 0.0f, a.params, (uint64_t)blockIdx.x * kLdsTile, s_step);
 }
 
 // Several tensors of a model in one launch: block -> (tensor, tile) through the prefix table of tile
@@ -288,7 +343,49 @@ hipError_t launch_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool alig
     return hipGetLastError();
 }
 
+template <int R, int NBR, bool STRADDLE>
+hipError_t launch_mean_rows(const AggregateArgs& a, hipStream_t stream) {
+    const uint32_t tile = 1024u * R;
+    const uint64_t tiles = (a.n + tile - 1) / tile;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
+    const dim3 grid((uint32_t)tiles), block(kThreads);
+    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(al)::value, decltype(once)::value, 0, true>),
+                           grid, block, 0, stream, a);
+    });
+    return hipGetLastError();
+}
+
+template <bool STRADDLE>
+hipError_t launch_mean_s(const AggregateArgs& a, hipStream_t stream) {
+    const uint64_t tiles = (a.n + kLdsTile - 1) / kLdsTile;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
+    const dim3 grid((uint32_t)tiles), block(kThreads);
+    const size_t lds = sizeof(float) * a.W * kMaxBuckets;
+    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
+        hipLaunchKernelGGL((aggregate_mean_kernel<STRADDLE, decltype(al)::value, decltype(once)::value>),
+                           grid, block, lds, stream, a);
+    });
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// a.params: the output (n floats); a.neg_c unused
+hipError_t launch_aggregate_mean(const AggregateArgs& a, hipStream_t stream) {
+    if (a.n == 0) return hipSuccess;
+    constexpr int R = MQG_AGG_ROWS_R;
+    const bool straddle = (32u % a.bits) != 0u;
+    if (a.bucket % 256u == 0u) {
+        return straddle ? launch_mean_rows<R, 1, true>(a, stream) : launch_mean_rows<R, 1, false>(a, stream);
+    }
+    if (a.bucket % 128u == 0u) {
+        return straddle ? launch_mean_rows<R, 2, true>(a, stream) : launch_mean_rows<R, 2, false>(a, stream);
+    }
+    return straddle ? launch_mean_s<true>(a, stream) : launch_mean_s<false>(a, stream);
+}
 
 uint32_t aggregate_batch_tile() { return kLdsTile; }
 

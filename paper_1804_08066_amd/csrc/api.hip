@@ -135,6 +135,38 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 
+mqg_status mqg_aggregate_mean(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                              uint64_t n, uint32_t bits, uint32_t bucket,
+                              float* mean_out, void* stream) {
+    if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (packed == nullptr || scales == nullptr || mean_out == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(mean_out)) return MQG_EALIGN;
+    mqg::AggregateArgs a;
+    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
+        a.packed[w] = nullptr;
+        a.scales[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || misaligned4(scales[w])) return MQG_EALIGN;
+        a.packed[w] = packed[w];
+        a.scales[w] = scales[w];
+    }
+    a.W = W;
+    a.n = n;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.neg_c = 0.0f;
+    a.params = mean_out;
+    a.per_tensor = 0u;
+    const hipError_t err = mqg::launch_aggregate_mean(a, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
 mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* const* scales, uint32_t W,
                                     uint64_t n, uint32_t bits, uint32_t bucket,
                                     uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,

@@ -93,6 +93,7 @@ hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream);
 bool requantize_wave_supported(const RequantArgs& a);         // quantize_wave.hip
 hipError_t launch_requantize_wave(const RequantArgs& a, hipStream_t stream);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);
+hipError_t launch_aggregate_mean(const AggregateArgs& a, hipStream_t stream);   // a.params receives the mean gradient
 
 // minmax.hip: deterministic [min, max] encoding; `scales` holds (min, max) pairs, 2 floats per bucket
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream);

@@ -18,7 +18,7 @@ MQG_MAX_WORKERS = 64
 EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
-    "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
+    "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_aggregate_mean", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
     "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax",
     "mqg_tensor_range", "mqg_quantize_minmax_tensor", "mqg_aggregate_update_minmax_tensor", "mqg_sum_squares", "mqg_adaptive_default_config",
     "mqg_adaptive_bits",
@@ -104,6 +104,8 @@ def lib():
     L.mqg_quantize_minmax_tensor.restype = C.c_int
     L.mqg_aggregate_update_minmax_tensor.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, f32, vp, vp]
     L.mqg_aggregate_update_minmax_tensor.restype = C.c_int
+    L.mqg_aggregate_mean.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, vp, vp]
+    L.mqg_aggregate_mean.restype = C.c_int
     L.mqg_sum_squares.argtypes = [vp, u64, vp, vp]
     L.mqg_sum_squares.restype = C.c_int
     L.mqg_adaptive_default_config.argtypes = [C.POINTER(AdaptiveConfig)]
@@ -227,6 +229,20 @@ def _worker_arrays(packed, scales, n, bits, bucket):
     pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
     sa = (C.c_void_p * max(W, 1))(*[s.data_ptr() for s in scales])
     return W, pa, sa
+
+
+def mqg_aggregate_mean(packed, scales, n, bits, bucket, mean_out=None, stream=None):
+    """Mean over the workers of their de-quantized gradients (W = 1: De-quantize). Returns the fp32 tensor."""
+    W, pa, sa = _worker_arrays(packed, scales, n, bits, bucket)
+    if mean_out is None:
+        mean_out = torch.empty(n, dtype=torch.float32, device=packed[0].device)
+    _check(mean_out, torch.float32, "mean_out")
+    if mean_out.numel() != n:
+        raise ValueError("mean_out must have n elements")
+    st = lib().mqg_aggregate_mean(pa, sa, W, n, bits, bucket, mean_out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_mean")
+    return mean_out
 
 
 def mqg_aggregate_requantize(packed, scales, n, bits, bucket, seed, iteration=0, worker=0, elem_base=0,

@@ -79,6 +79,14 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert a(scales=null1) == mqgrad.MQG_EINVAL
     assert a(params=C.c_void_p(0x1003)) == mqgrad.MQG_EALIGN
     assert a(n=0, params=None) == mqgrad.MQG_OK
+    m = lambda packed=one, scales=one, W=1, n=64, bits=4, bucket=512, out=fake: \
+        L.mqg_aggregate_mean(packed, scales, W, n, bits, bucket, out, None)
+    assert m(W=0) == mqgrad.MQG_EINVAL
+    assert m(bits=9) == mqgrad.MQG_EINVAL
+    assert m(out=None) == mqgrad.MQG_EINVAL
+    assert m(scales=null1) == mqgrad.MQG_EINVAL
+    assert m(out=C.c_void_p(0x1002)) == mqgrad.MQG_EALIGN
+    assert m(n=0, out=None) == mqgrad.MQG_OK
 
 
 def test_binding_refuses_cpu_tensors():

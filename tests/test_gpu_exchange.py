@@ -84,3 +84,17 @@ def test_full_exchange_iterations_stay_on_the_oracle():
         assert np.array_equal(to_u32(mean_pk), m_pk) and np.array_equal(mean_sc.cpu().numpy(), m_sc), "iteration %d" % it
         p_ref = ref.dequantize_update(m_pk, m_sc, n, bits, bucket, lr, p_ref)
         assert ulp_distance(params.cpu().numpy(), p_ref).max() == 0, "iteration %d" % it
+
+
+@pytest.mark.parametrize("bits", [1, 3, 4, 8])
+@pytest.mark.parametrize("W,bucket", [(1, 32), (3, 96), (8, 1024), (5, 16384)])
+def test_mean_gradient_output_matches_oracle(bits, W, bucket):
+    n = 2 * 16384 + 2048 + 13
+    grads = [workloads.normal(n, 0.01, 50 * w + bits, DEV) for w in range(W)]
+    q = [mqgrad.mqg_quantize(g, bits, bucket, seed=3, iteration=1, worker=w) for w, g in enumerate(grads)]
+    store = torch.full((n + 2,), 7.0, device=DEV)
+    out = mqgrad.mqg_aggregate_mean([x[0] for x in q], [x[1] for x in q], n, bits, bucket, mean_out=store[1:n + 1])
+    torch.cuda.synchronize()
+    want = ref.aggregate_mean([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n, bits, bucket)
+    assert out.cpu().numpy().tobytes() == want.tobytes()
+    assert store[0].item() == 7.0 and store[n + 1].item() == 7.0          # neighbours untouched
