@@ -312,6 +312,11 @@ void mqg_mdp_destroy(mqg_mdp* agent);
  * paper's transition function moves n_t by the greedy action only.  Returns 0 if agent is NULL. */
 uint32_t mqg_mdp_step(mqg_mdp* agent, double loss, double elapsed_ms);
 
+/* The same from the workers' local losses: the server restores the global loss as their mean over the
+ * P workers (Algorithm 1, ReceiveLossThenSendbits), summed in worker order, and steps the agent with it.
+ * Returns 0 if agent or worker_losses is NULL or P is 0. */
+uint32_t mqg_mdp_step_workers(mqg_mdp* agent, const double* worker_losses, uint32_t P, double elapsed_ms);
+
 /* Introspection for tests: current n_t, the smoothed-loss window (writes `window` doubles,
  * oldest first), the last reward, and the number of decisions taken so far. */
 uint32_t mqg_mdp_current_bits(const mqg_mdp* agent);

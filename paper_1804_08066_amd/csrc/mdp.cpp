@@ -237,6 +237,13 @@ uint32_t mqg_mdp_step(mqg_mdp* agent, double loss, double elapsed_ms) {
     return bits;
 }
 
+uint32_t mqg_mdp_step_workers(mqg_mdp* agent, const double* worker_losses, uint32_t P, double elapsed_ms) {
+    if (!agent || !worker_losses || P == 0u) return 0;
+    double sum = 0.0;
+    for (uint32_t p = 0; p < P; ++p) sum = sum + worker_losses[p];
+    return mqg_mdp_step(agent, sum / (double)P, elapsed_ms);
+}
+
 uint32_t mqg_mdp_current_bits(const mqg_mdp* agent) { return agent ? agent->n_t : 0u; }
 
 void mqg_mdp_smoothed_losses(const mqg_mdp* agent, double* out) {

@@ -22,7 +22,7 @@ EXPORTS = [
     "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax",
     "mqg_tensor_range", "mqg_quantize_minmax_tensor", "mqg_aggregate_update_minmax_tensor", "mqg_sum_squares", "mqg_adaptive_default_config",
     "mqg_adaptive_bits",
-    "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step",
+    "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step", "mqg_mdp_step_workers",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
 ]
 
@@ -120,6 +120,8 @@ def lib():
     L.mqg_mdp_destroy.restype = None
     L.mqg_mdp_step.argtypes = [vp, C.c_double, C.c_double]
     L.mqg_mdp_step.restype = u32
+    L.mqg_mdp_step_workers.argtypes = [vp, C.POINTER(C.c_double), u32, C.c_double]
+    L.mqg_mdp_step_workers.restype = u32
     L.mqg_mdp_current_bits.argtypes = [vp]
     L.mqg_mdp_current_bits.restype = u32
     L.mqg_mdp_smoothed_losses.argtypes = [vp, C.POINTER(C.c_double)]
@@ -499,6 +501,12 @@ class Mdp:
 
     def step(self, loss, elapsed_ms):
         return int(lib().mqg_mdp_step(self._h, float(loss), float(elapsed_ms)))
+
+    def step_workers(self, worker_losses, elapsed_ms):
+        """Step with the mean of the workers' local losses (Algorithm 1, ReceiveLossThenSendbits)."""
+        P = len(worker_losses)
+        arr = (C.c_double * max(P, 1))(*[float(v) for v in worker_losses])
+        return int(lib().mqg_mdp_step_workers(self._h, arr, P, float(elapsed_ms)))
 
     @property
     def current_bits(self):

@@ -105,3 +105,24 @@ def test_width_is_capped_at_the_maximum():
     seen = [agent.step(1.0 / (m + 1), 1.0) for m in range(50)]
     assert max(seen) == 8 and min(seen) >= 7
     assert agent.current_bits <= 8
+
+
+def test_step_from_worker_losses_is_step_with_their_mean():
+    # Algorithm 1, ReceiveLossThenSendbits: the global loss is the mean of the workers' local losses
+    import random
+    rnd = random.Random(4)
+    a = mqgrad.Mdp(seed=9)
+    b = mqgrad.Mdp(seed=9)
+    for m in range(60):
+        losses = [2.0 * 0.97 ** m + rnd.gauss(0, 0.01) for _ in range(5)]
+        mean = 0.0
+        for v in losses:
+            mean = mean + v
+        mean /= len(losses)
+        ka = a.step_workers(losses, 50.0)
+        kb = b.step(mean, 50.0)
+        assert ka == kb
+    assert a.smoothed_losses == b.smoothed_losses
+    assert a.step_workers([], 1.0) == 0
+    a.close()
+    b.close()
