@@ -68,3 +68,31 @@ def test_captured_step_replays_like_eager_launches():
         outs[0][0].zero_()
         sumsq.fill_(123.0)
         torch.cuda.synchronize()
+
+
+def test_workers_on_concurrent_streams_give_the_sequential_result():
+    # the library keeps no state between or across calls: W quantize calls in flight on W streams at
+    # once (default priority) write exactly what they write one after the other
+    n, W, bits, bucket = 3_000_000 + 5, 6, 3, 2048
+    grads = [workloads.laplace(n, 1e-3, 20 + w, DEV) for w in range(W)]
+    seq = [mqgrad.mqg_quantize(g, bits, bucket, seed=8, iteration=4, worker=w) for w, g in enumerate(grads)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(W)]
+    outs = [mqgrad.alloc_outputs(n, bits, bucket, DEV) for _ in range(W)]
+    for rep in range(3):
+        for w in range(W):
+            outs[w][0].zero_()
+        torch.cuda.synchronize()
+        for w in range(W):
+            mqgrad.mqg_quantize(grads[w], bits, bucket, seed=8, iteration=4, worker=w, packed_out=outs[w][0],
+                                scales_out=outs[w][1], stream=streams[w])
+        torch.cuda.synchronize()
+        for w in range(W):
+            assert torch.equal(outs[w][0], seq[w][0]) and torch.equal(outs[w][1], seq[w][1]), "stream %d rep %d" % (w, rep)
+    params_a = workloads.uniform(n, -0.05, 0.05, 1, DEV)
+    params_b = params_a.clone()
+    mqgrad.mqg_aggregate_update([o[0] for o in seq], [o[1] for o in seq], n, bits, bucket, 0.1, params_a)
+    with torch.cuda.stream(streams[0]):
+        mqgrad.mqg_aggregate_update([o[0] for o in outs], [o[1] for o in outs], n, bits, bucket, 0.1, params_b)
+    torch.cuda.synchronize()
+    assert torch.equal(params_a, params_b)
