@@ -493,9 +493,13 @@ hipError_t launch_quantize_r(const QuantizeArgs& a, hipStream_t stream) {
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(NT);
-    if (a.scales_in != nullptr) {
-        if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, true>), grid, block, 0, stream, a, tile_elems);
-        else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, true>), grid, block, 0, stream, a, tile_elems);
+    if (a.scales_in != nullptr) {   // whole-tensor range: the caller tiles with 4096-element tiles
+        if constexpr (NT == 256) {
+            if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, true>), grid, block, 0, stream, a, tile_elems);
+            else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, true>), grid, block, 0, stream, a, tile_elems);
+        } else {
+            return hipErrorInvalidValue;
+        }
     } else {
         if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, false>), grid, block, 0, stream, a, tile_elems);
         else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, false>), grid, block, 0, stream, a, tile_elems);
