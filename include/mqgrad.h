@@ -84,7 +84,7 @@ size_t mqg_packed_words(uint64_t n, uint32_t bits);
  *   packed_out  device, mqg_packed_words(n, bits) words, fully overwritten.
  *   scales_out  device, mqg_num_buckets(n, bucket) floats, fully overwritten.
  *   stream      hipStream_t.
- * Pointers need 4-byte alignment; 16-byte aligned `grad` takes the fast path.
+ * Pointers need 4-byte alignment only (128-bit accesses are used at any dword address).
  * Errors: MQG_EINVAL (bits, bucket, elem_base out of range; NULL pointer with n > 0),
  *         MQG_EALIGN, MQG_ELAUNCH. */
 mqg_status mqg_quantize(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,

@@ -17,7 +17,7 @@ FLAGS = [
     "-ffp-contract=off", "-fno-fast-math", "-fhip-fp32-correctly-rounded-divide-sqrt",
     "-fno-gpu-flush-denormals-to-zero",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wextra", "-Wno-unused-parameter",
+    "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wl,--no-undefined",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

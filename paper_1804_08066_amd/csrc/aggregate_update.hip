@@ -69,7 +69,7 @@ using decode::readlane_f32;
 // ---- buckets that are multiples of 128: bucket steps live in the wave ---------------------------
 // NBR = buckets a 256-element row can touch: 1 when the bucket is a multiple of 256, else 2.
 // MEAN: a.params is an output that receives acc / W (the mean gradient) instead of being updated.
-template <int R, int NBR, bool STRADDLE, bool ALIGNED, bool ONCE, int WIDTH, bool MEAN = false>
+template <int R, int NBR, bool STRADDLE, bool ONCE, int WIDTH, bool MEAN = false>
 __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const AggregateArgs a) {
     constexpr uint32_t TILE = 1024u * R;
     const uint32_t tid = threadIdx.x;
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
 #pragma unroll
         for (int j = 0; j < R; ++j) x[j] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);   // fma(1, v, -0) = v for every v
     } else {
-        load_params<R, ALIGNED>(p, tile_count, full, x);
+        load_params<R>(p, tile_count, full, x);
     }
 
     const uint32_t b = a.bits;
@@ -138,9 +138,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     }
     if (MEAN) {
         scale_to_mean<R>(acc, a.W);
-        update_params<R, ALIGNED>(p, tile_count, full, 1.0f, x, acc);
+        update_params<R>(p, tile_count, full, 1.0f, x, acc);
     } else {
-        update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+        update_params<R>(p, tile_count, full, a.neg_c, x, acc);
     }
 }
 
@@ -153,7 +153,7 @@ constexpr uint32_t kMaxBuckets = kLdsTile / 32u + 1u;   // buckets a tile can to
 // (in kernel-argument memory).  raw != nullptr: an uncompressed layer -- the W pointers are fp32
 // gradients that are summed in worker order instead of decoded.
 // MEAN: `params` is an output that receives acc / W (the mean gradient) instead of being updated.
-template <bool STRADDLE, bool ALIGNED, bool ONCE, bool MEAN = false>
+template <bool STRADDLE, bool ONCE, bool MEAN = false>
 __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed, const float* const* scales,
                                                    const float* const* raw, uint32_t W, uint64_t n, uint32_t b,
                                                    uint32_t bucket, int bucket_shift, float neg_c,
@@ -170,7 +170,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
 #pragma unroll
         for (int j = 0; j < R; ++j) x[j] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);   // fma(1, v, -0) = v for every v
     } else {
-        load_params<R, ALIGNED>(p, tile_count, full, x);
+        load_params<R>(p, tile_count, full, x);
     }
     float4 acc[R];
 #pragma unroll
@@ -183,13 +183,20 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const uint32_t el = 4u * (j * kThreads + tid);
-                if (el + 0u < tile_count) acc[j].x = acc[j].x + g[el + 0];
-                if (el + 1u < tile_count) acc[j].y = acc[j].y + g[el + 1];
-                if (el + 2u < tile_count) acc[j].z = acc[j].z + g[el + 2];
-                if (el + 3u < tile_count) acc[j].w = acc[j].w + g[el + 3];
+                if (full || el + 4u <= tile_count) {
+                    const float4 t = load_f4_stream(g + el);
+                    acc[j].x = acc[j].x + t.x;
+                    acc[j].y = acc[j].y + t.y;
+                    acc[j].z = acc[j].z + t.z;
+                    acc[j].w = acc[j].w + t.w;
+                } else {
+                    if (el + 0u < tile_count) acc[j].x = acc[j].x + g[el + 0];
+                    if (el + 1u < tile_count) acc[j].y = acc[j].y + g[el + 1];
+                    if (el + 2u < tile_count) acc[j].z = acc[j].z + g[el + 2];
+                }
             }
         }
-        update_params<R, ALIGNED>(p, tile_count, full, neg_c, x, acc);
+        update_params<R>(p, tile_count, full, neg_c, x, acc);
         return;
     }
 
@@ -241,29 +248,29 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
     if (MEAN) {
         // mean = acc / W with one IEEE fp32 division per element; x = -0, so the store's fma(1, mean, -0) is mean
         scale_to_mean<R>(acc, W);
-        update_params<R, ALIGNED>(p, tile_count, full, 1.0f, x, acc);
+        update_params<R>(p, tile_count, full, 1.0f, x, acc);
         return;
     }
-    update_params<R, ALIGNED>(p, tile_count, full, neg_c, x, acc);
+    update_params<R>(p, tile_count, full, neg_c, x, acc);
 }
 
-template <bool STRADDLE, bool ALIGNED, bool ONCE>
+template <bool STRADDLE, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_lds_kernel(const AggregateArgs a) {
     extern __shared__ float s_step[];   // [W][nbt]
-    aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket, a.bucket_shift,
+    aggregate_tile_lds<STRADDLE, ONCE>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket, a.bucket_shift,
                                           a.neg_c, a.params, (uint64_t)blockIdx.x * kLdsTile, s_step);
 }
 
-template <bool STRADDLE, bool ALIGNED, bool ONCE>
+template <bool STRADDLE, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_mean_kernel(const AggregateArgs a) {
     extern __shared__ float s_step[];   // [W][nbt]
-    aggregate_tile_lds<STRADDLE, ALIGNED, ONCE, true>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket,
+    aggregate_tile_lds<STRADDLE, ONCE, true>(a.packed, a.scales, nullptr, a.W, a.n, a.bits, a.bucket,
                                                       a.bucket_shift, 0.0f, a.params, (uint64_t)blockIdx.x * kLdsTile, s_step);
 }
 
 // Several tensors of a model in one launch: block -> (tensor, tile) through the prefix table of tile
 // counts.  A tensor is either quantized (W packed + W scale pointers) or raw (W fp32 gradients).
-template <bool STRADDLE, bool ALIGNED, bool ONCE>
+template <bool STRADDLE, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_tensors_kernel(const BatchAggregateArgs a) {
     extern __shared__ float s_step[];
     uint32_t lo = 0, hi = a.count;           // tile_start[lo] <= blockIdx.x < tile_start[hi]
@@ -275,23 +282,19 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_tensors_kernel(cons
     const uint64_t tile_base = (uint64_t)(blockIdx.x - a.tile_start[lo]) * kLdsTile;
     const void* const* ptrs = a.ptrs + t.first_ptr;
     if (t.raw) {
-        aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(nullptr, nullptr, reinterpret_cast<const float* const*>(ptrs), a.W, t.n,
+        aggregate_tile_lds<STRADDLE, ONCE>(nullptr, nullptr, reinterpret_cast<const float* const*>(ptrs), a.W, t.n,
                                               a.bits, a.bucket, a.bucket_shift, a.neg_c, t.params, tile_base, s_step);
     } else {
-        aggregate_tile_lds<STRADDLE, ALIGNED, ONCE>(reinterpret_cast<const uint32_t* const*>(ptrs),
+        aggregate_tile_lds<STRADDLE, ONCE>(reinterpret_cast<const uint32_t* const*>(ptrs),
                                               reinterpret_cast<const float* const*>(ptrs + a.W), nullptr, a.W, t.n,
                                               a.bits, a.bucket, a.bucket_shift, a.neg_c, t.params, tile_base, s_step);
     }
 }
 
-// Calls f(aligned, read_once) with the two flags as compile-time constants.
+// Calls f(read_once) with the flag as a compile-time constant.
 template <class F>
-void with_flags(bool aligned, bool once, F f) {
-    if (aligned) {
-        if (once) f(std::true_type{}, std::true_type{}); else f(std::true_type{}, std::false_type{});
-    } else {
-        if (once) f(std::false_type{}, std::true_type{}); else f(std::false_type{}, std::false_type{});
-    }
+void with_once(bool once, F f) {
+    if (once) f(std::true_type{}); else f(std::false_type{});
 }
 
 template <int R, int NBR, bool STRADDLE>
@@ -299,20 +302,17 @@ hipError_t launch_rows(const AggregateArgs& a, hipStream_t stream) {
     const uint32_t tile = 1024u * R;
     const uint64_t tiles = (a.n + tile - 1) / tile;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     if (a.bits == 1u || a.bits == 8u) {   // three-operation decodes; neither width straddles words
         if (a.bits == 1u) {
-            if (aligned) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, true, false, 1>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, false, 1>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, 1>), grid, block, 0, stream, a);
         } else {
-            if (aligned) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, true, true, 8>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, true, 8>), grid, block, 0, stream, a);
+            hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, true, 8>), grid, block, 0, stream, a);
         }
         return hipGetLastError();
     }
-    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
-        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(al)::value, decltype(once)::value, 0>),
+    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(once)::value, 0>),
                            grid, block, 0, stream, a);
     });
     return hipGetLastError();
@@ -322,22 +322,21 @@ template <bool STRADDLE>
 hipError_t launch_lds(const AggregateArgs& a, hipStream_t stream) {
     const uint64_t tiles = (a.n + kLdsTile - 1) / kLdsTile;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     const size_t lds = sizeof(float) * a.W * kMaxBuckets;
-    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
-        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, decltype(al)::value, decltype(once)::value>),
+    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+        hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, decltype(once)::value>),
                            grid, block, lds, stream, a);
     });
     return hipGetLastError();
 }
 
 template <bool STRADDLE>
-hipError_t launch_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+hipError_t launch_tensors(const BatchAggregateArgs& a, uint32_t tiles, hipStream_t stream) {
     const dim3 grid(tiles), block(kThreads);
     const size_t lds = sizeof(float) * a.W * kMaxBuckets;
-    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
-        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, decltype(al)::value, decltype(once)::value>),
+    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+        hipLaunchKernelGGL((aggregate_update_tensors_kernel<STRADDLE, decltype(once)::value>),
                            grid, block, lds, stream, a);
     });
     return hipGetLastError();
@@ -348,10 +347,9 @@ hipError_t launch_mean_rows(const AggregateArgs& a, hipStream_t stream) {
     const uint32_t tile = 1024u * R;
     const uint64_t tiles = (a.n + tile - 1) / tile;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
-    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
-        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(al)::value, decltype(once)::value, 0, true>),
+    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+        hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(once)::value, 0, true>),
                            grid, block, 0, stream, a);
     });
     return hipGetLastError();
@@ -361,11 +359,10 @@ template <bool STRADDLE>
 hipError_t launch_mean_s(const AggregateArgs& a, hipStream_t stream) {
     const uint64_t tiles = (a.n + kLdsTile - 1) / kLdsTile;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     const size_t lds = sizeof(float) * a.W * kMaxBuckets;
-    with_flags(aligned, decode::codes_read_once(a.bits), [&](auto al, auto once) {
-        hipLaunchKernelGGL((aggregate_mean_kernel<STRADDLE, decltype(al)::value, decltype(once)::value>),
+    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+        hipLaunchKernelGGL((aggregate_mean_kernel<STRADDLE, decltype(once)::value>),
                            grid, block, lds, stream, a);
     });
     return hipGetLastError();
@@ -389,10 +386,10 @@ hipError_t launch_aggregate_mean(const AggregateArgs& a, hipStream_t stream) {
 
 uint32_t aggregate_batch_tile() { return kLdsTile; }
 
-hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, hipStream_t stream) {
     if (tiles == 0) return hipSuccess;
     const bool straddle = (32u % a.bits) != 0u;
-    return straddle ? launch_tensors<true>(a, tiles, aligned, stream) : launch_tensors<false>(a, tiles, aligned, stream);
+    return straddle ? launch_tensors<true>(a, tiles, stream) : launch_tensors<false>(a, tiles, stream);
 }
 
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream) {

@@ -237,11 +237,7 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
     a.common.packed = nullptr;
     a.common.scales = nullptr;
     a.count = count;
-    bool aligned = true;
-    for (uint32_t i = 0; i < count; ++i) {
-        if (items[i].n != 0 && (reinterpret_cast<uintptr_t>(items[i].grad) & 15u) != 0) aligned = false;
-    }
-    a.tile_elems = mqg::quantize_batch_tile(bucket, bits, a.common.bucket_shift, aligned);
+    a.tile_elems = mqg::quantize_batch_tile(bucket, bits, a.common.bucket_shift);
     uint64_t tiles = 0;
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
         a.tile_start[i] = (uint32_t)tiles;
@@ -259,7 +255,7 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
         if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
     }
     a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
-    const hipError_t err = mqg::launch_quantize_tensors(a, (uint32_t)tiles, aligned, static_cast<hipStream_t>(stream));
+    const hipError_t err = mqg::launch_quantize_tensors(a, (uint32_t)tiles, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 
@@ -279,7 +275,6 @@ mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t c
     a.neg_c = -(lr / (float)W);
     for (uint32_t i = 0; i < mqg::kMaxBatchPointers; ++i) a.ptrs[i] = nullptr;
     const uint32_t tile = mqg::aggregate_batch_tile();
-    bool aligned = true;
     uint64_t tiles = 0;
     uint32_t used = 0;
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
@@ -290,7 +285,6 @@ mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t c
         if (it.n == 0) continue;
         if (it.params == nullptr || it.n > (UINT64_MAX >> 4)) return MQG_EINVAL;
         if (misaligned4(it.params)) return MQG_EALIGN;
-        if ((reinterpret_cast<uintptr_t>(it.params) & 15u) != 0) aligned = false;
         const bool raw = it.packed == nullptr;
         const uint32_t need = raw ? W : 2u * W;
         if (used + need > mqg::kMaxBatchPointers) return MQG_EINVAL;
@@ -316,7 +310,7 @@ mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t c
         if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
     }
     a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
-    const hipError_t err = mqg::launch_aggregate_tensors(a, (uint32_t)tiles, aligned, static_cast<hipStream_t>(stream));
+    const hipError_t err = mqg::launch_aggregate_tensors(a, (uint32_t)tiles, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 

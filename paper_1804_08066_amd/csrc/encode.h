@@ -19,6 +19,10 @@ constexpr int kDppRowMirror = 0x140;      // lane i <-> 15 - i inside each row o
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+// the same 128-bit vectors at 4-byte alignment: global memory takes multi-dword accesses at any dword
+// address, so a tensor that starts off a 16-byte boundary is still read and written 128 bits at a time
+typedef v4f v4f_a4 __attribute__((aligned(4)));
+typedef v4u v4u_a4 __attribute__((aligned(4)));
 
 // DPP reads of a switched-off lane return 0: call these with every lane of the wave active.
 template <int CTRL>

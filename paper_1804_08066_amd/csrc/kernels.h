@@ -80,11 +80,11 @@ struct BatchQuantizeArgs {
 };
 
 uint32_t aggregate_batch_tile();
-hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, bool aligned, hipStream_t stream);
-uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift, bool aligned);   // elements per workgroup
+hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, hipStream_t stream);
+uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift);   // elements per workgroup
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits);                             // quantize_wave.hip
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream);
-hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream);
+hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream);
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_requantize(const RequantArgs& a, hipStream_t stream);

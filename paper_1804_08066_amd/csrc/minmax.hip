@@ -39,19 +39,15 @@ struct Shared {
 };
 
 // one HBM pass: the tile of the gradient into registers
-template <int R, int NT, bool ALIGNED, bool FULL>
+template <int R, int NT, bool FULL>
 __device__ __forceinline__ void load_grad_tile(const float* __restrict__ g, const uint32_t tile_count, float4 (&x)[R]) {
     const uint32_t tid = threadIdx.x;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const uint32_t el = 4u * (j * NT + tid);
         if (FULL || el + 4u <= tile_count) {
-            if (ALIGNED) {
-                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + el));
-                x[j] = make_float4(t.x, t.y, t.z, t.w);
-            } else {
-                x[j] = make_float4(g[el], g[el + 1], g[el + 2], g[el + 3]);
-            }
+            const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f_a4*>(g + el));
+            x[j] = make_float4(t.x, t.y, t.z, t.w);
         } else {
             x[j].x = (el + 0u < tile_count) ? g[el + 0] : 0.0f;
             x[j].y = (el + 1u < tile_count) ? g[el + 1] : 0.0f;
@@ -211,7 +207,7 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
 }
 
 // GIVEN: the range is read from a.scales_in (one pair for the whole tensor) instead of computed per bucket
-template <int R, int NT, bool ALIGNED, bool GIVEN>
+template <int R, int NT, bool GIVEN>
 __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
     __shared__ Shared<R, NT> sm;
     const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
@@ -219,12 +215,12 @@ __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs 
     const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
     float4 x[R];
     if (tile_count == Shared<R, NT>::kCap) {
-        load_grad_tile<R, NT, ALIGNED, true>(a.grad + tile_base, tile_count, x);
+        load_grad_tile<R, NT, true>(a.grad + tile_base, tile_count, x);
         clear_shared<R, NT>(sm, tile_count, a.bits);   // while the loads are in flight
         __syncthreads();
         encode_minmax_tile<R, NT, true, GIVEN>(a, tile_base, tile_count, x, 1.0f, sm);
     } else {
-        load_grad_tile<R, NT, ALIGNED, false>(a.grad + tile_base, tile_count, x);
+        load_grad_tile<R, NT, false>(a.grad + tile_base, tile_count, x);
         clear_shared<R, NT>(sm, tile_count, a.bits);
         __syncthreads();
         encode_minmax_tile<R, NT, false, GIVEN>(a, tile_base, tile_count, x, 1.0f, sm);
@@ -298,7 +294,7 @@ constexpr int kAggR = 2;
 constexpr uint32_t kAggTile = 1024u * kAggR;
 constexpr uint32_t kMaxBuckets = kAggTile / 32u + 1u;   // buckets a tile can touch
 
-template <bool STRADDLE, bool ALIGNED, bool ONCE>
+template <bool STRADDLE, bool ONCE>
 __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const AggregateArgs a) {
     extern __shared__ float2 s_tab[];   // [W][nbt]: (step, min) of each worker's buckets of the tile
     constexpr int R = kAggR;
@@ -310,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
     float* __restrict__ p = a.params + tile_base;
 
     float4 x[R];
-    tile_io::load_params<R, ALIGNED>(p, tile_count, full, x);
+    tile_io::load_params<R>(p, tile_count, full, x);
     float4 acc[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -352,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
             }
         }
     }
-    tile_io::update_params<R, ALIGNED>(p, tile_count, full, a.neg_c, x, acc);
+    tile_io::update_params<R>(p, tile_count, full, a.neg_c, x, acc);
 }
 
 // ---- whole-tensor range ---------------------------------------------------------------------------
@@ -491,18 +487,15 @@ hipError_t launch_quantize_r(const QuantizeArgs& a, hipStream_t stream) {
     const uint32_t tile_elems = (cap / a.bucket) * a.bucket;   // whole buckets, >= 1 by choice of R
     const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(NT);
     if (a.scales_in != nullptr) {   // whole-tensor range: the caller tiles with 4096-element tiles
         if constexpr (NT == 256) {
-            if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, true>), grid, block, 0, stream, a, tile_elems);
-            else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, true>), grid, block, 0, stream, a, tile_elems);
+            hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true>), grid, block, 0, stream, a, tile_elems);
         } else {
             return hipErrorInvalidValue;
         }
     } else {
-        if (aligned) hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true, false>), grid, block, 0, stream, a, tile_elems);
-        else hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false, false>), grid, block, 0, stream, a, tile_elems);
+        hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false>), grid, block, 0, stream, a, tile_elems);
     }
     return hipGetLastError();
 }
@@ -511,16 +504,12 @@ template <bool STRADDLE>
 hipError_t launch_aggregate_s(const AggregateArgs& a, hipStream_t stream) {
     const uint64_t tiles = (a.n + kAggTile - 1) / kAggTile;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.params) & 15u) == 0;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     const size_t lds = sizeof(float2) * a.W * kMaxBuckets;
-    const bool once = decode::codes_read_once(a.bits);
-    if (aligned) {
-        if (once) hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true, true>), grid, block, lds, stream, a);
-        else hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true, false>), grid, block, lds, stream, a);
+    if (decode::codes_read_once(a.bits)) {
+        hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, true>), grid, block, lds, stream, a);
     } else {
-        if (once) hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false, true>), grid, block, lds, stream, a);
-        else hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false, false>), grid, block, lds, stream, a);
+        hipLaunchKernelGGL((aggregate_update_minmax_kernel<STRADDLE, false>), grid, block, lds, stream, a);
     }
     return hipGetLastError();
 }

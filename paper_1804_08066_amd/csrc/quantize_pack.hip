@@ -1,7 +1,7 @@
 // Quantize(g, K) of Algorithm 1 on gfx950, workgroup-cooperative variant: the range-linear K-bit
 // encode of the Section 3.2 footnote in ONE pass over its input.  This kernel takes every bucket
-// size (any multiple of 32), any 4-byte alignment and both scale modes; power-of-two buckets on
-// aligned gradients go to the wave-local kernel in quantize_wave.hip instead.
+// size (any multiple of 32) and both scale modes; power-of-two buckets go to the wave-local kernel in
+// quantize_wave.hip instead.
 //
 //   a1  per-bucket range  s = max |g|            (DPP max over 8-lane cells, LDS max per bucket)
 //   a2  position on the 2^K-level grid           u = clamp(fma(g, (L/2)/s, L/2), 0, L)
@@ -64,7 +64,7 @@ __device__ __forceinline__ void bucket_of_quads(uint32_t bucket, int bucket_shif
 }
 
 // ---- source: the worker's gradient ---------------------------------------------------------------
-template <int R, bool ALIGNED>
+template <int R>
 struct GradSource {
     const float* __restrict__ g;
     float4 v[R];
@@ -76,12 +76,8 @@ struct GradSource {
         for (int j = 0; j < R; ++j) {
             const uint32_t el = 4u * (j * kThreads + tid);
             if (full || el + 4u <= tile_count) {
-                if (ALIGNED) {
-                    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + el));   // read once: streaming
-                    v[j] = make_float4(t.x, t.y, t.z, t.w);
-                } else {
-                    v[j] = make_float4(g[el], g[el + 1], g[el + 2], g[el + 3]);
-                }
+                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f_a4*>(g + el));   // read once: streaming
+                v[j] = make_float4(t.x, t.y, t.z, t.w);
             } else {
                 v[j].x = (el + 0u < tile_count) ? g[el + 0] : 0.0f;
                 v[j].y = (el + 1u < tile_count) ? g[el + 1] : 0.0f;
@@ -322,7 +318,7 @@ __device__ __forceinline__ void clear_shared(Shared<R>& sm, uint32_t tile_count,
     if (threadIdx.x < 128u) sm.bmax[threadIdx.x] = 0u;
 }
 
-template <int R, bool ALIGNED>
+template <int R>
 __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
     __shared__ Shared<R> sm;
     const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
@@ -330,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(const QuantizeA
     const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
     const bool full = tile_count == Tile<R>::kCap;
 
-    GradSource<R, ALIGNED> src;
+    GradSource<R> src;
     src.g = a.grad + tile_base;
     src.issue(tile_count, full);
     clear_shared<R>(sm, tile_count, a.bits);   // while the loads are in flight
@@ -369,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void requantize_pack_kernel(const Requant
 }
 
 // Several layer tensors of one worker in one launch: block -> (tensor, tile) through the prefix table.
-template <int R, bool ALIGNED>
+template <int R>
 __global__ __launch_bounds__(kThreads) void quantize_tensors_kernel(const BatchQuantizeArgs ba) {
     __shared__ Shared<R> sm;
     uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
@@ -388,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void quantize_tensors_kernel(const BatchQ
     const uint32_t tile_count = left < ba.tile_elems ? (uint32_t)left : ba.tile_elems;
     const bool full = tile_count == Tile<R>::kCap;
 
-    GradSource<R, ALIGNED> src;
+    GradSource<R> src;
     src.g = a.grad + tile_base;
     src.issue(tile_count, full);
     clear_shared<R>(sm, tile_count, a.bits);
@@ -403,13 +399,8 @@ __global__ __launch_bounds__(kThreads) void quantize_tensors_kernel(const BatchQ
 }
 
 template <int R>
-hipError_t launch_tensors_r(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
-    const dim3 grid(tiles), block(kThreads);
-    if (aligned) {
-        hipLaunchKernelGGL((quantize_tensors_kernel<R, true>), grid, block, 0, stream, a);
-    } else {
-        hipLaunchKernelGGL((quantize_tensors_kernel<R, false>), grid, block, 0, stream, a);
-    }
+hipError_t launch_tensors_r(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream) {
+    hipLaunchKernelGGL((quantize_tensors_kernel<R>), dim3(tiles), dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -419,13 +410,7 @@ hipError_t launch_r(const QuantizeArgs& a, hipStream_t stream) {
     const uint32_t tile_elems = (cap / a.bucket) * a.bucket;   // whole buckets, >= 1 by choice of R
     const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
-    const dim3 grid((uint32_t)tiles), block(kThreads);
-    if (aligned) {
-        hipLaunchKernelGGL((quantize_pack_kernel<R, true>), grid, block, 0, stream, a, tile_elems);
-    } else {
-        hipLaunchKernelGGL((quantize_pack_kernel<R, false>), grid, block, 0, stream, a, tile_elems);
-    }
+    hipLaunchKernelGGL((quantize_pack_kernel<R>), dim3((uint32_t)tiles), dim3(kThreads), 0, stream, a, tile_elems);
     return hipGetLastError();
 }
 
@@ -454,21 +439,21 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
     return launch_r<16>(a, stream);
 }
 
-// Power-of-two buckets on 16-byte aligned gradients take the wave-local kernel, like single calls.
-static bool batch_takes_wave_kernel(int bucket_shift, bool aligned) { return aligned && bucket_shift >= 5; }
+// Power-of-two buckets take the wave-local kernel, like single calls.
+static bool batch_takes_wave_kernel(int bucket_shift) { return bucket_shift >= 5; }
 
-uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift, bool aligned) {
-    if (batch_takes_wave_kernel(bucket_shift, aligned)) return quantize_wave_block_elems(bucket, bits);
+uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift) {
+    if (batch_takes_wave_kernel(bucket_shift)) return quantize_wave_block_elems(bucket, bits);
     const uint32_t cap = bucket <= 4096u ? Tile<4>::kCap : (bucket <= 8192u ? Tile<8>::kCap : Tile<16>::kCap);
     return (cap / bucket) * bucket;
 }
 
-hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, bool aligned, hipStream_t stream) {
+hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream) {
     if (tiles == 0) return hipSuccess;
-    if (batch_takes_wave_kernel(a.common.bucket_shift, aligned)) return launch_quantize_tensors_wave(a, tiles, stream);
-    if (a.common.bucket <= 4096u) return launch_tensors_r<4>(a, tiles, aligned, stream);
-    if (a.common.bucket <= 8192u) return launch_tensors_r<8>(a, tiles, aligned, stream);
-    return launch_tensors_r<16>(a, tiles, aligned, stream);
+    if (batch_takes_wave_kernel(a.common.bucket_shift)) return launch_quantize_tensors_wave(a, tiles, stream);
+    if (a.common.bucket <= 4096u) return launch_tensors_r<4>(a, tiles, stream);
+    if (a.common.bucket <= 8192u) return launch_tensors_r<8>(a, tiles, stream);
+    return launch_tensors_r<16>(a, tiles, stream);
 }
 
 hipError_t launch_requantize(const RequantArgs& ra, hipStream_t stream) {

@@ -1,7 +1,7 @@
 // Worker side of MQGrad's hot path on gfx950, wavefront-local variant: Quantize(g, K) of
 // Algorithm 1 (WorkerIterate), the range-linear K-bit encode of the Section 3.2 footnote, for
-// power-of-two buckets and 16-byte aligned gradients.  (Other bucket sizes and alignments take the
-// workgroup-cooperative kernel in quantize_pack.hip; both produce the same bits.)
+// power-of-two buckets.  (Other bucket sizes take the workgroup-cooperative kernel in
+// quantize_pack.hip; both produce the same bits.)
 //
 //   a1  per-bucket range  s = max |g|           DPP / swizzle butterfly inside the wave
 //       (or the bucket's L2 norm: quad squares in fp32, a fp64 butterfly above them)
@@ -133,7 +133,7 @@ __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const flo
     if (FULL) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + 4u * (j * 64u + lane)));
+            const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f_a4*>(g + 4u * (j * 64u + lane)));
             x[j] = make_float4(t.x, t.y, t.z, t.w);
         }
     } else {
@@ -299,10 +299,10 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
 
     // store the chunk's words
     uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
-    if (FULL && (reinterpret_cast<uintptr_t>(a.packed) & 15u) == 0u) {
+    if (FULL) {
         for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
             const v4u w = *reinterpret_cast<const v4u*>(&sm.words[wave][4u * i]);
-            __builtin_nontemporal_store(w, reinterpret_cast<v4u*>(out) + i);
+            __builtin_nontemporal_store(w, reinterpret_cast<v4u_a4*>(out) + i);
         }
     } else {
         const uint32_t nwords = (count * b + 31u) >> 5;
@@ -514,12 +514,9 @@ hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-// True when the wave-local kernel covers this call: power-of-two bucket,
-// 16-byte aligned gradient.
-bool quantize_wave_supported(const QuantizeArgs& a) {
-    return a.bucket_shift >= 5 &&
-           (reinterpret_cast<uintptr_t>(a.grad) & 15u) == 0;
-}
+// True when the wave-local kernel covers this call: every power-of-two bucket (any 4-byte alignment:
+// the 128-bit accesses only need dword alignment).
+bool quantize_wave_supported(const QuantizeArgs& a) { return a.bucket_shift >= 5; }
 
 // elements per workgroup of the wave-local kernel at this bucket size
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits) {

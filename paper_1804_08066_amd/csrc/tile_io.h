@@ -10,17 +10,21 @@ namespace tile_io {
 constexpr int kThreads = 256;
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+// Global memory takes multi-dword accesses at any dword address: a tensor that starts off a 16-byte
+// boundary is still read and written 128 bits at a time (a wave's row then touches nine 128-byte lines
+// instead of eight).
+typedef v4f v4f_a4 __attribute__((aligned(4)));
 
 __device__ __forceinline__ float4 load_f4_stream(const float* p) {
-    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f_a4*>(p));
     return make_float4(t.x, t.y, t.z, t.w);
 }
 __device__ __forceinline__ void store_f4_stream(float* p, const float4& r) {
     v4f t = {r.x, r.y, r.z, r.w};
-    __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f_a4*>(p));
 }
 
-template <int R, bool ALIGNED>
+template <int R>
 __device__ __forceinline__ void load_params(const float* __restrict__ p, uint32_t tile_count, bool full,
                                             float4 (&x)[R]) {
     const uint32_t tid = threadIdx.x;
@@ -28,11 +32,7 @@ __device__ __forceinline__ void load_params(const float* __restrict__ p, uint32_
     for (int j = 0; j < R; ++j) {
         const uint32_t el = 4u * (j * kThreads + tid);
         if (full || el + 4u <= tile_count) {
-            if (ALIGNED) {
-                x[j] = load_f4_stream(p + el);
-            } else {
-                x[j] = make_float4(p[el], p[el + 1], p[el + 2], p[el + 3]);
-            }
+            x[j] = load_f4_stream(p + el);
         } else {
             x[j].x = (el + 0u < tile_count) ? p[el + 0] : 0.0f;
             x[j].y = (el + 1u < tile_count) ? p[el + 1] : 0.0f;
@@ -43,7 +43,7 @@ __device__ __forceinline__ void load_params(const float* __restrict__ p, uint32_
 }
 
 // a7: p <- fma(-(lr/W), acc, p)
-template <int R, bool ALIGNED>
+template <int R>
 __device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t tile_count, bool full, float neg_c,
                                               const float4 (&x)[R], const float4 (&acc)[R]) {
     const uint32_t tid = threadIdx.x;
@@ -56,11 +56,7 @@ __device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t ti
         r.z = __builtin_fmaf(neg_c, acc[j].z, x[j].z);
         r.w = __builtin_fmaf(neg_c, acc[j].w, x[j].w);
         if (full || el + 4u <= tile_count) {
-            if (ALIGNED) {
-                store_f4_stream(p + el, r);
-            } else {
-                p[el] = r.x; p[el + 1] = r.y; p[el + 2] = r.z; p[el + 3] = r.w;
-            }
+            store_f4_stream(p + el, r);
         } else {
             if (el + 0u < tile_count) p[el + 0] = r.x;
             if (el + 1u < tile_count) p[el + 1] = r.y;
