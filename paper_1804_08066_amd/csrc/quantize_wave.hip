@@ -16,8 +16,8 @@
 // rounding and the packing need no workgroup barrier.  Larger buckets (WPB = 2 .. 16 waves per
 // bucket) exchange one value per wave through LDS behind a single barrier.
 //
-// The kernel is bound by vector-ALU issue rather than by HBM once the loads stream, so work is
-// moved off the vector ALU where possible: cross-lane exchange through LDS-pipe swizzles, per-bucket
+// The kernel sits close to both of its limits (the vector ALU is busy for about three quarters of
+// its HBM-bound duration), so work is moved off the vector ALU where possible: cross-lane exchange through LDS-pipe swizzles, per-bucket
 // values through small per-wave LDS tables, bit placement through LDS atomics.
 
 #include "decode.h"
