@@ -546,7 +546,8 @@ hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
         case 2048: return launch_requant_wave<4, 2, 4>(ra, stream);
         case 4096: return launch_requant_wave<4, 4, 4>(ra, stream);
         case 8192: return launch_requant_wave<8, 4, 4>(ra, stream);
-        case 16384: return launch_requant_wave<4, 16, 16>(ra, stream);
+        case 16384: return ra.q.bits == 8u ? launch_requant_wave<8, 8, 8>(ra, stream)
+                                           : launch_requant_wave<4, 16, 16>(ra, stream);
         default: return launch_requant_wave<4, 1, 4>(ra, stream);   // 256 .. 1024
     }
 }
