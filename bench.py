@@ -164,13 +164,13 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
     m_bytes = W * (n * bits / 8.0 + 4.0 * nb) + 4.0 * n
     r_bytes = (W + 1) * (n * bits / 8.0 + 4.0 * nb)
     d_bytes = n * bits / 8.0 + 4.0 * nb + 8.0 * n
-    r_ops = n * ((3.0 if bits in (1, 8) else 4.0) * W + 17.0)   # 1 and 8 bits decode in three operations
+    r_ops = n * ((3.0 if bits in (1, 8) else 3.5) * W + 17.0)   # decode: 3 operations per code at 1 and 8 bits, else 3.5
     log("exchange: requantize %.1f us (%.1f T lane-ops/s, %.0f GB/s), dequantize_update %.1f us (%.0f GB/s), "
         "aggregate_mean %.1f us (%.0f GB/s)" %
         (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9,
          m_ms * 1e3, m_bytes / (m_ms * 1e-3) / 1e9))
     return {
-        "requantize": {"kernel": "requantize_pack_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
+        "requantize": {"kernel": "requantize_wave_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
                        "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T lane-ops/s",
                        "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
                        "algorithmic_ops_per_launch": r_ops, "algorithmic_bytes_per_launch": r_bytes,

@@ -73,7 +73,8 @@ template <int R, int NBR, bool STRADDLE, bool ONCE, int WIDTH, bool MEAN = false
 __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const AggregateArgs a) {
     constexpr uint32_t TILE = 1024u * R;
     const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
     const uint64_t tile_base = (uint64_t)blockIdx.x * TILE;
     const uint64_t left = a.n - tile_base;
     const uint32_t tile_count = left < TILE ? (uint32_t)left : TILE;
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
     }
 
     const uint32_t b = a.bits;
-    const int negL = -(int)((1u << b) - 1u);
+    const decode::Centred cd = decode::centred(b);
     const float Lf = (float)((1u << b) - 1u);
     const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
                 for (int j = 0; j < R; ++j) {
                     float dw = readlane_f32(d[j][0], w0 + t);
                     if (NBR > 1) dw = second[j] ? readlane_f32(d[j][NBR - 1], w0 + t) : dw;
-                    decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], b, negL, dw, acc[j]);
+                    decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], cd, dw, acc[j]);
                 }
             }
         }
@@ -200,7 +201,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
         return;
     }
 
-    const int negL = -(int)((1u << b) - 1u);
+    const decode::Centred cd = decode::centred(b);
     const float Lf = (float)((1u << b) - 1u);
     const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
@@ -240,7 +241,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
                 const float* __restrict__ dw = s_step + (w0 + t) * nbt;
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], b, negL, dw[bl[j]], acc[j]);
+                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], cd, dw[bl[j]], acc[j]);
                 }
             }
         }

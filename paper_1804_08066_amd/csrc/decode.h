@@ -19,8 +19,8 @@ constexpr int kDppWaveShl1 = 0x130;   // DPP wave_shl:1: lane i reads lane i + 1
 // clamped to the last word of the stream so that quads past the end still read valid memory).
 template <int R>
 struct CodeWindows {
-    uint32_t word[R];    // first word
-    uint32_t sh[R];      // bit offset of the first code inside `word`
+    uint32_t byte[R];    // byte offset of the quad's first word from the tile's first word (< 2^32)
+    uint32_t sh[R];      // bit offset of the first code inside that word
     uint64_t tile_word;  // first word of the tile in the stream
 };
 
@@ -42,7 +42,7 @@ __device__ __forceinline__ CodeWindows<R> code_windows(uint64_t n, uint64_t tile
             word = last_word;
             sh = 0u;
         }
-        cw.word[j] = word;
+        cw.byte[j] = word * 4u;
         cw.sh[j] = sh;
     }
     return cw;
@@ -70,10 +70,12 @@ __device__ __forceinline__ void fetch_codes(const uint32_t* const* packed, uint3
 #pragma unroll
     for (int t = 0; t < CH; ++t) {
         if (w0 + t < W) {
-            const uint32_t* __restrict__ src = packed[w0 + t] + cw.tile_word;
+            // uniform base + 32-bit lane offset: the address costs no vector operation
+            const char* __restrict__ src = (const char*)(packed[w0 + t] + cw.tile_word);
 #pragma unroll
             for (int j = 0; j < R; ++j) {
-                c.lo[t][j] = ONCE ? __builtin_nontemporal_load(src + cw.word[j]) : src[cw.word[j]];
+                const uint32_t* q = (const uint32_t*)(src + cw.byte[j]);
+                c.lo[t][j] = ONCE ? __builtin_nontemporal_load(q) : *q;
             }
         }
     }
@@ -101,24 +103,68 @@ __device__ __forceinline__ void extract_quad(uint32_t lo, uint32_t sh, uint32_t 
     k[3] = (int)__builtin_amdgcn_ubfe(v, o + 3u * b, b);
 }
 
+// (float)(2c - L) without extracting c: two vector operations per code, where bit-field extract,
+// shift-add and convert take three.
+// With the b-bit code at bit P of `y` (P = 1 or 1 + b; the other bits of `y` are arbitrary):
+//   1. AND with the field mask, OR with the bits of 1.0f: the code becomes mantissa bits of
+//      x = 1 + c * 2^(P - 23)  (P + b <= 23 holds for b <= 8);
+//   2. one fma: x * 2^(24 - P) - (2^(24 - P) + L) = 2c - L.  Every quantity is a whole number of
+//      units 2^(1 - P) <= 1 and below 2^24 units, so the constants are exact and the fma rounds nothing.
+// The constants are uniform; the subtrahends are pinned to vector registers (an fma takes one scalar
+// operand) so that no use re-materialises them.
+struct Centred {
+    uint32_t b;
+    uint32_t field[2];    // L << P
+    float scale[2];       // 2^(24 - P)
+    float minus_c[2];     // -(2^(24 - P) + L)
+};
+__device__ __forceinline__ Centred centred(uint32_t b) {
+    const uint32_t L = (1u << b) - 1u;
+    Centred cd;
+    cd.b = b;
+    cd.field[0] = L << 1;
+    cd.field[1] = L << (1u + b);
+    uint32_t s0 = 150u << 23, s1 = (150u - b) << 23;   // 2^23, 2^(23 - b)
+    uint32_t c0 = 0x80000000u | s0 | L, c1 = 0x80000000u | s1 | (L << b);
+    asm volatile("" : "+s"(s0), "+s"(s1));
+    asm volatile("" : "+v"(c0), "+v"(c1));
+    cd.scale[0] = __builtin_bit_cast(float, s0);
+    cd.scale[1] = __builtin_bit_cast(float, s1);
+    cd.minus_c[0] = __builtin_bit_cast(float, c0);
+    cd.minus_c[1] = __builtin_bit_cast(float, c1);
+    return cd;
+}
+__device__ __forceinline__ float centred_code(uint32_t y, const Centred& cd, int place) {
+    const float x = __builtin_bit_cast(float, (y & cd.field[place]) | 0x3F800000u);
+    return __builtin_fmaf(x, cd.scale[place], cd.minus_c[place]);
+}
+
 // One worker's 4 codes of one quad, de-quantized with step d and accumulated:
 // acc <- fma((float)(2c - L), d, acc), the ordered chain of the server's sum.
 template <bool STRADDLE>
-__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, uint32_t b, int negL,
-                                                float d, float4& acc) {
-    int k[4];
-    extract_quad<STRADDLE>(lo, sh, b, k);
-    acc.x = __builtin_fmaf((float)(2 * k[0] + negL), d, acc.x);
-    acc.y = __builtin_fmaf((float)(2 * k[1] + negL), d, acc.y);
-    acc.z = __builtin_fmaf((float)(2 * k[2] + negL), d, acc.z);
-    acc.w = __builtin_fmaf((float)(2 * k[3] + negL), d, acc.w);
+__device__ __forceinline__ void accumulate_quad(uint32_t lo, uint32_t sh, const Centred& cd, float d, float4& acc) {
+    // ya holds codes 0 and 1 of the quad at bits 1 and 1 + b, yb codes 2 and 3 at the same places.
+    uint32_t ya, yb;
+    if (STRADDLE) {
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, kDppWaveShl1, 0xF, 0xF, false);
+        const uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);   // as in extract_quad
+        ya = v << 1;
+        yb = v >> (2u * cd.b - 1u);
+    } else {
+        ya = __builtin_amdgcn_alignbit(lo, lo, (sh - 1u) & 31u);    // rotate: bit sh moves to bit 1
+        yb = __builtin_amdgcn_alignbit(ya, ya, 2u * cd.b);          // rotate again: at 8 bits code 3 wraps round
+    }
+    acc.x = __builtin_fmaf(centred_code(ya, cd, 0), d, acc.x);
+    acc.y = __builtin_fmaf(centred_code(ya, cd, 1), d, acc.y);
+    acc.z = __builtin_fmaf(centred_code(yb, cd, 0), d, acc.z);
+    acc.w = __builtin_fmaf(centred_code(yb, cd, 1), d, acc.w);
 }
 
 // One-bit codes: (2c - L) is +1 or -1, so the fma of the chain is an exactly rounded add or subtract
 // of d.  The code bit is shifted to the sign position and XOR-ed into d with one three-input bitwise
 // operation ((a & b) ^ c has the truth table 0x6A for a = 0xF0, b = 0xCC, c = 0xAA); what is
 // subtracted is -d for a set bit and +d for a clear one: three vector operations per element
-// instead of four, bit-identical results.
+// (the general form takes three and a half), bit-identical results.
 __device__ __forceinline__ float minus_signed_step(uint32_t word, uint32_t shl, float d) {
     const uint32_t t = word << shl;   // code bit at bit 31
     const int r = __builtin_amdgcn_bitop3_b32((int)t, (int)0x80000000u, __builtin_bit_cast(int, d), 0x6A);
@@ -133,7 +179,7 @@ __device__ __forceinline__ void accumulate_quad_onebit(uint32_t lo, uint32_t sh,
 
 // Eight-bit codes: a quad is the four bytes of one word, and a byte converts to fp32 in one
 // instruction (v_cvt_f32_ubyte0..3); 2c - 255 is then one exact fma, so the chain's fma sees the same
-// multiplier as in the general path: three vector operations per element instead of four.
+// multiplier as in the general path: three vector operations per element, no shifts per quad.
 __device__ __forceinline__ void accumulate_quad_bytes(uint32_t lo, float d, float4& acc) {
     const float k0 = (float)(lo & 0xFFu), k1 = (float)((lo >> 8) & 0xFFu);
     const float k2 = (float)((lo >> 16) & 0xFFu), k3 = (float)(lo >> 24);
@@ -145,13 +191,13 @@ __device__ __forceinline__ void accumulate_quad_bytes(uint32_t lo, float d, floa
 
 // Dispatch on the width class: WIDTH = 1 or 8 select the three-operation forms above, 0 the general one.
 template <bool STRADDLE, int WIDTH>
-__device__ __forceinline__ void accumulate_quad_w(uint32_t lo, uint32_t sh, uint32_t b, int negL, float d, float4& acc) {
+__device__ __forceinline__ void accumulate_quad_w(uint32_t lo, uint32_t sh, const Centred& cd, float d, float4& acc) {
     if (WIDTH == 1) {
         accumulate_quad_onebit(lo, sh, d, acc);
     } else if (WIDTH == 8) {
         accumulate_quad_bytes(lo, d, acc);
     } else {
-        accumulate_quad<STRADDLE>(lo, sh, b, negL, d, acc);
+        accumulate_quad<STRADDLE>(lo, sh, cd, d, acc);
     }
 }
 

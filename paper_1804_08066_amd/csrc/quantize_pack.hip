@@ -120,7 +120,7 @@ struct DecodeSource {
     }
     __device__ __forceinline__ void finish(float4 (&x)[R], uint32_t tile_count, bool full) {
         const uint32_t b = ra.q.bits;
-        const int negL = -(int)((1u << b) - 1u);
+        const decode::Centred cd = decode::centred(b);
         const bool straddle = (32u % b) != 0u;
         uint32_t bl[R];
         bucket_of_quads<R>(ra.q.bucket, ra.q.bucket_shift, bl);
@@ -138,9 +138,9 @@ struct DecodeSource {
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
                         if (straddle) {
-                            decode::accumulate_quad<true>(c.lo[t][j], cw.sh[j], b, negL, dw[bl[j]], x[j]);
+                            decode::accumulate_quad<true>(c.lo[t][j], cw.sh[j], cd, dw[bl[j]], x[j]);
                         } else {
-                            decode::accumulate_quad<false>(c.lo[t][j], cw.sh[j], b, negL, dw[bl[j]], x[j]);
+                            decode::accumulate_quad<false>(c.lo[t][j], cw.sh[j], cd, dw[bl[j]], x[j]);
                         }
                     }
                 }

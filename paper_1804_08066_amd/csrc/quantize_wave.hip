@@ -318,7 +318,8 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
     const uint64_t chunk = block * NW + wave;
     const uint64_t cb = chunk * CH;                 // first element of the chunk
     const bool active = cb < a.n;                   // waves past the end only keep the barrier company
@@ -351,16 +352,19 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
     }
 }
 
-template <int R, int WPB, int NW>
-__global__ __launch_bounds__(64 * NW) void quantize_wave_kernel(const QuantizeArgs a) {
+// OCC: cap on the waves per SIMD (8 = none).  The 2048-element shape fits six waves per SIMD; that is
+// faster than five up to 3 bits and slower from 4 bits on, where a wave writes more (measured at 100 M
+// elements, buckets 128 and 1024: -2..-4 us and +1..+3 us), so the launch picks the cap by the width.
+template <int R, int WPB, int NW, int OCC>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_wave_kernel(const QuantizeArgs a) {
     __shared__ WaveShared<R, NW> sm;
     quantize_wave_block<R, WPB, NW>(a, blockIdx.x, sm);
 }
 
 // Several layer tensors of one worker in one launch: workgroup -> (tensor, block of the tensor) through
 // the prefix table of block counts.
-template <int R, int WPB, int NW>
-__global__ __launch_bounds__(64 * NW) void quantize_tensors_wave_kernel(const BatchQuantizeArgs ba) {
+template <int R, int WPB, int NW, int OCC>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_tensors_wave_kernel(const BatchQuantizeArgs ba) {
     __shared__ WaveShared<R, NW> sm;
     uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
     while (hi - lo > 1u) {
@@ -391,7 +395,8 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     const QuantizeArgs& a = ra.q;
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
     const uint64_t chunk = (uint64_t)blockIdx.x * NW + wave;
     const uint64_t cb = chunk * CH;
     const bool active = cb < a.n;
@@ -411,7 +416,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     for (int j = 0; j < R; ++j) x[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (active) {
         const uint32_t b = a.bits;
-        const int negL = -(int)((1u << b) - 1u);
+        const decode::Centred cd = decode::centred(b);
         const float Lf = (float)((1u << b) - 1u);
         const decode::CodeWindows<R> cw = decode::code_windows<R, 64>(a.n, cb, b, lane);
         decode::CodeRegs<R, kChunk> c;
@@ -435,7 +440,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
                         const float dw = decode::readlane_f32(d[j], w0 + t);
-                        decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], b, negL, dw, x[j]);
+                        decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], cd, dw, x[j]);
                     }
                 }
             }
@@ -491,24 +496,27 @@ template <class F>
 auto with_wave_shape(uint32_t bucket, uint32_t bits, F f) {
     using std::integral_constant;
     // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
+    using free = integral_constant<int, 8>;   // no cap on the waves per SIMD
     if (bits == 8u && (bucket == 512u || bucket == 1024u)) {
-        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{});
+        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{});
     }
     switch (bucket) {
-        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{});
-        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
-        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
-        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
-        default: return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{});   // 32 .. 1024
+        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{});
+        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{});
+        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{});
+        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{});
+        default:   // 32 .. 1024
+            if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{});
+            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{});
     }
 }
 
-template <int R, int WPB, int NW>
+template <int R, int WPB, int NW, int OCC>
 hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
     const uint64_t groups = (a.n + per_group - 1) / per_group;
     if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
+    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -520,20 +528,20 @@ bool quantize_wave_supported(const QuantizeArgs& a) { return a.bucket_shift >= 5
 
 // elements per workgroup of the wave-local kernel at this bucket size
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits) {
-    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
+    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
 }
 
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
-    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw) {
-        constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value;
-        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW>), dim3(blocks), dim3(64 * NW), 0, stream, a);
+    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ) {
+        constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value, OCC = decltype(occ)::value;
+        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC>), dim3(blocks), dim3(64 * NW), 0, stream, a);
         return hipGetLastError();
     });
 }
 
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
-    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw) {
-        return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value>(a, stream);
+    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ) {
+        return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value, decltype(occ)::value>(a, stream);
     });
 }
 
