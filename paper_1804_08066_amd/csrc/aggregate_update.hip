@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_rows_kernel(const A
                 for (int j = 0; j < R; ++j) {
                     float dw = readlane_f32(d[j][0], w0 + t);
                     if (NBR > 1) dw = second[j] ? readlane_f32(d[j][NBR - 1], w0 + t) : dw;
-                    decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], cd, dw, acc[j]);
+                    decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh, cd, dw, acc[j]);
                 }
             }
         }
@@ -241,7 +241,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
                 const float* __restrict__ dw = s_step + (w0 + t) * nbt;
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh[j], cd, dw[bl[j]], acc[j]);
+                    accumulate_quad<STRADDLE>(c.lo[t][j], cw.sh, cd, dw[bl[j]], acc[j]);
                 }
             }
         }

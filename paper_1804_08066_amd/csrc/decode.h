@@ -15,12 +15,14 @@ namespace decode {
 
 constexpr int kDppWaveShl1 = 0x130;   // DPP wave_shl:1: lane i reads lane i + 1
 
-// Where the codes of the lane's R quads sit in every worker's stream (tile-local word indices,
-// clamped to the last word of the stream so that quads past the end still read valid memory).
+// Where the codes of the lane's R quads sit in every worker's stream.  A row of the tile is a whole
+// number of words (ROW is a multiple of 8 quads), so the bit offset inside the first word is the same
+// for every row; the byte offsets are clamped to the last word of the stream so that quads past the
+// end still read valid memory (what they decode is never used).
 template <int R>
 struct CodeWindows {
     uint32_t byte[R];    // byte offset of the quad's first word from the tile's first word (< 2^32)
-    uint32_t sh[R];      // bit offset of the first code inside that word
+    uint32_t sh;         // bit offset of the quad's first code inside that word
     uint64_t tile_word;  // first word of the tile in the stream
 };
 
@@ -28,22 +30,20 @@ struct CodeWindows {
 // Row j of the lane is quad j*ROW + idx of the tile that starts at element `tile_base`.
 template <int R, int ROW>
 __device__ __forceinline__ CodeWindows<R> code_windows(uint64_t n, uint64_t tile_base, uint32_t b, uint32_t idx) {
+    static_assert(ROW % 8 == 0, "a row is a whole number of words at every width");
     CodeWindows<R> cw;
     cw.tile_word = (tile_base >> 5) * b;   // tile_base is a multiple of 32
     const uint64_t stream_words = (n >> 5) * b + ((((n & 31u) * b) + 31u) >> 5);
     const uint64_t room = stream_words - cw.tile_word;   // >= 1 whenever tile_base < n
     const uint32_t last_word = room - 1u > 0x3FFFFFFFull ? 0x3FFFFFFFu : (uint32_t)(room - 1u);
+    const uint32_t bit = 4u * b * idx;
+    const uint32_t word = bit >> 5;
+    const uint32_t row_words = (ROW / 8) * b;
+    cw.sh = bit & 31u;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const uint32_t ql = j * ROW + idx;
-        const uint32_t bit = 4u * b * ql;
-        uint32_t word = bit >> 5, sh = bit & 31u;
-        if (word > last_word) {   // quad entirely past the end
-            word = last_word;
-            sh = 0u;
-        }
-        cw.byte[j] = word * 4u;
-        cw.sh[j] = sh;
+        const uint32_t wj = word + j * row_words;
+        cw.byte[j] = (wj < last_word ? wj : last_word) * 4u;
     }
     return cw;
 }

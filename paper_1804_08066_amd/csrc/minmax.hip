@@ -276,7 +276,7 @@ __global__ __launch_bounds__(NT) void requantize_minmax_kernel(const RequantArgs
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     const float2 sl = tw[bl[j]];
-                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh[j], b, sl.x, sl.y, x[j]);
+                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh, b, sl.x, sl.y, x[j]);
                 }
             }
         }
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     const float2 sl = tw[bl[j]];
-                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh[j], b, sl.x, sl.y, acc[j]);
+                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh, b, sl.x, sl.y, acc[j]);
                 }
             }
         }

@@ -138,9 +138,9 @@ struct DecodeSource {
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
                         if (straddle) {
-                            decode::accumulate_quad<true>(c.lo[t][j], cw.sh[j], cd, dw[bl[j]], x[j]);
+                            decode::accumulate_quad<true>(c.lo[t][j], cw.sh, cd, dw[bl[j]], x[j]);
                         } else {
-                            decode::accumulate_quad<false>(c.lo[t][j], cw.sh[j], cd, dw[bl[j]], x[j]);
+                            decode::accumulate_quad<false>(c.lo[t][j], cw.sh, cd, dw[bl[j]], x[j]);
                         }
                     }
                 }

@@ -386,7 +386,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
 // exactly as a gradient would be; the stored range is divided by W.  Buckets of 256 elements and more:
 // a wave's 256-element row lies in one bucket, so lane w divides worker w's scale of each row once
 // and the worker loop broadcasts it with v_readlane (no LDS table, no barrier).
-template <int R, int WPB, int NW, bool STRADDLE, bool ONCE, int WIDTH>
+// ONE (with WPB == 1): the bucket is exactly the wave's chunk, so every row shares one step per worker.
+template <int R, int WPB, int NW, bool ONE, bool STRADDLE, bool ONCE, int WIDTH>
 __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantArgs ra) {
     constexpr uint32_t CH = 256u * R;
     constexpr int kChunk = 32 / R;   // workers whose code loads are in flight together
@@ -404,12 +405,12 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     const bool full = count == CH;
 
     const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 8 here
-    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);
-    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (1u << (shift - 8u));    // rows per bucket
-    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);
+    const uint32_t nbc = (WPB > 1 || ONE) ? 1u : (CH >> shift);
+    const uint32_t rpb = (WPB > 1 || ONE) ? (uint32_t)R : (1u << (shift - 8u));    // rows per bucket
+    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (ONE ? chunk : (cb >> shift));
     uint32_t slot[R];
 #pragma unroll
-    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((256u * j) >> shift);   // uniform: a row lies in one bucket
+    for (int j = 0; j < R; ++j) slot[j] = (WPB > 1 || ONE) ? 0u : ((256u * j) >> shift);   // uniform: a row lies in one bucket
 
     float4 x[R];
 #pragma unroll
@@ -440,7 +441,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
                         const float dw = decode::readlane_f32(d[j], w0 + t);
-                        decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh[j], cd, dw, x[j]);
+                        decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh, cd, dw, x[j]);
                     }
                 }
             }
@@ -467,7 +468,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     }
 }
 
-template <int R, int WPB, int NW>
+template <int R, int WPB, int NW, bool ONE = false>
 hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
     const uint64_t groups = (ra.q.n + per_group - 1) / per_group;
@@ -476,15 +477,15 @@ hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     const bool straddle = (32u % ra.q.bits) != 0u;
     const bool once = decode::codes_read_once(ra.q.bits);
     if (ra.q.bits == 1u) {          // three-operation decodes at 1 and 8 bits
-        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, false, 1>), grid, block, 0, stream, ra);
+        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, false, 1>), grid, block, 0, stream, ra);
     } else if (ra.q.bits == 8u) {
-        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, true, 8>), grid, block, 0, stream, ra);
+        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, true, 8>), grid, block, 0, stream, ra);
     } else if (straddle) {
-        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, true, 0>), grid, block, 0, stream, ra);
-        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, true, false, 0>), grid, block, 0, stream, ra);
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, true, true, 0>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, true, false, 0>), grid, block, 0, stream, ra);
     } else {
-        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, true, 0>), grid, block, 0, stream, ra);
-        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, false, false, 0>), grid, block, 0, stream, ra);
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, true, 0>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, false, 0>), grid, block, 0, stream, ra);
     }
     return hipGetLastError();
 }
@@ -556,7 +557,8 @@ hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
         case 8192: return launch_requant_wave<8, 4, 4>(ra, stream);
         case 16384: return ra.q.bits == 8u ? launch_requant_wave<8, 8, 8>(ra, stream)
                                            : launch_requant_wave<4, 16, 16>(ra, stream);
-        default: return launch_requant_wave<4, 1, 4>(ra, stream);   // 256 .. 1024
+        case 1024: return launch_requant_wave<4, 1, 4, true>(ra, stream);   // the bucket is the wave's chunk
+        default: return launch_requant_wave<4, 1, 4>(ra, stream);   // 256, 512
     }
 }
 
