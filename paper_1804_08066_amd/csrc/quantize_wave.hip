@@ -554,9 +554,8 @@ hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
     switch (ra.q.bucket) {   // measured choices (100 M elements, W = 8)
         case 2048: return launch_requant_wave<4, 2, 4>(ra, stream);
         case 4096: return launch_requant_wave<4, 4, 4>(ra, stream);
-        case 8192: return launch_requant_wave<8, 4, 4>(ra, stream);
-        case 16384: return ra.q.bits == 8u ? launch_requant_wave<8, 8, 8>(ra, stream)
-                                           : launch_requant_wave<4, 16, 16>(ra, stream);
+        case 8192: return launch_requant_wave<4, 8, 8>(ra, stream);
+        case 16384: return launch_requant_wave<8, 8, 8>(ra, stream);   // workgroups of 16 waves are slower
         case 1024: return launch_requant_wave<4, 1, 4, true>(ra, stream);   // the bucket is the wave's chunk
         default: return launch_requant_wave<4, 1, 4>(ra, stream);   // 256, 512
     }
