@@ -24,7 +24,11 @@ using namespace encode;
 using tile_io::kThreads;
 
 constexpr int kChunk = 8;   // workers whose code loads are in flight together
-constexpr uint32_t kSumBlocks = 2048;   // workgroups of the whole-tensor reductions (8 per compute unit)
+// The whole-tensor reductions end with one atomic per workgroup on one address; those serialize at
+// about 5 ns each and every workgroup arrives at the end together, so the workgroups are few and large:
+// 512 of 512 lanes (8 waves per SIMD) read as fast as 2048 of 256 and end 7 us earlier at 100 M elements.
+constexpr int kSumThreads = 512;
+constexpr uint32_t kSumBlocks = 512;
 
 // NT lanes own a tile of at most 4*NT*R elements
 template <int R, int NT>
@@ -369,38 +373,34 @@ __global__ void range_finish_kernel(uint32_t* keys) {
     keys[1] = __builtin_bit_cast(uint32_t, mx);
 }
 
-__global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __restrict__ g, const uint64_t n,
-                                                                const uint32_t head, uint32_t* keys) {
-    __shared__ uint32_t s_lo[kThreads / 64], s_hi[kThreads / 64];
+__global__ __launch_bounds__(kSumThreads) void tensor_range_kernel(const float* __restrict__ g, const uint64_t n,
+                                                                   uint32_t* keys) {
+    __shared__ uint32_t s_lo[kSumThreads / 64], s_hi[kSumThreads / 64];
     const uint32_t tid = threadIdx.x;
-    const uint64_t gtid = (uint64_t)blockIdx.x * kThreads + tid;
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    const uint64_t gtid = (uint64_t)blockIdx.x * kSumThreads + tid;
+    const uint64_t stride = (uint64_t)gridDim.x * kSumThreads;
     float lo = __builtin_inff(), hi = -__builtin_inff();
-    if (gtid < head) {   // `head` leading elements bring the rest to a 16-byte boundary
-        lo = hi = g[gtid];
-    }
-    const v4f* __restrict__ g4 = reinterpret_cast<const v4f*>(g + head);
-    const uint64_t nq = (n - head) >> 2;
-    const uint64_t pieces = nq >> 10;   // contiguous 16 KB pieces, four float4 per lane in flight
+    const v4f_a4* __restrict__ g4 = reinterpret_cast<const v4f_a4*>(g);   // 128-bit loads need dword alignment only
+    const uint64_t nq = n >> 2;
+    const uint64_t pieces = nq / (4u * kSumThreads);   // contiguous 32 KB pieces, four float4 per lane in flight
     for (uint64_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
-        const v4f* __restrict__ src = g4 + (pc << 10) + tid;
+        const v4f_a4* __restrict__ src = g4 + pc * (4u * kSumThreads) + tid;
         v4f t[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(src + u * kThreads);
+        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(src + u * kSumThreads);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             lo = fminf(lo, fminf(fminf(t[u].x, t[u].y), fminf(t[u].z, t[u].w)));
             hi = fmaxf(hi, fmaxf(fmaxf(t[u].x, t[u].y), fmaxf(t[u].z, t[u].w)));
         }
     }
-    for (uint64_t q = (pieces << 10) + gtid; q < nq; q += stride) {
+    for (uint64_t q = pieces * (4u * kSumThreads) + gtid; q < nq; q += stride) {   // less than one piece is left
         const v4f t = g4[q];
         lo = fminf(lo, fminf(fminf(t.x, t.y), fminf(t.z, t.w)));
         hi = fmaxf(hi, fmaxf(fmaxf(t.x, t.y), fmaxf(t.z, t.w)));
     }
-    const uint64_t tail0 = head + (nq << 2);
-    if (gtid < n - tail0) {
-        const float v = g[tail0 + gtid];
+    if (gtid < (n & 3u)) {
+        const float v = g[(nq << 2) + gtid];
         lo = fminf(lo, v);
         hi = fmaxf(hi, v);
     }
@@ -413,13 +413,12 @@ __global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __r
     __syncthreads();
     if (tid == 0u) {
 #pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) {
+        for (int w = 1; w < kSumThreads / 64; ++w) {
             kl = min(kl, s_lo[w]);
             kh = max(kh, s_hi[w]);
         }
-        // Same-address atomics serialize in L2, and after the first workgroups almost none improves the
-        // bounds: look first.  The keys only ever move one way, so a stale read can cause a needless
-        // atomic but never a wrong skip.
+        // Same-address atomics serialize in L2: look first.  The keys only ever move one way, so a
+        // stale read can cause a needless atomic but never a wrong skip.
         if (kl < __atomic_load_n(&keys[0], __ATOMIC_RELAXED)) atomicMin(&keys[0], kl);
         if (kh > __atomic_load_n(&keys[1], __ATOMIC_RELAXED)) atomicMax(&keys[1], kh);
     }
@@ -432,41 +431,35 @@ __global__ __launch_bounds__(kThreads) void tensor_range_kernel(const float* __r
 
 __global__ void clear_f64_kernel(double* out) { *out = 0.0; }
 
-__global__ __launch_bounds__(kThreads) void sum_squares_kernel(const float* __restrict__ g, const uint64_t n,
-                                                               const uint32_t head, double* out) {
-    __shared__ double s_part[kThreads / 64];
+__global__ __launch_bounds__(kSumThreads) void sum_squares_kernel(const float* __restrict__ g, const uint64_t n,
+                                                                  double* out) {
+    __shared__ double s_part[kSumThreads / 64];
     const uint32_t tid = threadIdx.x;
-    const uint64_t gtid = (uint64_t)blockIdx.x * kThreads + tid;
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    const uint64_t gtid = (uint64_t)blockIdx.x * kSumThreads + tid;
+    const uint64_t stride = (uint64_t)gridDim.x * kSumThreads;
     double acc = 0.0;
-    // `head` leading elements bring the rest to a 16-byte boundary
-    if (gtid < head) {
-        const double v = (double)g[gtid];
-        acc += v * v;
-    }
-    const v4f* __restrict__ g4 = reinterpret_cast<const v4f*>(g + head);
-    const uint64_t nq = (n - head) >> 2;
-    // a workgroup reads 16 KB contiguous pieces (four float4 per lane in flight), pieces gridDim.x apart
-    const uint64_t pieces = nq >> 10;
+    const v4f_a4* __restrict__ g4 = reinterpret_cast<const v4f_a4*>(g);   // 128-bit loads need dword alignment only
+    const uint64_t nq = n >> 2;
+    // a workgroup reads 32 KB contiguous pieces (four float4 per lane in flight), pieces gridDim.x apart
+    const uint64_t pieces = nq / (4u * kSumThreads);
     for (uint64_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
-        const v4f* __restrict__ src = g4 + (pc << 10) + tid;
+        const v4f_a4* __restrict__ src = g4 + pc * (4u * kSumThreads) + tid;
         v4f t[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(src + u * kThreads);
+        for (int u = 0; u < 4; ++u) t[u] = __builtin_nontemporal_load(src + u * kSumThreads);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const double a0 = (double)t[u].x, a1 = (double)t[u].y, a2 = (double)t[u].z, a3 = (double)t[u].w;
             acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
         }
     }
-    for (uint64_t q = (pieces << 10) + gtid; q < nq; q += stride) {   // fewer than 1024 quads are left
+    for (uint64_t q = pieces * (4u * kSumThreads) + gtid; q < nq; q += stride) {   // less than one piece is left
         const v4f t = __builtin_nontemporal_load(g4 + q);
         const double a0 = (double)t.x, a1 = (double)t.y, a2 = (double)t.z, a3 = (double)t.w;
         acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
     }
-    const uint64_t tail0 = head + (nq << 2);
-    if (gtid < n - tail0) {
-        const double v = (double)g[tail0 + gtid];
+    if (gtid < (n & 3u)) {
+        const double v = (double)g[(nq << 2) + gtid];
         acc += v * v;
     }
 #pragma unroll
@@ -476,7 +469,7 @@ __global__ __launch_bounds__(kThreads) void sum_squares_kernel(const float* __re
     if (tid == 0u) {
         double t = 0.0;
 #pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) t += s_part[w];
+        for (int w = 0; w < kSumThreads / 64; ++w) t += s_part[w];
         atomicAdd(out, t);
     }
 }
@@ -568,30 +561,21 @@ hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, 
     if (n == 0) return hipSuccess;
     uint32_t* keys = reinterpret_cast<uint32_t*>(range_out);
     hipLaunchKernelGGL(range_init_kernel, dim3(1), dim3(1), 0, stream, keys);
-    const uint64_t mis = (reinterpret_cast<uintptr_t>(grad) & 15u) >> 2;
-    uint32_t head = mis ? (uint32_t)(4u - mis) : 0u;
-    if (head > n) head = (uint32_t)n;
-    const uint64_t quads = (n - head) >> 2;
-    uint64_t blocks = (quads + kThreads - 1) / kThreads;
+    uint64_t blocks = ((n >> 2) + kSumThreads - 1) / kSumThreads;
     if (blocks < 1) blocks = 1;
     if (blocks > kSumBlocks) blocks = kSumBlocks;
-    hipLaunchKernelGGL(tensor_range_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, grad, n, head, keys);
+    hipLaunchKernelGGL(tensor_range_kernel, dim3((uint32_t)blocks), dim3(kSumThreads), 0, stream, grad, n, keys);
     hipLaunchKernelGGL(range_finish_kernel, dim3(1), dim3(1), 0, stream, keys);
     return hipGetLastError();
 }
-
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream) {
     hipLaunchKernelGGL(clear_f64_kernel, dim3(1), dim3(1), 0, stream, out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n == 0) return e;
-    const uint64_t mis = (reinterpret_cast<uintptr_t>(grad) & 15u) >> 2;     // floats past a 16-byte boundary
-    uint32_t head = mis ? (uint32_t)(4u - mis) : 0u;
-    if (head > n) head = (uint32_t)n;
-    const uint64_t quads = (n - head) >> 2;
-    uint64_t blocks = (quads + kThreads - 1) / kThreads;
+    uint64_t blocks = ((n >> 2) + kSumThreads - 1) / kSumThreads;
     if (blocks < 1) blocks = 1;
     if (blocks > kSumBlocks) blocks = kSumBlocks;
-    hipLaunchKernelGGL(sum_squares_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, grad, n, head, out);
+    hipLaunchKernelGGL(sum_squares_kernel, dim3((uint32_t)blocks), dim3(kSumThreads), 0, stream, grad, n, out);
     return hipGetLastError();
 }
 
