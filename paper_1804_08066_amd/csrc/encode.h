@@ -91,6 +91,18 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
     return (uint32_t)__builtin_amdgcn_bitop3_b32((int)a, (int)b, (int)c, 0x96);
 }
 
+// Lanes of one wave exchange data through LDS without a workgroup barrier.  The hardware executes a
+// wave's LDS instructions in program order, so what one lane wrote is there for the others as soon as
+// the instructions are in that order; this fence keeps the COMPILER from moving memory accesses
+// across the exchange point (without it a lane's read may legally be hoisted above another lane's
+// write: to the compiler they are unordered accesses of different threads).  Wavefront scope: no
+// cache maintenance and no instruction beyond the waits the accesses need anyway.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Philox4x32-10 (Salmon et al., SC'11).  Ten rounds of two 32x32->64 multiplies; the key is
 // bumped by the Weyl constants between rounds.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,

@@ -125,11 +125,23 @@ __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lan
                                               const uint32_t (&slot)[R], uint32_t seg_lanes, uint32_t rpb,
                                               WaveShared<R, NW>& sm, bool l2 = false);
 
-template <int R, int WPB, int NW, bool FULL>
-__device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const float* __restrict__ g, uint32_t count,
-                                                uint32_t lane, uint32_t wave, const uint32_t (&slot)[R],
-                                                uint32_t seg_lanes, uint32_t rpb, float4 (&x)[R], WaveShared<R, NW>& sm) {
-    // one HBM pass
+// One Philox call covers 8 consecutive elements = the quads of an even/odd lane pair.  For the row
+// pair (jp, jp + 1) the even lane draws for row jp and the odd lane for row jp + 1, so no lane makes a
+// call whose output is thrown away.  The numbers depend on the position only, not on the data.
+__device__ __forceinline__ void draw_pair(const QuantizeArgs& a, uint64_t cb, uint32_t lane, int jp, uint32_t (&o)[4]) {
+    const uint64_t group0 = (a.elem_base + cb) >> 3;           // both multiples of 8
+    const uint32_t my_row = jp + (lane & 1u);
+    const uint64_t grp = group0 + (uint64_t)((my_row * 64u + lane) >> 1);
+    philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
+}
+template <int R>
+struct Draws {
+    uint32_t o[R / 2][4];
+};
+
+// one HBM pass: the chunk's values into registers
+template <int R, bool FULL>
+__device__ __forceinline__ void load_chunk(const float* __restrict__ g, uint32_t count, uint32_t lane, float4 (&x)[R]) {
     if (FULL) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
@@ -146,10 +158,6 @@ __device__ __forceinline__ void load_and_reduce(const QuantizeArgs& a, const flo
             x[j].w = (el + 3u < count) ? g[el + 3] : 0.0f;
         }
     }
-    // clear the packing area of this wave while the loads are in flight (LDS is in order per wave)
-    clear_words<R, NW>(lane, wave, sm);
-    if (a.scales_in != nullptr) return;
-    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm, a.scale_mode == MQG_SCALE_L2);
 }
 
 // a1: bucket range of the values in registers
@@ -210,13 +218,14 @@ template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
                                                   uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
                                                   uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm,
-                                                  float range_div = 1.0f) {
+                                                  float range_div = 1.0f, const Draws<R>* drawn = nullptr) {
     // range_div: the stored scale is range / range_div (1 for a plain quantize, W for the server's mean)
     const uint32_t b = a.bits;
     const uint32_t shift = (uint32_t)a.bucket_shift;
     const float Lf = (float)((1u << b) - 1u);
     const float halfL = 0.5f * Lf;
 
+    wave_lds_fence();   // the ranges other lanes of this wave published are read below
     if (WPB > 1 && a.scales_in == nullptr && lane == 0u) {
         const uint32_t w0 = wave & ~(uint32_t)(WPB - 1);
         float r = sm.wave_max[w0];
@@ -249,9 +258,9 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
         }
         sm.ainv[wave][lane] = (s > 0.0f) ? halfL / s : 0.0f;   // IEEE-correct fp32 division, once per bucket
     }
+    wave_lds_fence();   // every lane reads its buckets' factors; the packing area was cleared by other lanes
 
     const uint32_t odd = lane & 1u;
-    const uint64_t group0 = (a.elem_base + cb) >> 3;           // both multiples of 8
     const uint32_t cell_bit = 4u * b * (lane & 7u);            // this lane's bit offset in its 32-element cell
     const uint32_t sh = cell_bit & 31u;
     const uint32_t word_in_cell = cell_bit >> 5;
@@ -259,15 +268,17 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
 
 #pragma unroll
     for (int jp = 0; jp < R; jp += 2) {
-        // One Philox call covers 8 consecutive elements = the quads of an even/odd lane pair.  The
-        // even lane draws for row jp, the odd lane for row jp + 1; each then takes the half it
-        // needs from its partner.  The swaps run with every lane active (a lane swap under a
-        // divergent branch would read switched-off partners); the selects that follow keep the
-        // half each lane needs.
-        const uint32_t my_row = jp + odd;
-        const uint64_t grp = group0 + (uint64_t)((my_row * 64u + lane) >> 1);
+        // The lane pair's call for rows jp and jp + 1 (made here unless it was made earlier); each lane
+        // then takes the half it needs from its partner.  The swaps run with every lane active (a lane
+        // swap under a divergent branch would read switched-off partners); the selects that follow
+        // keep the half each lane needs.
         uint32_t o[4];
-        philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
+        if (drawn != nullptr) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = drawn->o[jp / 2][i];
+        } else {
+            draw_pair(a, cb, lane, jp, o);
+        }
         const uint32_t p0 = swap_adjacent(o[0]), p1 = swap_adjacent(o[1]);
         const uint32_t p2 = swap_adjacent(o[2]), p3 = swap_adjacent(o[3]);
         const uint32_t rw[2][2] = {{odd ? p2 : o[0], odd ? p3 : o[1]},    // row jp: the even lane's call
@@ -298,6 +309,7 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
     }
 
     // store the chunk's words
+    wave_lds_fence();   // a word holds bits placed by several lanes
     uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
     if (FULL) {
         for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
@@ -312,7 +324,9 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
 
 // R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; otherwise bucket = WPB*CH);
 // NW: waves per workgroup, a multiple of WPB
-template <int R, int WPB, int NW>
+// HOIST: the Philox calls of the chunk are made before the range reduction and its barrier (they depend
+// on the position only) and kept in 2*R registers until the rounding.
+template <int R, int WPB, int NW, bool HOIST>
 __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const uint64_t block, WaveShared<R, NW>& sm) {
     constexpr uint32_t CH = 256u * R;
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
@@ -339,31 +353,43 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
 
     float4 x[R];
     if (full) {
-        load_and_reduce<R, WPB, NW, true>(a, a.grad + cb, count, lane, wave, slot, seg_lanes, rpb, x, sm);
+        load_chunk<R, true>(a.grad + cb, count, lane, x);
     } else {
-        load_and_reduce<R, WPB, NW, false>(a, a.grad + cb, count, lane, wave, slot, seg_lanes, rpb, x, sm);
+        load_chunk<R, false>(a.grad + cb, count, lane, x);
+    }
+    // while the loads are in flight: clear the wave's packing area; when asked to, draw the chunk's
+    // random numbers ahead of the barrier
+    clear_words<R, NW>(lane, wave, sm);
+    Draws<R> draws;
+    if (HOIST) {
+#pragma unroll
+        for (int jp = 0; jp < R; jp += 2) draw_pair(a, cb, lane, jp, draws.o[jp / 2]);
+    }
+    if (a.scales_in == nullptr) {
+        reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm, a.scale_mode == MQG_SCALE_L2);
     }
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
     if (!active) return;
+    const Draws<R>* drawn = HOIST ? &draws : nullptr;
     if (full) {
-        quantize_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm);
+        quantize_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
     } else {
-        quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm);
+        quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
     }
 }
 
 // OCC: cap on the waves per SIMD (8 = none).  The 2048-element shape fits six waves per SIMD; that is
 // faster than five up to 3 bits and slower from 4 bits on, where a wave writes more (measured at 100 M
 // elements, buckets 128 and 1024: -2..-4 us and +1..+3 us), so the launch picks the cap by the width.
-template <int R, int WPB, int NW, int OCC>
+template <int R, int WPB, int NW, int OCC, bool HOIST>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_wave_kernel(const QuantizeArgs a) {
     __shared__ WaveShared<R, NW> sm;
-    quantize_wave_block<R, WPB, NW>(a, blockIdx.x, sm);
+    quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x, sm);
 }
 
 // Several layer tensors of one worker in one launch: workgroup -> (tensor, block of the tensor) through
 // the prefix table of block counts.
-template <int R, int WPB, int NW, int OCC>
+template <int R, int WPB, int NW, int OCC, bool HOIST>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_tensors_wave_kernel(const BatchQuantizeArgs ba) {
     __shared__ WaveShared<R, NW> sm;
     uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
@@ -377,7 +403,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
     a.elem_base = ba.t[lo].elem_base;
     a.packed = ba.t[lo].packed;
     a.scales = ba.t[lo].scales;
-    quantize_wave_block<R, WPB, NW>(a, blockIdx.x - ba.tile_start[lo], sm);
+    quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x - ba.tile_start[lo], sm);
 }
 
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
@@ -498,26 +524,31 @@ auto with_wave_shape(uint32_t bucket, uint32_t bits, F f) {
     using std::integral_constant;
     // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
     using free = integral_constant<int, 8>;   // no cap on the waves per SIMD
+    using early = std::true_type;              // random numbers drawn before the range reduction's barrier
+    using late = std::false_type;
     if (bits == 8u && (bucket == 512u || bucket == 1024u)) {
-        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{});
+        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{});
     }
+    // Where a barrier lines eight waves of a workgroup up (buckets 8192 and 16384), drawing before it
+    // fills the time the waves would otherwise spend waiting for each other: 1-4 us faster at every
+    // width; with four waves per workgroup (2048, 4096) it makes no difference (measured, 100 M elements).
     switch (bucket) {
-        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{});
-        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{});
-        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{});
-        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{});
+        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{}, late{});
+        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{}, late{});
+        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
+        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
         default:   // 32 .. 1024
-            if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{});
-            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{});
+            if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{});
+            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{}, late{});
     }
 }
 
-template <int R, int WPB, int NW, int OCC>
+template <int R, int WPB, int NW, int OCC, bool HOIST>
 hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
     const uint64_t groups = (a.n + per_group - 1) / per_group;
     if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
+    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC, HOIST>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -529,20 +560,22 @@ bool quantize_wave_supported(const QuantizeArgs& a) { return a.bucket_shift >= 5
 
 // elements per workgroup of the wave-local kernel at this bucket size
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits) {
-    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
+    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
 }
 
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
-    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ) {
+    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist) {
         constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value, OCC = decltype(occ)::value;
-        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC>), dim3(blocks), dim3(64 * NW), 0, stream, a);
+        constexpr bool HOIST = decltype(hoist)::value;
+        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC, HOIST>), dim3(blocks), dim3(64 * NW), 0, stream, a);
         return hipGetLastError();
     });
 }
 
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
-    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ) {
-        return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value, decltype(occ)::value>(a, stream);
+    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist) {
+        return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value, decltype(occ)::value,
+                           decltype(hoist)::value>(a, stream);
     });
 }
 
