@@ -13,8 +13,9 @@
 // it in registers (R float4 per lane: row j of the chunk is the 256 elements the wave loads with
 // one float4 per lane), so every gradient byte is read from HBM exactly once.  Buckets of up to CH
 // elements live entirely inside one wave: range reduction, the one IEEE division per bucket, the
-// rounding and the packing need no workgroup barrier.  Larger buckets (WPB = 2 .. 16 waves per
-// bucket) exchange one value per wave through LDS behind a single barrier.
+// rounding and the packing need no workgroup barrier (the lanes of a wave exchange through LDS behind
+// wavefront-scope fences).  Larger buckets (WPB = 2 .. 8 waves per bucket) exchange one value per wave
+// through LDS behind a single barrier.
 //
 // The kernel sits close to both of its limits (the vector ALU is busy for about three quarters of
 // its HBM-bound duration), so work is moved off the vector ALU where possible: cross-lane exchange through LDS-pipe swizzles, per-bucket
