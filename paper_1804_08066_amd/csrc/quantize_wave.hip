@@ -413,8 +413,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
 // exactly as a gradient would be; the stored range is divided by W.  Buckets of 256 elements and more:
 // a wave's 256-element row lies in one bucket, so lane w divides worker w's scale of each row once
 // and the worker loop broadcasts it with v_readlane (no LDS table, no barrier).
-// ONE (with WPB == 1): the bucket is exactly the wave's chunk, so every row shares one step per worker.
-template <int R, int WPB, int NW, bool ONE, bool STRADDLE, bool ONCE, int WIDTH>
+// RPB: rows of the chunk per bucket (bucket = 256 * RPB when WPB == 1; R when the chunk is part of one
+// bucket), a compile-time number so that rows of one bucket share one division and one v_readlane per worker.
+template <int R, int WPB, int NW, int RPB, bool STRADDLE, bool ONCE, int WIDTH>
 __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantArgs ra) {
     constexpr uint32_t CH = 256u * R;
     constexpr int kChunk = 32 / R;   // workers whose code loads are in flight together
@@ -432,12 +433,13 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     const bool full = count == CH;
 
     const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 8 here
-    const uint32_t nbc = (WPB > 1 || ONE) ? 1u : (CH >> shift);
-    const uint32_t rpb = (WPB > 1 || ONE) ? (uint32_t)R : (1u << (shift - 8u));    // rows per bucket
-    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (ONE ? chunk : (cb >> shift));
+    static_assert(R % RPB == 0 && (WPB == 1 || RPB == R), "whole buckets per chunk, or one bucket over several chunks");
+    constexpr uint32_t nbc = R / RPB;                                      // buckets per chunk
+    constexpr uint32_t rpb = RPB;                                          // rows per bucket
+    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : chunk * nbc;       // global index of the chunk's first bucket
     uint32_t slot[R];
 #pragma unroll
-    for (int j = 0; j < R; ++j) slot[j] = (WPB > 1 || ONE) ? 0u : ((256u * j) >> shift);   // uniform: a row lies in one bucket
+    for (int j = 0; j < R; ++j) slot[j] = (uint32_t)(j / RPB);   // uniform: a row lies in one bucket
 
     float4 x[R];
 #pragma unroll
@@ -495,7 +497,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     }
 }
 
-template <int R, int WPB, int NW, bool ONE = false>
+template <int R, int WPB, int NW, int RPB = R>
 hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
     const uint64_t groups = (ra.q.n + per_group - 1) / per_group;
@@ -504,15 +506,15 @@ hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     const bool straddle = (32u % ra.q.bits) != 0u;
     const bool once = decode::codes_read_once(ra.q.bits);
     if (ra.q.bits == 1u) {          // three-operation decodes at 1 and 8 bits
-        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, false, 1>), grid, block, 0, stream, ra);
+        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, RPB, false, false, 1>), grid, block, 0, stream, ra);
     } else if (ra.q.bits == 8u) {
-        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, true, 8>), grid, block, 0, stream, ra);
+        hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, RPB, false, true, 8>), grid, block, 0, stream, ra);
     } else if (straddle) {
-        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, true, true, 0>), grid, block, 0, stream, ra);
-        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, true, false, 0>), grid, block, 0, stream, ra);
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, RPB, true, true, 0>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, RPB, true, false, 0>), grid, block, 0, stream, ra);
     } else {
-        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, true, 0>), grid, block, 0, stream, ra);
-        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, ONE, false, false, 0>), grid, block, 0, stream, ra);
+        if (once) hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, RPB, false, true, 0>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_wave_kernel<R, WPB, NW, RPB, false, false, 0>), grid, block, 0, stream, ra);
     }
     return hipGetLastError();
 }
@@ -590,8 +592,10 @@ hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
         case 4096: return launch_requant_wave<4, 4, 4>(ra, stream);
         case 8192: return launch_requant_wave<4, 8, 8>(ra, stream);
         case 16384: return launch_requant_wave<8, 8, 8>(ra, stream);   // workgroups of 16 waves are slower
-        case 1024: return launch_requant_wave<4, 1, 4, true>(ra, stream);   // the bucket is the wave's chunk
-        default: return launch_requant_wave<4, 1, 4>(ra, stream);   // 256, 512
+        case 1024: return launch_requant_wave<4, 1, 4>(ra, stream);      // the bucket is the wave's chunk
+        case 512: return launch_requant_wave<4, 1, 4, 2>(ra, stream);
+        case 256: return launch_requant_wave<4, 1, 4, 1>(ra, stream);
+        default: return hipErrorInvalidValue;   // requantize_wave_supported() admits none other
     }
 }
 
