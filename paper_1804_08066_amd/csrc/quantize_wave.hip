@@ -410,11 +410,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
 // ReceiveQGThenSendQG of Algorithm 1: the chunk's values are not loaded but decoded -- the sum over the
 // W workers' de-quantized gradients, the ordered fma chain of the fused update -- and then quantized
-// exactly as a gradient would be; the stored range is divided by W.  Buckets of 256 elements and more:
-// a wave's 256-element row lies in one bucket, so lane w divides worker w's scale of each row once
-// and the worker loop broadcasts it with v_readlane (no LDS table, no barrier).
+// exactly as a gradient would be; the stored range is divided by W.  Buckets of 128 elements and more:
+// a wave's 256-element row lies in one bucket (two at bucket 128), so the bucket steps of the chunk are
+// divided once by a few lanes and the worker loop broadcasts them with v_readlane (no LDS table, no
+// barrier).
 // RPB: rows of the chunk per bucket (bucket = 256 * RPB when WPB == 1; R when the chunk is part of one
-// bucket), a compile-time number so that rows of one bucket share one division and one v_readlane per worker.
+// bucket), a compile-time number so that rows of one bucket share one division and one v_readlane per
+// worker.  RPB = 0 stands for bucket 128: a row is two buckets, lanes 0-31 and 32-63 select their step.
 template <int R, int WPB, int NW, int RPB, bool STRADDLE, bool ONCE, int WIDTH>
 __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantArgs ra) {
     constexpr uint32_t CH = 256u * R;
@@ -432,14 +434,18 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
     const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
     const bool full = count == CH;
 
-    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 8 here
-    static_assert(R % RPB == 0 && (WPB == 1 || RPB == R), "whole buckets per chunk, or one bucket over several chunks");
-    constexpr uint32_t nbc = R / RPB;                                      // buckets per chunk
-    constexpr uint32_t rpb = RPB;                                          // rows per bucket
+    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 7 here
+    constexpr bool HALF = RPB == 0;                                        // bucket 128: two buckets per row
+    constexpr int RP = HALF ? 1 : RPB;
+    static_assert(HALF ? (WPB == 1 && R == 4) : (R % RP == 0 && (WPB == 1 || RPB == R)),
+                  "whole buckets per chunk, or one bucket over several chunks");
+    constexpr uint32_t nbc = HALF ? 2u * R : R / RP;                       // buckets per chunk
+    constexpr uint32_t rpb = RP;                                           // rows per bucket
+    constexpr uint32_t seg_lanes = HALF ? 32u : 64u;                       // lanes of a row per bucket
     const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : chunk * nbc;       // global index of the chunk's first bucket
     uint32_t slot[R];
 #pragma unroll
-    for (int j = 0; j < R; ++j) slot[j] = (uint32_t)(j / RPB);   // uniform: a row lies in one bucket
+    for (int j = 0; j < R; ++j) slot[j] = HALF ? 2u * j + (lane >> 5) : (uint32_t)(j / RP);   // bucket of row j's quad
 
     float4 x[R];
 #pragma unroll
@@ -448,29 +454,64 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
         const uint32_t b = a.bits;
         const decode::Centred cd = decode::centred(b);
         const float Lf = (float)((1u << b) - 1u);
+        const uint64_t nb_total = (a.n + a.bucket - 1u) >> shift;
+        // Bucket 128 -- eight buckets per chunk and eight workers per worker chunk: lane l takes (worker
+        // l / 8 of the worker chunk, bucket l % 8), one division per lane; the decode reads the two steps
+        // of a row back with v_readlane and each half of the wave selects its own.  The first scale is
+        // requested ahead of the code words: loads return in order, so the wait for it does not have
+        // to drain the code loads behind it.
+        static_assert(!HALF || kChunk * nbc == 64u, "one (worker, bucket) pair per lane");
+        uint64_t my_kb = kb_first + (lane % nbc);
+        if (my_kb >= nb_total) my_kb = nb_total - 1u;   // bucket past the end
+        const auto my_scale = [&](uint32_t w0) {
+            const uint32_t w = w0 + lane / nbc;
+            return ra.scales[w < ra.W ? w : 0u][my_kb];
+        };
+        float sw = HALF ? my_scale(0u) : 0.0f;
         const decode::CodeWindows<R> cw = decode::code_windows<R, 64>(a.n, cb, b, lane);
         decode::CodeRegs<R, kChunk> c;
         decode::fetch_codes<R, kChunk, ONCE>(ra.packed, ra.W, 0u, cw, c);
         clear_words<R, NW>(lane, wave, sm);   // while the loads are in flight
-        // lane w: worker w's step of each row's bucket
-        const uint64_t nb_total = (a.n + a.bucket - 1u) >> shift;
-        const float* my_scales = ra.scales[lane < ra.W ? lane : 0u];
-        float d[R];
+        if (HALF) {
+            const bool second = lane >= 32u;
+            for (uint32_t w0 = 0; w0 < ra.W; w0 += kChunk) {
+                if (w0 > 0) {
+                    sw = my_scale(w0);
+                    decode::fetch_codes<R, kChunk, ONCE>(ra.packed, ra.W, w0, cw, c);
+                }
+                const float dl = sw / Lf;   // IEEE-correct fp32 division
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            uint64_t kb = kb_first + slot[j];
-            if (kb >= nb_total) kb = nb_total - 1u;   // row past the end
-            d[j] = my_scales[kb] / Lf;                // IEEE-correct fp32 division
-        }
-        for (uint32_t w0 = 0; w0 < ra.W; w0 += kChunk) {
-            if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(ra.packed, ra.W, w0, cw, c);
+                for (int t = 0; t < kChunk; ++t) {
+                    if (w0 + t < ra.W) {
 #pragma unroll
-            for (int t = 0; t < kChunk; ++t) {
-                if (w0 + t < ra.W) {
+                        for (int j = 0; j < R; ++j) {
+                            const float d0 = decode::readlane_f32(dl, t * nbc + 2u * j);
+                            const float d1 = decode::readlane_f32(dl, t * nbc + 2u * j + 1u);
+                            decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh, cd, second ? d1 : d0, x[j]);
+                        }
+                    }
+                }
+            }
+        } else {
+            // lane w: worker w's step of each bucket of the chunk
+            const float* my_scales = ra.scales[lane < ra.W ? lane : 0u];
+            float d[R];
 #pragma unroll
-                    for (int j = 0; j < R; ++j) {
-                        const float dw = decode::readlane_f32(d[j], w0 + t);
-                        decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh, cd, dw, x[j]);
+            for (int j = 0; j < R; ++j) {
+                uint64_t kb = kb_first + slot[j];
+                if (kb >= nb_total) kb = nb_total - 1u;   // row past the end
+                d[j] = my_scales[kb] / Lf;                // IEEE-correct fp32 division
+            }
+            for (uint32_t w0 = 0; w0 < ra.W; w0 += kChunk) {
+                if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(ra.packed, ra.W, w0, cw, c);
+#pragma unroll
+                for (int t = 0; t < kChunk; ++t) {
+                    if (w0 + t < ra.W) {
+#pragma unroll
+                        for (int j = 0; j < R; ++j) {
+                            const float dw = decode::readlane_f32(d[j], w0 + t);
+                            decode::accumulate_quad_w<STRADDLE, WIDTH>(c.lo[t][j], cw.sh, cd, dw, x[j]);
+                        }
                     }
                 }
             }
@@ -486,7 +527,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
             }
         }
     }
-    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, 64u, rpb, sm);
+    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm);
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
     if (!active) return;
     const float Wf = (float)ra.W;
@@ -582,9 +623,9 @@ hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
     });
 }
 
-// The re-quantizing server step takes the wave-local kernel for power-of-two buckets of 256 elements
+// The re-quantizing server step takes the wave-local kernel for power-of-two buckets of 128 elements
 // and more.
-bool requantize_wave_supported(const RequantArgs& ra) { return ra.q.bucket_shift >= 8; }
+bool requantize_wave_supported(const RequantArgs& ra) { return ra.q.bucket_shift >= 7; }
 
 hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
     switch (ra.q.bucket) {   // measured choices (100 M elements, W = 8)
@@ -595,6 +636,7 @@ hipError_t launch_requantize_wave(const RequantArgs& ra, hipStream_t stream) {
         case 1024: return launch_requant_wave<4, 1, 4>(ra, stream);      // the bucket is the wave's chunk
         case 512: return launch_requant_wave<4, 1, 4, 2>(ra, stream);
         case 256: return launch_requant_wave<4, 1, 4, 1>(ra, stream);
+        case 128: return launch_requant_wave<4, 1, 4, 0>(ra, stream);
         default: return hipErrorInvalidValue;   // requantize_wave_supported() admits none other
     }
 }

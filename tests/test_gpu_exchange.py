@@ -24,7 +24,7 @@ def to_dev(pk, sc):
             [torch.from_numpy(s.copy()).to(DEV) for s in sc])
 
 
-@pytest.mark.parametrize("bucket", [32, 96, 128, 512, 1024, 4096, 4128, 8192, 16384])
+@pytest.mark.parametrize("bucket", [32, 96, 128, 256, 512, 1024, 2048, 4096, 4128, 8192, 16384])
 def test_requantize_matches_oracle_all_bits(bucket):
     for n in (1, 33, 5000, 40000 + 77):
         for bits in range(1, 9):
