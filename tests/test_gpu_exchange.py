@@ -40,9 +40,10 @@ def test_requantize_matches_oracle_all_bits(bucket):
                 assert np.array_equal(to_u32(got_pk), want_pk), label + " codes"
 
 
+@pytest.mark.parametrize("bucket", [128, 512, 16384])   # two buckets per row; rows share a bucket; workers in chunks of 4
 @pytest.mark.parametrize("W", [2, 9, 17, 64])
-def test_requantize_many_workers(W):
-    n, bucket = 20000 + 3, 512
+def test_requantize_many_workers(W, bucket):
+    n = 20000 + 3
     for bits in (1, 3, 8):
         pk, sc = oracle_workers(n, bits, bucket, W, seed=W)
         dpk, dsc = to_dev(pk, sc)
