@@ -414,8 +414,8 @@ mqg_status mqg_quantize_minmax_tensor(const float* grad, uint64_t n, uint32_t bi
     a.grad = grad;
     a.n = n;
     a.bits = bits;
-    a.bucket = 4096u;            // tiling only: every tile takes the one range in scales_in
-    a.bucket_shift = 12;
+    a.bucket = 1024u;            // tiling only: every chunk takes the one range in scales_in
+    a.bucket_shift = 10;
     a.scales_in = range_out;
     a.packed = packed_out;
     a.scales = nullptr;          // not written when the range is given

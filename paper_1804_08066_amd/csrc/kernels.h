@@ -90,6 +90,8 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_requantize(const RequantArgs& a, hipStream_t stream);
 bool quantize_wave_supported(const QuantizeArgs& a);          // quantize_wave.hip
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream);
+bool quantize_minmax_wave_supported(const QuantizeArgs& a);   // quantize_wave.hip
+hipError_t launch_quantize_minmax_wave(const QuantizeArgs& a, hipStream_t stream);
 bool requantize_wave_supported(const RequantArgs& a);         // quantize_wave.hip
 hipError_t launch_requantize_wave(const RequantArgs& a, hipStream_t stream);
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream);

@@ -75,7 +75,7 @@ __device__ __forceinline__ void clear_shared(Shared<R, NT>& sm, uint32_t tile_co
 // The tile, once its values are in registers; enters right after the barrier that follows
 // clear_shared.  range_div: the stored range is [mn, mx] / range_div (1 for a plain encode, W for the
 // server's mean).
-template <int R, int NT, bool FULL, bool GIVEN = false>
+template <int R, int NT, bool FULL>
 __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
                                                    const uint32_t tile_count, const float4 (&x)[R],
                                                    const float range_div, Shared<R, NT>& sm) {
@@ -99,8 +99,7 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
     constexpr bool kOne = Shared<R, NT>::kOneBucket;
     const uint32_t lane = tid & 63u;
     const bool row_in_bucket = kOne || (a.bucket & 255u) == 0u;   // uniform over the launch
-    constexpr bool given = GIVEN;                                 // one range for the whole tensor, computed before
-    if (!given) {
+    {
     float lo[R], hi[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -153,23 +152,16 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
             }
         }
     }
-    }   // !given
+    }
     __syncthreads();
 
     const float Lf = (float)((1u << b) - 1u);
     if (tid < nbt) {
-        float mn, mx;
-        if (given) {
-            mn = a.scales_in[0];
-            mx = a.scales_in[1];
-        } else {
-            mn = key_value(sm.kmin[tid]);
-            mx = key_value(sm.kmax[tid]);
-            if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
-            if (mx == 0.0f) mx = 0.0f;
-            a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
-            a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
-        }
+        float mn = key_value(sm.kmin[tid]), mx = key_value(sm.kmax[tid]);
+        if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
+        if (mx == 0.0f) mx = 0.0f;
+        a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
+        a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
         const float r = mx - mn;
         sm.mn[tid] = mn;
         sm.a[tid] = (r >= 0x1p-96f) ? Lf / r : 0.0f;   // IEEE-correct fp32 division, once per bucket
@@ -210,8 +202,8 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
     for (uint32_t i = tid; i < nwords; i += NT) __builtin_nontemporal_store(sm.words[i], out + i);
 }
 
-// GIVEN: the range is read from a.scales_in (one pair for the whole tensor) instead of computed per bucket
-template <int R, int NT, bool GIVEN>
+// Bucket sizes that are not powers of two (the others take the wave-local kernel in quantize_wave.hip).
+template <int R, int NT>
 __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
     __shared__ Shared<R, NT> sm;
     const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
@@ -222,12 +214,12 @@ __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs 
         load_grad_tile<R, NT, true>(a.grad + tile_base, tile_count, x);
         clear_shared<R, NT>(sm, tile_count, a.bits);   // while the loads are in flight
         __syncthreads();
-        encode_minmax_tile<R, NT, true, GIVEN>(a, tile_base, tile_count, x, 1.0f, sm);
+        encode_minmax_tile<R, NT, true>(a, tile_base, tile_count, x, 1.0f, sm);
     } else {
         load_grad_tile<R, NT, false>(a.grad + tile_base, tile_count, x);
         clear_shared<R, NT>(sm, tile_count, a.bits);
         __syncthreads();
-        encode_minmax_tile<R, NT, false, GIVEN>(a, tile_base, tile_count, x, 1.0f, sm);
+        encode_minmax_tile<R, NT, false>(a, tile_base, tile_count, x, 1.0f, sm);
     }
 }
 
@@ -481,15 +473,8 @@ hipError_t launch_quantize_r(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid((uint32_t)tiles), block(NT);
-    if (a.scales_in != nullptr) {   // whole-tensor range: the caller tiles with 4096-element tiles
-        if constexpr (NT == 256) {
-            hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, true>), grid, block, 0, stream, a, tile_elems);
-        } else {
-            return hipErrorInvalidValue;
-        }
-    } else {
-        hipLaunchKernelGGL((quantize_minmax_kernel<R, NT, false>), grid, block, 0, stream, a, tile_elems);
-    }
+    if (a.scales_in != nullptr) return hipErrorInvalidValue;   // a given range is tiled with a power-of-two bucket
+    hipLaunchKernelGGL((quantize_minmax_kernel<R, NT>), grid, block, 0, stream, a, tile_elems);
     return hipGetLastError();
 }
 
@@ -544,6 +529,7 @@ hipError_t launch_requantize_minmax(const RequantArgs& ra, hipStream_t stream) {
 // a.scales: 2 floats (min, max) per bucket; a.scale_mode, key, iteration, worker, elem_base unused
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
+    if (quantize_minmax_wave_supported(a)) return launch_quantize_minmax_wave(a, stream);   // power-of-two buckets
     // four float4 per lane at every bucket size; larger buckets take larger workgroups
     if (a.bucket <= 4096u) return launch_quantize_r<4, 256>(a, stream);
     if (a.bucket <= 8192u) return launch_quantize_r<4, 512>(a, stream);

@@ -214,8 +214,29 @@ __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lan
     if (WPB > 1 && lane == 0u) sm.wave_max[wave] = sm.smax[wave][0];   // buckets spanning WPB waves
 }
 
+// The chunk's packed words from the wave's LDS area to the stream, 128 bits per lane.  PLAIN: ordinary
+// stores instead of streaming ones -- the hint pays up to 7 bits (1-3 us at 100 M elements), but at 8
+// bits, where a chunk's words are a quarter of the bytes of its input, ordinary stores are 2-5 us faster.
+template <int R, int NW, bool FULL, bool PLAIN>
+__device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ out, uint32_t count, uint32_t b, uint32_t lane,
+                                                  uint32_t wave, const WaveShared<R, NW>& sm) {
+    if (FULL) {
+        for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
+            const v4u w = *reinterpret_cast<const v4u*>(&sm.words[wave][4u * i]);
+            if (PLAIN) {
+                *(reinterpret_cast<v4u_a4*>(out) + i) = w;
+            } else {
+                __builtin_nontemporal_store(w, reinterpret_cast<v4u_a4*>(out) + i);
+            }
+        }
+    } else {
+        const uint32_t nwords = (count * b + 31u) >> 5;
+        for (uint32_t i = lane; i < nwords; i += 64u) out[i] = sm.words[wave][i];
+    }
+}
+
 // ---- phase 2: scales, grid position, stochastic rounding, packing, store -------------------------
-template <int R, int WPB, int NW, bool FULL>
+template <int R, int WPB, int NW, bool FULL, bool PLAIN = false>
 __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
                                                   uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
                                                   uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm,
@@ -312,22 +333,14 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
     // store the chunk's words
     wave_lds_fence();   // a word holds bits placed by several lanes
     uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
-    if (FULL) {
-        for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
-            const v4u w = *reinterpret_cast<const v4u*>(&sm.words[wave][4u * i]);
-            __builtin_nontemporal_store(w, reinterpret_cast<v4u_a4*>(out) + i);
-        }
-    } else {
-        const uint32_t nwords = (count * b + 31u) >> 5;
-        for (uint32_t i = lane; i < nwords; i += 64u) out[i] = sm.words[wave][i];
-    }
+    store_chunk_words<R, NW, FULL, PLAIN>(out, count, b, lane, wave, sm);
 }
 
 // R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; otherwise bucket = WPB*CH);
 // NW: waves per workgroup, a multiple of WPB
 // HOIST: the Philox calls of the chunk are made before the range reduction and its barrier (they depend
 // on the position only) and kept in 2*R registers until the rounding.
-template <int R, int WPB, int NW, bool HOIST>
+template <int R, int WPB, int NW, bool HOIST, bool PLAIN>
 __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const uint64_t block, WaveShared<R, NW>& sm) {
     constexpr uint32_t CH = 256u * R;
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
@@ -373,24 +386,24 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
     if (!active) return;
     const Draws<R>* drawn = HOIST ? &draws : nullptr;
     if (full) {
-        quantize_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, true, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
     } else {
-        quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, false, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
     }
 }
 
 // OCC: cap on the waves per SIMD (8 = none).  The 2048-element shape fits six waves per SIMD; that is
 // faster than five up to 3 bits and slower from 4 bits on, where a wave writes more (measured at 100 M
 // elements, buckets 128 and 1024: -2..-4 us and +1..+3 us), so the launch picks the cap by the width.
-template <int R, int WPB, int NW, int OCC, bool HOIST>
+template <int R, int WPB, int NW, int OCC, bool HOIST, bool PLAIN>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_wave_kernel(const QuantizeArgs a) {
     __shared__ WaveShared<R, NW> sm;
-    quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x, sm);
+    quantize_wave_block<R, WPB, NW, HOIST, PLAIN>(a, blockIdx.x, sm);
 }
 
 // Several layer tensors of one worker in one launch: workgroup -> (tensor, block of the tensor) through
 // the prefix table of block counts.
-template <int R, int WPB, int NW, int OCC, bool HOIST>
+template <int R, int WPB, int NW, int OCC, bool HOIST, bool PLAIN>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_tensors_wave_kernel(const BatchQuantizeArgs ba) {
     __shared__ WaveShared<R, NW> sm;
     uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
@@ -404,7 +417,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
     a.elem_base = ba.t[lo].elem_base;
     a.packed = ba.t[lo].packed;
     a.scales = ba.t[lo].scales;
-    quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x - ba.tile_start[lo], sm);
+    quantize_wave_block<R, WPB, NW, HOIST, PLAIN>(a, blockIdx.x - ba.tile_start[lo], sm);
 }
 
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
@@ -560,39 +573,237 @@ hipError_t launch_requant_wave(const RequantArgs& ra, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// ---- the deterministic [min, max] encoder on the same decomposition ----------------------------------
+// The footnote of Section 3.2 read literally: per bucket mn = min g, mx = max g, 2^K - 1 equal steps,
+// nearest level (rint), no random numbers.  Same chunks, same packing; the range is a pair, reduced on
+// order-preserving integer keys (the minimum as the maximum of the complemented key, so both run
+// through the same butterfly).  a.scales receives (mn, mx) pairs; a.scales_in != nullptr gives ONE
+// pair for every element (the whole-tensor range computed by an earlier pass).
+template <int R, int NW>
+struct WaveLows {
+    float lo[NW][8 * R];   // per bucket: key of the minimum, then the minimum itself
+    float wave_lo[NW];     // chunk minimum key, for buckets that span several waves
+};
+
+template <int R, int WPB, int NW, bool FULL>
+__device__ __forceinline__ void reduce_minmax(const float4 (&x)[R], uint32_t count, uint32_t lane, uint32_t wave,
+                                              const uint32_t (&slot)[R], uint32_t seg_lanes, uint32_t rpb,
+                                              WaveShared<R, NW>& sm, WaveLows<R, NW>& lw) {
+    const float inf = __builtin_inff();
+    float lo[R], hi[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        if (FULL) {
+            lo[j] = fminf(fminf(x[j].x, x[j].y), fminf(x[j].z, x[j].w));
+            hi[j] = fmaxf(fmaxf(x[j].x, x[j].y), fmaxf(x[j].z, x[j].w));
+        } else {   // elements past the end take no part
+            const uint32_t el = 4u * (j * 64u + lane);
+            const bool v0 = el + 0u < count, v1 = el + 1u < count, v2 = el + 2u < count, v3 = el + 3u < count;
+            lo[j] = fminf(fminf(v0 ? x[j].x : inf, v1 ? x[j].y : inf), fminf(v2 ? x[j].z : inf, v3 ? x[j].w : inf));
+            hi[j] = fmaxf(fmaxf(v0 ? x[j].x : -inf, v1 ? x[j].y : -inf), fmaxf(v2 ? x[j].z : -inf, v3 ? x[j].w : -inf));
+        }
+    }
+    // fold the rows of one bucket into its first row
+#pragma unroll
+    for (int step = 1; step < R; step <<= 1) {
+        if (rpb > (uint32_t)step) {
+#pragma unroll
+            for (int j = 0; j + step < R; j += 2 * step) {
+                lo[j] = fminf(lo[j], lo[j + step]);
+                hi[j] = fmaxf(hi[j], hi[j + step]);
+            }
+        }
+    }
+    uint32_t kh[R], nl[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        kh[j] = order_key(hi[j]);
+        nl[j] = ~order_key(lo[j]);
+    }
+    segment_max_dispatch<R>(kh, rpb, seg_lanes, lane);
+    segment_max_dispatch<R>(nl, rpb, seg_lanes, lane);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        if (((uint32_t)j & (rpb - 1u)) == 0u && (lane & (seg_lanes - 1u)) == 0u) {
+            sm.smax[wave][slot[j]] = __builtin_bit_cast(float, kh[j]);
+            lw.lo[wave][slot[j]] = __builtin_bit_cast(float, ~nl[j]);
+        }
+    }
+    if (WPB > 1 && lane == 0u) {   // buckets spanning WPB waves
+        sm.wave_max[wave] = sm.smax[wave][0];
+        lw.wave_lo[wave] = lw.lo[wave][0];
+    }
+}
+
+template <int R, int WPB, int NW, bool FULL, bool PLAIN>
+__device__ __forceinline__ void encode_minmax_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
+                                                       uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
+                                                       uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm,
+                                                       WaveLows<R, NW>& lw) {
+    const uint32_t b = a.bits;
+    const uint32_t shift = (uint32_t)a.bucket_shift;
+    const float Lf = (float)((1u << b) - 1u);
+    const bool given = a.scales_in != nullptr;
+
+    wave_lds_fence();   // the keys other lanes of this wave published are read below
+    if (WPB > 1 && !given && lane == 0u) {
+        const uint32_t w0 = wave & ~(uint32_t)(WPB - 1);
+        uint32_t kh = __builtin_bit_cast(uint32_t, sm.wave_max[w0]), kl = __builtin_bit_cast(uint32_t, lw.wave_lo[w0]);
+#pragma unroll
+        for (int t = 1; t < WPB; ++t) {
+            kh = max(kh, __builtin_bit_cast(uint32_t, sm.wave_max[w0 + t]));
+            kl = min(kl, __builtin_bit_cast(uint32_t, lw.wave_lo[w0 + t]));
+        }
+        sm.smax[wave][0] = __builtin_bit_cast(float, kh);
+        lw.lo[wave][0] = __builtin_bit_cast(float, kl);
+    }
+    // one lane per bucket: the range, its store, one division
+    if (lane < nbc) {
+        const bool exists = WPB > 1 ? true : ((lane << shift) < count);   // bucket starts inside the vector
+        float mn = 0.0f, mx = 0.0f;
+        if (exists) {
+            if (given) {
+                mn = a.scales_in[0];
+                mx = a.scales_in[1];
+            } else {
+                mn = key_value(__builtin_bit_cast(uint32_t, lw.lo[wave][lane]));
+                mx = key_value(__builtin_bit_cast(uint32_t, sm.smax[wave][lane]));
+                if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
+                if (mx == 0.0f) mx = 0.0f;
+                if (WPB == 1 || (wave & (WPB - 1)) == 0u) {
+                    a.scales[2u * (kb_first + lane)] = mn;
+                    a.scales[2u * (kb_first + lane) + 1u] = mx;
+                }
+            }
+        }
+        const float r = mx - mn;
+        lw.lo[wave][lane] = mn;
+        sm.ainv[wave][lane] = (r >= 0x1p-96f) ? Lf / r : 0.0f;   // IEEE-correct fp32 division, once per bucket
+    }
+    wave_lds_fence();   // every lane reads its buckets' (mn, a); the packing area was cleared by other lanes
+
+    const uint32_t cell_bit = 4u * b * (lane & 7u);            // this lane's bit offset in its 32-element cell
+    const uint32_t sh = cell_bit & 31u;
+    const uint32_t word_in_cell = cell_bit >> 5;
+    const bool straddle = sh + 4u * b > 32u;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const uint32_t ql = j * 64u + lane;
+        const uint32_t el = 4u * ql;
+        const float mn = lw.lo[wave][slot[j]], ai = sm.ainv[wave][slot[j]];
+        // fmaxf drops a NaN position to 0; positions are integers after rint
+        uint32_t k0 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].x - mn) * ai), 0.0f), Lf);
+        uint32_t k1 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].y - mn) * ai), 0.0f), Lf);
+        uint32_t k2 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].z - mn) * ai), 0.0f), Lf);
+        uint32_t k3 = (uint32_t)fminf(fmaxf(__builtin_rintf((x[j].w - mn) * ai), 0.0f), Lf);
+        if (!FULL) {   // elements past the end contribute zero bits
+            if (el + 0u >= count) k0 = 0u;
+            if (el + 1u >= count) k1 = 0u;
+            if (el + 2u >= count) k2 = 0u;
+            if (el + 3u >= count) k3 = 0u;
+        }
+        const uint32_t v = (((((k3 << b) | k2) << b) | k1) << b) | k0;
+        if (FULL || el < count) {
+            const uint32_t w0 = (ql >> 3) * b + word_in_cell;
+            atomicOr(&sm.words[wave][w0], v << sh);
+            if (straddle) atomicOr(&sm.words[wave][w0 + 1u], v >> (32u - sh));
+        }
+    }
+
+    wave_lds_fence();   // a word holds bits placed by several lanes
+    uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
+    store_chunk_words<R, NW, FULL, PLAIN>(out, count, b, lane, wave, sm);
+}
+
+template <int R, int WPB, int NW, bool PLAIN>
+__global__ __launch_bounds__(64 * NW) void quantize_minmax_wave_kernel(const QuantizeArgs a) {
+    constexpr uint32_t CH = 256u * R;
+    static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
+    __shared__ WaveShared<R, NW> sm;
+    __shared__ WaveLows<R, NW> lw;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
+    const uint64_t chunk = (uint64_t)blockIdx.x * NW + wave;
+    const uint64_t cb = chunk * CH;
+    const bool active = cb < a.n;                   // waves past the end only keep the barrier company
+    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
+    const bool full = count == CH;
+
+    // chunk / bucket geometry as in quantize_wave_block
+    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 5
+    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);
+    const uint32_t seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
+    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);
+    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);
+    uint32_t slot[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> shift);
+
+    float4 x[R];
+    if (full) {
+        load_chunk<R, true>(a.grad + cb, count, lane, x);
+    } else {
+        load_chunk<R, false>(a.grad + cb, count, lane, x);
+    }
+    clear_words<R, NW>(lane, wave, sm);   // while the loads are in flight
+    if (a.scales_in == nullptr) {
+        if (full) {
+            reduce_minmax<R, WPB, NW, true>(x, count, lane, wave, slot, seg_lanes, rpb, sm, lw);
+        } else {
+            reduce_minmax<R, WPB, NW, false>(x, count, lane, wave, slot, seg_lanes, rpb, sm, lw);
+        }
+    }
+    if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
+    if (!active) return;
+    if (full) {
+        encode_minmax_and_pack<R, WPB, NW, true, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
+    } else {
+        encode_minmax_and_pack<R, WPB, NW, false, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
+    }
+}
+
 // The measured choice of (R, WPB, NW) per bucket size (100 M elements, every width): buckets up to 1024
 // elements live inside one wave that holds 2048 elements (R = 8); buckets of 2048 .. 8192 span waves of
 // 1024 elements each, 4 or 8 to a workgroup; 16384 spans 8 waves of 2048.
-template <class F>
-auto with_wave_shape(uint32_t bucket, uint32_t bits, F f) {
+template <bool EIGHT, class F>
+auto with_wave_shape_w(uint32_t bucket, uint32_t bits, F f) {
     using std::integral_constant;
-    // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
     using free = integral_constant<int, 8>;   // no cap on the waves per SIMD
     using early = std::true_type;              // random numbers drawn before the range reduction's barrier
     using late = std::false_type;
-    if (bits == 8u && (bucket == 512u || bucket == 1024u)) {
-        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{});
+    using plain = std::integral_constant<bool, EIGHT>;   // ordinary stores of the packed words at 8 bits
+    // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
+    if (EIGHT && (bucket == 512u || bucket == 1024u)) {
+        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
     }
     // Where a barrier lines eight waves of a workgroup up (buckets 8192 and 16384), drawing before it
     // fills the time the waves would otherwise spend waiting for each other: 1-4 us faster at every
     // width; with four waves per workgroup (2048, 4096) it makes no difference (measured, 100 M elements).
     switch (bucket) {
-        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{}, late{});
-        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{}, late{});
-        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
-        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
+        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{}, plain{});
+        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{}, plain{});
         default:   // 32 .. 1024
-            if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{});
-            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{}, late{});
+            if constexpr (!EIGHT) {
+                if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+            }
+            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{}, late{}, plain{});
     }
 }
+template <class F>
+auto with_wave_shape(uint32_t bucket, uint32_t bits, F f) {
+    return bits == 8u ? with_wave_shape_w<true>(bucket, bits, f) : with_wave_shape_w<false>(bucket, bits, f);
+}
 
-template <int R, int WPB, int NW, int OCC, bool HOIST>
+template <int R, int WPB, int NW, int OCC, bool HOIST, bool PLAIN>
 hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
     const uint64_t groups = (a.n + per_group - 1) / per_group;
     if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC, HOIST>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
+    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC, HOIST, PLAIN>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -604,23 +815,53 @@ bool quantize_wave_supported(const QuantizeArgs& a) { return a.bucket_shift >= 5
 
 // elements per workgroup of the wave-local kernel at this bucket size
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits) {
-    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
+    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto, auto, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
 }
 
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
-    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist) {
+    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist, auto plain) {
         constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value, OCC = decltype(occ)::value;
-        constexpr bool HOIST = decltype(hoist)::value;
-        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC, HOIST>), dim3(blocks), dim3(64 * NW), 0, stream, a);
+        constexpr bool HOIST = decltype(hoist)::value, PLAIN = decltype(plain)::value;
+        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC, HOIST, PLAIN>), dim3(blocks), dim3(64 * NW), 0, stream, a);
         return hipGetLastError();
     });
 }
 
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
-    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist) {
+    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist, auto plain) {
         return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value, decltype(occ)::value,
-                           decltype(hoist)::value>(a, stream);
+                           decltype(hoist)::value, decltype(plain)::value>(a, stream);
     });
+}
+
+// The [min, max] encoder takes the same shapes (a given whole-tensor range needs no bucket at all and
+// runs the barrier-free shape).
+bool quantize_minmax_wave_supported(const QuantizeArgs& a) { return a.bucket_shift >= 5; }
+
+template <int R, int WPB, int NW>
+hipError_t launch_minmax_wave(const QuantizeArgs& a, hipStream_t stream) {
+    const uint64_t per_group = (uint64_t)NW * 256u * R;
+    const uint64_t groups = (a.n + per_group - 1) / per_group;
+    if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)groups), block(64 * NW);
+    if (a.bits == 8u) {   // ordinary stores of the packed words, as in the stochastic quantizer
+        hipLaunchKernelGGL((quantize_minmax_wave_kernel<R, WPB, NW, true>), grid, block, 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((quantize_minmax_wave_kernel<R, WPB, NW, false>), grid, block, 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_minmax_wave(const QuantizeArgs& a, hipStream_t stream) {
+    // With no random numbers to draw this encoder is light on the vector ALU, and 1024 elements per wave
+    // beat 2048 at every bucket size up to 1024 (63-65 us against 70 us at 1 bit, 100 M elements).
+    switch (a.bucket) {
+        case 2048: return launch_minmax_wave<4, 2, 4>(a, stream);
+        case 4096: return launch_minmax_wave<4, 4, 4>(a, stream);
+        case 8192: return launch_minmax_wave<4, 8, 8>(a, stream);
+        case 16384: return launch_minmax_wave<8, 8, 8>(a, stream);
+        default: return launch_minmax_wave<4, 1, 4>(a, stream);   // 32 .. 1024
+    }
 }
 
 // The re-quantizing server step takes the wave-local kernel for power-of-two buckets of 128 elements
