@@ -775,8 +775,10 @@ auto with_wave_shape_w(uint32_t bucket, uint32_t bits, F f) {
     using late = std::false_type;
     using plain = std::integral_constant<bool, EIGHT>;   // ordinary stores of the packed words at 8 bits
     // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
-    if (EIGHT && (bucket == 512u || bucket == 1024u)) {
-        return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+    if constexpr (EIGHT) {
+        if (bucket == 512u || bucket == 1024u) {
+            return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+        }
     }
     // Where a barrier lines eight waves of a workgroup up (buckets 8192 and 16384), drawing before it
     // fills the time the waves would otherwise spend waiting for each other: 1-4 us faster at every
