@@ -311,10 +311,10 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
                                 "achieved": by / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "frac": frac(by, ms),
                                 "algorithmic_bytes_per_launch": by}
     return {"bits": bits, "bucket": bucket,
-            "quantize_minmax": row("quantize_minmax_kernel", q_bytes, q_ms),
+            "quantize_minmax": row("quantize_minmax_wave_kernel", q_bytes, q_ms),
             "aggregate_update_minmax": row("aggregate_update_minmax_kernel", a_bytes, a_ms),
             "sum_squares": row("sum_squares_kernel", s_bytes, s_ms),
-            "quantize_minmax_tensor": row("tensor_range_kernel + quantize_minmax_kernel", t_bytes, t_ms),
+            "quantize_minmax_tensor": row("tensor_range_kernel + quantize_minmax_wave_kernel", t_bytes, t_ms),
             "requantize_minmax": {"kernel": "requantize_minmax_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
                                   "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
                                   "unit": "T lane-ops/s", "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
