@@ -125,6 +125,60 @@ def copy_ceiling(wl, reps=30):
     return 8.0 * wl.n / (ts[reps // 2] * 1e-3) / 1e9
 
 
+def machine_state(wl, bits, bucket, seconds=2.0):
+    """Clock levels and performance level as rocm-smi reports them, idle and while the quantize kernel
+    runs back to back (a reader of the numbers wants to know what state the chip was in).  rocm-smi is
+    started as a child process from a thread; the launches go on from the main thread meanwhile."""
+    import re
+    import subprocess
+    import threading
+    import torch
+    from paper_1804_08066_amd import mqgrad
+
+    def sample():
+        try:
+            txt = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--showpower"], capture_output=True,
+                                 text=True, timeout=20).stdout
+        except (OSError, subprocess.SubprocessError) as e:
+            return {"error": str(e)}
+        res = {}
+        for name in ("sclk", "mclk", "fclk", "socclk"):
+            m = re.search(r"GPU\[0\]\s*:\s*%s clock level: \d+: \((\d+)Mhz\)" % name, txt)
+            if m:
+                res[name + "_mhz"] = int(m.group(1))
+        m = re.search(r"GPU\[0\]\s*:\s*Performance Level: (\w+)", txt)
+        if m:
+            res["performance_level"] = m.group(1)
+        m = re.search(r"GPU\[0\]\s*:.*?Power.*?:\s*([\d.]+)", txt)
+        if m:
+            res["power_w"] = float(m.group(1))
+        return res
+
+    torch.cuda.synchronize()
+    state = {"idle": sample()}
+    outs = wl.outputs(bits, bucket)
+    got = {}
+    th = threading.Thread(target=lambda: got.update(sample()))
+    t0 = time.time()
+    started = False
+    k = 0
+    while time.time() - t0 < seconds or th.is_alive():
+        for w in range(wl.W):
+            mqgrad.mqg_quantize(wl.grads[w], bits, bucket, seed=1234, iteration=k, worker=w,
+                                packed_out=outs[w][0], scales_out=outs[w][1])
+        k += 1
+        if k % 8 == 0:
+            torch.cuda.synchronize()   # keep the queue short so that the loop follows the clock
+        if not started and time.time() - t0 > 0.3 * seconds:
+            th.start()
+            started = True
+    torch.cuda.synchronize()
+    th.join()
+    state["under_load"] = got
+    state["load"] = "mqg_quantize back to back for %.1f s (b=%d, bucket=%d)" % (time.time() - t0, bits, bucket)
+    return state
+
+
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 compute units x 64 lanes per clock x 2.4 GHz, one-lane-op units
 
 
@@ -383,6 +437,8 @@ def main():
                     help="also time the small CNN's layer list: one launch per layer versus the multi-tensor calls")
     ap.add_argument("--minmax", action="store_true",
                     help="also time the deterministic [min, max] encoding, its server step and the sum of squares")
+    ap.add_argument("--machine-state", action="store_true",
+                    help="also record rocm-smi's clock and performance levels, idle and while the quantize kernel runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
@@ -465,6 +521,10 @@ def main():
 
     if args.tensors:
         out["tensors"] = time_tensors(W, bits, 512, args.lr, 200, 20, wl.device)
+
+    if args.machine_state:
+        out["machine_state"] = machine_state(wl, bits, bucket)
+        log("machine state: %s" % json.dumps(out["machine_state"]))
 
     if args.calibrate_copy:
         dst = torch.empty_like(wl.grads[0])
