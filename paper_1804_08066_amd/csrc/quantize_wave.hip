@@ -1,7 +1,8 @@
 // Worker side of MQGrad's hot path on gfx950, wavefront-local variant: Quantize(g, K) of
 // Algorithm 1 (WorkerIterate), the range-linear K-bit encode of the Section 3.2 footnote, for
 // power-of-two buckets.  (Other bucket sizes take the workgroup-cooperative kernel in
-// quantize_pack.hip; both produce the same bits.)
+// quantize_pack.hip; both produce the same bits.)  The server's re-quantizing step and the
+// deterministic [min, max] encoder run on the same decomposition further down.
 //
 //   a1  per-bucket range  s = max |g|           DPP / swizzle butterfly inside the wave
 //       (or the bucket's L2 norm: quad squares in fp32, a fp64 butterfly above them)
