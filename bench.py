@@ -179,6 +179,50 @@ def machine_state(wl, bits, bucket, seconds=2.0):
     return state
 
 
+def smi_clocks():
+    """Clock and performance levels as rocm-smi reports them (started as a child process)."""
+    import re
+    import subprocess
+    try:
+        txt = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel"], capture_output=True, text=True, timeout=20).stdout
+    except (OSError, subprocess.SubprocessError) as e:
+        return {"error": str(e)}
+    res = {}
+    for name in ("sclk", "mclk", "fclk", "socclk"):
+        m = re.search(r"GPU\[0\]\s*:\s*%s clock level: \d+: \((\d+)Mhz\)" % name, txt)
+        if m:
+            res[name + "_mhz"] = int(m.group(1))
+    m = re.search(r"GPU\[0\]\s*:\s*Performance Level: (\w+)", txt)
+    if m:
+        res["performance_level"] = m.group(1)
+    return res
+
+
+def transient(wl, bits, bucket, lr, steps):
+    """Per-step launch times of the first `steps` steps: right after the inputs were generated (the
+    state the timed region of a short run starts in), after two seconds of idling, and right after
+    that series (the settled state); rocm-smi's clock levels after each series."""
+    import torch
+    series = []
+    for name, idle_s in (("right after input generation", 0.0), ("after 2 s idle", 2.0), ("back to back with the previous series", 0.0)):
+        if idle_s:
+            time.sleep(idle_s)
+        ev = []
+        run_steps(wl, bits, bucket, lr, steps, 0, ev)
+        torch.cuda.synchronize()
+        q = [e[0].elapsed_time(e[1]) / wl.W * 1e3 for e in ev]
+        a = [e[1].elapsed_time(e[2]) * 1e3 for e in ev]
+        t_ms, acc = [], 0.0
+        for e in ev:
+            t_ms.append(acc)
+            acc += e[0].elapsed_time(e[2])
+        series.append({"start": name, "quantize_us": [round(v, 1) for v in q], "aggregate_us": [round(v, 1) for v in a],
+                       "step_start_ms": [round(v, 2) for v in t_ms], "clocks_after": smi_clocks()})
+        log("transient, %s: quantize first 5 %.1f us, steps 5..24 %.1f us, last 20 %.1f us | aggregate %.1f / %.1f / %.1f us" %
+            (name, sum(q[:5]) / 5, sum(q[5:25]) / 20, sum(q[-20:]) / 20, sum(a[:5]) / 5, sum(a[5:25]) / 20, sum(a[-20:]) / 20))
+    return series
+
+
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 compute units x 64 lanes per clock x 2.4 GHz, one-lane-op units
 
 
@@ -439,6 +483,9 @@ def main():
                     help="also time the deterministic [min, max] encoding, its server step and the sum of squares")
     ap.add_argument("--machine-state", action="store_true",
                     help="also record rocm-smi's clock and performance levels, idle and while the quantize kernel runs")
+    ap.add_argument("--transient", type=int, default=0, metavar="STEPS",
+                    help="before anything else, record the per-step launch times of the first STEPS steps "
+                         "(cold, after idling, settled) into the JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 3 plain device copies of one gradient buffer (4n bytes read, 4n written): "
@@ -463,6 +510,7 @@ def main():
     n, W, bits, bucket = args.n, args.workers, args.bits, args.bucket
     wl = Workload(n, W, dev)
 
+    transient_series = transient(wl, bits, bucket, args.lr, args.transient) if args.transient > 0 else None
     ms_step, q_ms, a_ms = time_config(wl, bits, bucket, args.lr, args.steps, args.warmup)
     value = 4.0 * n * W / (ms_step * 1e-3) / 1e9
     qb, ab = quantize_bytes(n, bits, bucket), aggregate_bytes(n, bits, bucket, W)
@@ -498,6 +546,9 @@ def main():
         "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "copy_ceiling": {"kernel": "torch copy_ of one gradient buffer", "gbs": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS},
     }
+
+    if transient_series is not None:
+        out["transient"] = transient_series
 
     if args.sweep:
         rows = []

@@ -104,17 +104,21 @@ __device__ __forceinline__ void wave_lds_fence() {
 }
 
 // Philox4x32-10 (Salmon et al., SC'11).  Ten rounds of two 32x32->64 multiplies; the key is
-// bumped by the Weyl constants between rounds.
+// bumped by the Weyl constants between rounds.  NOT: return the complement of the four output words
+// (the rounding below consumes 65535 - h); two of the four complements ride along in the last round's
+// three-input xor through a complemented key, which is scalar work.
+template <bool NOT = false>
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint64_t)c0;
         const uint64_t p1 = (uint64_t)kPhiloxM1 * (uint64_t)c2;
-        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
-        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
+        const bool flip = NOT && r == 9;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, flip ? ~k0 : k0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, flip ? ~k1 : k1);
+        c1 = flip ? ~(uint32_t)p1 : (uint32_t)p1;
+        c3 = flip ? ~(uint32_t)p0 : (uint32_t)p0;
         c0 = n0;
         c2 = n2;
         k0 += kPhiloxW0;
@@ -123,17 +127,51 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
 }
 
-// code of one element: floor(u) + [(h + 1/2) / 65536 < frac(u)].
-// The comparison is evaluated as  h < frac*65536 - 1/2 : the right-hand side is exact in fp32
-// whenever it is non-negative (frac*65536 < 2^16 has an ulp of at most 2^-8), and negative
-// otherwise, so both forms decide identically for every integer h in [0, 65535].
-__device__ __forceinline__ uint32_t round_code(float x, float ainv, float halfL, float Lf, uint32_t h16) {
-    float u = __builtin_fmaf(x, ainv, halfL);
-    u = __builtin_amdgcn_fmed3f(u, 0.0f, Lf);
-    const float fr = __builtin_amdgcn_fractf(u);
-    const float t = __builtin_fmaf(fr, 65536.0f, -0.5f);
-    const float hf = (float)h16;
-    return (uint32_t)u + ((hf < t) ? 1u : 0u);
+// Stochastic rounding of one element in 16.16 fixed point.
+//
+// The code is floor(u) + [(h + 1/2) / 65536 < frac(u)], u = clamp(fma(x, a, L/2), 0, L).  For an integer
+// h the comparison says h < T with T = ceil(frac(u) * 65536 - 1/2), the number of the 65536 uniforms
+// that round up.  floor(u) * 65536 + T is ceil(u * 65536 - 1/2) =: F, so
+//     code = (F + 65535 - h) >> 16
+// (the low halves add up to T + 65535 - h, which carries exactly when h < T).  u * 65536 comes out of
+// the same fma with both constants scaled by 2^16 -- a power of two moves through the rounding of the
+// fma unchanged; where u itself is a denormal both forms give code 0 -- and F is one conversion:
+// v_cvt_rpi_i32_f32 returns floor(s + 1/2) exactly, also for |s| >= 2^23, and floor(-v + 1/2) = -F.
+// Five vector operations per element (fma, clamp, convert, subtract, shift) where the floating-point
+// comparison took eight.
+struct FixedGrid {
+    float half16;   // (L/2) * 65536
+    float top16;    // L * 65536
+};
+__device__ __forceinline__ FixedGrid fixed_grid(uint32_t bits) {
+    const float Lf = (float)((1u << bits) - 1u);
+    return FixedGrid{0.5f * Lf * 65536.0f, Lf * 65536.0f};   // exact: L <= 255
+}
+// a16 = fl((L/2)/s) * 65536; returns -F
+__device__ __forceinline__ int neg_fixed_position(float x, float a16, const FixedGrid& g) {
+    float v = __builtin_fmaf(x, a16, g.half16);
+    v = __builtin_amdgcn_fmed3f(v, 0.0f, g.top16);
+    int r;
+    asm("v_cvt_rpi_i32_f32_e64 %0, -%1" : "=v"(r) : "v"(v));
+    return r;
+}
+// nh16 = 65535 - h, the complemented 16-bit uniform.  Returns (code << 16) | (16 bits of no interest).
+__device__ __forceinline__ uint32_t round_code_hi(float x, float a16, const FixedGrid& g, uint32_t nh16) {
+    return nh16 - (uint32_t)neg_fixed_position(x, a16, g);
+}
+
+// The four codes of a quad, each in the upper half-word of its register, as one value of 4 * bits bits
+// (code 0 lowest).  The shifts and the first or read the upper half-word directly (SDWA operand
+// selection), so no separate >> 16 is issued: five operations per quad.  s1, s2, s3 = bits, 2 * bits,
+// 3 * bits.
+__device__ __forceinline__ uint32_t pack_quad_hi(uint32_t t0, uint32_t t1, uint32_t t2, uint32_t t3,
+                                                 uint32_t s1, uint32_t s2, uint32_t s3) {
+    uint32_t v1, v2, v3, v0;
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(v1) : "s"(s1), "v"(t1));
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(v2) : "s"(s2), "v"(t2));
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(v3) : "s"(s3), "v"(t3));
+    asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:DWORD" : "=v"(v0) : "v"(t0), "v"(v1));
+    return v0 | v2 | v3;
 }
 
 }  // namespace encode

@@ -254,7 +254,8 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
             s = a.scales_in[kb0 + tid];
         }
         a.scales[kb0 + tid] = (range_div == 1.0f) ? s : s / range_div;
-        sm.ainv[tid] = (s > 0.0f) ? halfL / s : 0.0f;   // IEEE-correct fp32 division, once per bucket
+        // IEEE-correct fp32 division, once per bucket; kept times 2^16 (exact) for the fixed-point rounding
+        sm.ainv[tid] = (s > 0.0f) ? (halfL / s) * 65536.0f : 0.0f;
     }
     __syncthreads();
 
@@ -262,6 +263,7 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
     const uint32_t odd = tid & 1u;
     const uint64_t group0 = (a.elem_base + tile_base) >> 3;   // both multiples of 8
     const uint32_t b = a.bits;
+    const FixedGrid fg = fixed_grid(b);
     const uint32_t cell_bit = 4u * b * (tid & 7u);            // this lane's bit offset in its cell
     const uint32_t sh = cell_bit & 31u;
     const uint32_t word_in_cell = cell_bit >> 5;
@@ -273,7 +275,7 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
         const uint32_t my_row = jp + odd;
         const uint64_t grp = group0 + (uint64_t)((my_row * kThreads + tid) >> 1);
         uint32_t o[4];
-        philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
+        philox4x32_10<true>((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);   // complemented words
         // the swaps run with every lane active; the selects keep the half each lane needs
         const uint32_t p0 = dpp_u32<kDppQuadSwap1>(o[0]), p1 = dpp_u32<kDppQuadSwap1>(o[1]);
         const uint32_t p2 = dpp_u32<kDppQuadSwap1>(o[2]), p3 = dpp_u32<kDppQuadSwap1>(o[3]);
@@ -285,17 +287,17 @@ __device__ __forceinline__ void quantize_tile(const QuantizeArgs& a, const uint6
             const uint32_t ql = j * kThreads + tid;
             const uint32_t el = 4u * ql;
             const float ainv = sm.ainv[bl[j]];
-            uint32_t k0 = round_code(x[j].x, ainv, halfL, Lf, rw[t][0] & 0xFFFFu);
-            uint32_t k1 = round_code(x[j].y, ainv, halfL, Lf, rw[t][0] >> 16);
-            uint32_t k2 = round_code(x[j].z, ainv, halfL, Lf, rw[t][1] & 0xFFFFu);
-            uint32_t k3 = round_code(x[j].w, ainv, halfL, Lf, rw[t][1] >> 16);
+            uint32_t t0 = round_code_hi(x[j].x, ainv, fg, rw[t][0] & 0xFFFFu);
+            uint32_t t1 = round_code_hi(x[j].y, ainv, fg, rw[t][0] >> 16);
+            uint32_t t2 = round_code_hi(x[j].z, ainv, fg, rw[t][1] & 0xFFFFu);
+            uint32_t t3 = round_code_hi(x[j].w, ainv, fg, rw[t][1] >> 16);
             if (!FULL) {   // elements past the end contribute zero bits
-                if (el + 0u >= tile_count) k0 = 0u;
-                if (el + 1u >= tile_count) k1 = 0u;
-                if (el + 2u >= tile_count) k2 = 0u;
-                if (el + 3u >= tile_count) k3 = 0u;
+                if (el + 0u >= tile_count) t0 = 0u;
+                if (el + 1u >= tile_count) t1 = 0u;
+                if (el + 2u >= tile_count) t2 = 0u;
+                if (el + 3u >= tile_count) t3 = 0u;
             }
-            const uint32_t v = (((((k3 << b) | k2) << b) | k1) << b) | k0;
+            const uint32_t v = pack_quad_hi(t0, t1, t2, t3, b, 2u * b, 3u * b);
             if (FULL || el < tile_count) {
                 const uint32_t w0 = (ql >> 3) * b + word_in_cell;
                 atomicOr(&sm.words[w0], v << sh);

@@ -130,11 +130,12 @@ __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lan
 // One Philox call covers 8 consecutive elements = the quads of an even/odd lane pair.  For the row
 // pair (jp, jp + 1) the even lane draws for row jp and the odd lane for row jp + 1, so no lane makes a
 // call whose output is thrown away.  The numbers depend on the position only, not on the data.
+// Returns the complemented words: the rounding consumes 65535 - h.
 __device__ __forceinline__ void draw_pair(const QuantizeArgs& a, uint64_t cb, uint32_t lane, int jp, uint32_t (&o)[4]) {
     const uint64_t group0 = (a.elem_base + cb) >> 3;           // both multiples of 8
     const uint32_t my_row = jp + (lane & 1u);
     const uint64_t grp = group0 + (uint64_t)((my_row * 64u + lane) >> 1);
-    philox4x32_10((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
+    philox4x32_10<true>((uint32_t)grp, (uint32_t)(grp >> 32), a.iteration, a.worker, a.key0, a.key1, o);
 }
 template <int R>
 struct Draws {
@@ -247,6 +248,7 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
     const uint32_t shift = (uint32_t)a.bucket_shift;
     const float Lf = (float)((1u << b) - 1u);
     const float halfL = 0.5f * Lf;
+    const FixedGrid fg = fixed_grid(b);
 
     wave_lds_fence();   // the ranges other lanes of this wave published are read below
     if (WPB > 1 && a.scales_in == nullptr && lane == 0u) {
@@ -279,7 +281,9 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
             }
             if (WPB == 1 || (wave & (WPB - 1)) == 0u) a.scales[kb_first + lane] = (range_div == 1.0f) ? s : s / range_div;
         }
-        sm.ainv[wave][lane] = (s > 0.0f) ? halfL / s : 0.0f;   // IEEE-correct fp32 division, once per bucket
+        // IEEE-correct fp32 division, once per bucket; the factor is kept times 2^16 (exact) for the
+        // fixed-point rounding
+        sm.ainv[wave][lane] = (s > 0.0f) ? (halfL / s) * 65536.0f : 0.0f;
     }
     wave_lds_fence();   // every lane reads its buckets' factors; the packing area was cleared by other lanes
 
@@ -312,17 +316,17 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
             const uint32_t ql = j * 64u + lane;
             const uint32_t el = 4u * ql;
             const float ainv = sm.ainv[wave][slot[j]];
-            uint32_t k0 = round_code(x[j].x, ainv, halfL, Lf, rw[t][0] & 0xFFFFu);
-            uint32_t k1 = round_code(x[j].y, ainv, halfL, Lf, rw[t][0] >> 16);
-            uint32_t k2 = round_code(x[j].z, ainv, halfL, Lf, rw[t][1] & 0xFFFFu);
-            uint32_t k3 = round_code(x[j].w, ainv, halfL, Lf, rw[t][1] >> 16);
+            uint32_t t0 = round_code_hi(x[j].x, ainv, fg, rw[t][0] & 0xFFFFu);
+            uint32_t t1 = round_code_hi(x[j].y, ainv, fg, rw[t][0] >> 16);
+            uint32_t t2 = round_code_hi(x[j].z, ainv, fg, rw[t][1] & 0xFFFFu);
+            uint32_t t3 = round_code_hi(x[j].w, ainv, fg, rw[t][1] >> 16);
             if (!FULL) {   // elements past the end contribute zero bits
-                if (el + 0u >= count) k0 = 0u;
-                if (el + 1u >= count) k1 = 0u;
-                if (el + 2u >= count) k2 = 0u;
-                if (el + 3u >= count) k3 = 0u;
+                if (el + 0u >= count) t0 = 0u;
+                if (el + 1u >= count) t1 = 0u;
+                if (el + 2u >= count) t2 = 0u;
+                if (el + 3u >= count) t3 = 0u;
             }
-            const uint32_t v = (((((k3 << b) | k2) << b) | k1) << b) | k0;   // three shift-or steps
+            const uint32_t v = pack_quad_hi(t0, t1, t2, t3, b, 2u * b, 3u * b);
             if (FULL || el < count) {
                 const uint32_t w0 = (ql >> 3) * b + word_in_cell;
                 atomicOr(&sm.words[wave][w0], v << sh);
