@@ -59,7 +59,13 @@ struct CodeRegs {
 // the same line, and a streaming load would fetch it from L2 once per wave: there the loads are
 // ordinary ones, so that the vector L1 serves the neighbours (measured at 100 M elements, W = 8:
 // 7-11 % faster at 1, 2, 3, 5, 7 bits; 6 bits is 2 % faster with the hint).
+#if defined(MQG_XONCE) && MQG_XONCE == 0
+inline __host__ __device__ bool codes_read_once(uint32_t b) { return false; }
+#elif defined(MQG_XONCE) && MQG_XONCE == 1
+inline __host__ __device__ bool codes_read_once(uint32_t b) { return true; }
+#else
 inline __host__ __device__ bool codes_read_once(uint32_t b) { return b >= 4u && (b & 1u) == 0u; }
+#endif
 
 // Fetch the first code word of each of the lane's quads for workers [w0, min(w0 + CH, W)): one
 // aligned dword load per worker and quad, all issued before any is consumed.  Adjacent lanes read

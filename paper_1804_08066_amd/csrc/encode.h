@@ -24,6 +24,14 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef v4f v4f_a4 __attribute__((aligned(4)));
 typedef v4u v4u_a4 __attribute__((aligned(4)));
 
+// 128-bit store with agent scope (the sc1 cache-policy bit): the data is written through to memory at
+// once and the line stays valid in L2.  HIP has no builtin for a scoped 128-bit store.  `base` must be
+// wave-uniform (it travels in scalar registers), `byte_off` is the lane's offset from it.  The
+// instruction reads its operands when it issues, so the registers are free right after it.
+__device__ __forceinline__ void store_v4u_agent(const void* base, uint32_t byte_off, v4u w) {
+    asm volatile("global_store_dwordx4 %0, %1, %2 sc1" ::"v"(byte_off), "v"(w), "s"(base) : "memory");
+}
+
 // DPP reads of a switched-off lane return 0: call these with every lane of the wave active.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {

@@ -216,20 +216,18 @@ __device__ __forceinline__ void reduce_ranges(const float4 (&x)[R], uint32_t lan
     if (WPB > 1 && lane == 0u) sm.wave_max[wave] = sm.smax[wave][0];   // buckets spanning WPB waves
 }
 
-// The chunk's packed words from the wave's LDS area to the stream, 128 bits per lane.  PLAIN: ordinary
-// stores instead of streaming ones -- the hint pays up to 7 bits (1-3 us at 100 M elements), but at 8
-// bits, where a chunk's words are a quarter of the bytes of its input, ordinary stores are 2-5 us faster.
-template <int R, int NW, bool FULL, bool PLAIN>
+// The chunk's packed words from the wave's LDS area to the stream, 128 bits per lane.  The stores carry
+// agent scope (write-through to memory, the line stays in L2): measured against streaming and ordinary
+// stores at 100 M elements they are 1-3 us faster in this kernel at every width, and the server step
+// that follows finds the code words in the last-level cache (8 workers at up to 4 bits are 400 MB or
+// less): its time drops by 3-11 %.
+template <int R, int NW, bool FULL>
 __device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ out, uint32_t count, uint32_t b, uint32_t lane,
                                                   uint32_t wave, const WaveShared<R, NW>& sm) {
     if (FULL) {
         for (uint32_t i = lane; i < 2u * R * b; i += 64u) {   // 8*R*bits words = 2*R*bits groups of 4
             const v4u w = *reinterpret_cast<const v4u*>(&sm.words[wave][4u * i]);
-            if (PLAIN) {
-                *(reinterpret_cast<v4u_a4*>(out) + i) = w;
-            } else {
-                __builtin_nontemporal_store(w, reinterpret_cast<v4u_a4*>(out) + i);
-            }
+            store_v4u_agent(out, 16u * i, w);
         }
     } else {
         const uint32_t nwords = (count * b + 31u) >> 5;
@@ -238,7 +236,7 @@ __device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ out, ui
 }
 
 // ---- phase 2: scales, grid position, stochastic rounding, packing, store -------------------------
-template <int R, int WPB, int NW, bool FULL, bool PLAIN = false>
+template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
                                                   uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
                                                   uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm,
@@ -338,14 +336,14 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
     // store the chunk's words
     wave_lds_fence();   // a word holds bits placed by several lanes
     uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
-    store_chunk_words<R, NW, FULL, PLAIN>(out, count, b, lane, wave, sm);
+    store_chunk_words<R, NW, FULL>(out, count, b, lane, wave, sm);
 }
 
 // R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; otherwise bucket = WPB*CH);
 // NW: waves per workgroup, a multiple of WPB
 // HOIST: the Philox calls of the chunk are made before the range reduction and its barrier (they depend
 // on the position only) and kept in 2*R registers until the rounding.
-template <int R, int WPB, int NW, bool HOIST, bool PLAIN>
+template <int R, int WPB, int NW, bool HOIST>
 __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const uint64_t block, WaveShared<R, NW>& sm) {
     constexpr uint32_t CH = 256u * R;
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
@@ -391,24 +389,24 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
     if (!active) return;
     const Draws<R>* drawn = HOIST ? &draws : nullptr;
     if (full) {
-        quantize_and_pack<R, WPB, NW, true, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
     } else {
-        quantize_and_pack<R, WPB, NW, false, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
     }
 }
 
 // OCC: cap on the waves per SIMD (8 = none).  The 2048-element shape fits six waves per SIMD; that is
 // faster than five up to 3 bits and slower from 4 bits on, where a wave writes more (measured at 100 M
 // elements, buckets 128 and 1024: -2..-4 us and +1..+3 us), so the launch picks the cap by the width.
-template <int R, int WPB, int NW, int OCC, bool HOIST, bool PLAIN>
+template <int R, int WPB, int NW, int OCC, bool HOIST>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_wave_kernel(const QuantizeArgs a) {
     __shared__ WaveShared<R, NW> sm;
-    quantize_wave_block<R, WPB, NW, HOIST, PLAIN>(a, blockIdx.x, sm);
+    quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x, sm);
 }
 
 // Several layer tensors of one worker in one launch: workgroup -> (tensor, block of the tensor) through
 // the prefix table of block counts.
-template <int R, int WPB, int NW, int OCC, bool HOIST, bool PLAIN>
+template <int R, int WPB, int NW, int OCC, bool HOIST>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_tensors_wave_kernel(const BatchQuantizeArgs ba) {
     __shared__ WaveShared<R, NW> sm;
     uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
@@ -422,7 +420,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
     a.elem_base = ba.t[lo].elem_base;
     a.packed = ba.t[lo].packed;
     a.scales = ba.t[lo].scales;
-    quantize_wave_block<R, WPB, NW, HOIST, PLAIN>(a, blockIdx.x - ba.tile_start[lo], sm);
+    quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x - ba.tile_start[lo], sm);
 }
 
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
@@ -640,7 +638,7 @@ __device__ __forceinline__ void reduce_minmax(const float4 (&x)[R], uint32_t cou
     }
 }
 
-template <int R, int WPB, int NW, bool FULL, bool PLAIN>
+template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void encode_minmax_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
                                                        uint32_t wave, const uint32_t (&slot)[R], uint32_t nbc,
                                                        uint64_t kb_first, const float4 (&x)[R], WaveShared<R, NW>& sm,
@@ -717,10 +715,10 @@ __device__ __forceinline__ void encode_minmax_and_pack(const QuantizeArgs& a, ui
 
     wave_lds_fence();   // a word holds bits placed by several lanes
     uint32_t* __restrict__ out = a.packed + (cb >> 5) * b;
-    store_chunk_words<R, NW, FULL, PLAIN>(out, count, b, lane, wave, sm);
+    store_chunk_words<R, NW, FULL>(out, count, b, lane, wave, sm);
 }
 
-template <int R, int WPB, int NW, bool PLAIN>
+template <int R, int WPB, int NW>
 __global__ __launch_bounds__(64 * NW) void quantize_minmax_wave_kernel(const QuantizeArgs a) {
     constexpr uint32_t CH = 256u * R;
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
@@ -763,9 +761,9 @@ __global__ __launch_bounds__(64 * NW) void quantize_minmax_wave_kernel(const Qua
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
     if (!active) return;
     if (full) {
-        encode_minmax_and_pack<R, WPB, NW, true, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
+        encode_minmax_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
     } else {
-        encode_minmax_and_pack<R, WPB, NW, false, PLAIN>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
+        encode_minmax_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
     }
 }
 
@@ -778,26 +776,37 @@ auto with_wave_shape_w(uint32_t bucket, uint32_t bits, F f) {
     using free = integral_constant<int, 8>;   // no cap on the waves per SIMD
     using early = std::true_type;              // random numbers drawn before the range reduction's barrier
     using late = std::false_type;
-    using plain = std::integral_constant<bool, EIGHT>;   // ordinary stores of the packed words at 8 bits
     // at 8 bits the packed chunk of a 2048-element wave is at its largest; 1024 elements per wave are as fast or faster there
     if constexpr (EIGHT) {
         if (bucket == 512u || bucket == 1024u) {
-            return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+            return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{});
         }
     }
     // Where a barrier lines eight waves of a workgroup up (buckets 8192 and 16384), drawing before it
     // fills the time the waves would otherwise spend waiting for each other: 1-4 us faster at every
     // width; with four waves per workgroup (2048, 4096) it makes no difference (measured, 100 M elements).
     switch (bucket) {
-        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
-        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
-        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{}, plain{});
-        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{}, plain{});
+        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{}, free{}, late{});
+        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{}, free{}, late{});
+        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
+        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
         default:   // 32 .. 1024
+#ifndef MQG_XR
+#define MQG_XR 8
+#endif
+#ifndef MQG_XNW
+#define MQG_XNW 4
+#endif
+#ifndef MQG_XOCC_LO
+#define MQG_XOCC_LO 8
+#endif
+#ifndef MQG_XOCC_HI
+#define MQG_XOCC_HI 5
+#endif
             if constexpr (!EIGHT) {
-                if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{}, plain{});
+                if (bits <= 3u) return f(integral_constant<int, MQG_XR>{}, integral_constant<int, 1>{}, integral_constant<int, MQG_XNW>{}, integral_constant<int, MQG_XOCC_LO>{}, late{});
             }
-            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{}, late{}, plain{});
+            return f(integral_constant<int, MQG_XR>{}, integral_constant<int, 1>{}, integral_constant<int, MQG_XNW>{}, integral_constant<int, MQG_XOCC_HI>{}, late{});
     }
 }
 template <class F>
@@ -805,12 +814,12 @@ auto with_wave_shape(uint32_t bucket, uint32_t bits, F f) {
     return bits == 8u ? with_wave_shape_w<true>(bucket, bits, f) : with_wave_shape_w<false>(bucket, bits, f);
 }
 
-template <int R, int WPB, int NW, int OCC, bool HOIST, bool PLAIN>
+template <int R, int WPB, int NW, int OCC, bool HOIST>
 hipError_t launch_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t per_group = (uint64_t)NW * 256u * R;
     const uint64_t groups = (a.n + per_group - 1) / per_group;
     if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC, HOIST, PLAIN>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
+    hipLaunchKernelGGL((quantize_wave_kernel<R, WPB, NW, OCC, HOIST>), dim3((uint32_t)groups), dim3(64 * NW), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -822,22 +831,22 @@ bool quantize_wave_supported(const QuantizeArgs& a) { return a.bucket_shift >= 5
 
 // elements per workgroup of the wave-local kernel at this bucket size
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits) {
-    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto, auto, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
+    return with_wave_shape(bucket, bits, [](auto r, auto, auto nw, auto, auto) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
 }
 
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
-    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist, auto plain) {
+    return with_wave_shape(a.common.bucket, a.common.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist) {
         constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value, OCC = decltype(occ)::value;
-        constexpr bool HOIST = decltype(hoist)::value, PLAIN = decltype(plain)::value;
-        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC, HOIST, PLAIN>), dim3(blocks), dim3(64 * NW), 0, stream, a);
+        constexpr bool HOIST = decltype(hoist)::value;
+        hipLaunchKernelGGL((quantize_tensors_wave_kernel<R, WPB, NW, OCC, HOIST>), dim3(blocks), dim3(64 * NW), 0, stream, a);
         return hipGetLastError();
     });
 }
 
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
-    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist, auto plain) {
+    return with_wave_shape(a.bucket, a.bits, [&](auto r, auto wpb, auto nw, auto occ, auto hoist) {
         return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value, decltype(occ)::value,
-                           decltype(hoist)::value, decltype(plain)::value>(a, stream);
+                           decltype(hoist)::value>(a, stream);
     });
 }
 
@@ -851,11 +860,7 @@ hipError_t launch_minmax_wave(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t groups = (a.n + per_group - 1) / per_group;
     if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid((uint32_t)groups), block(64 * NW);
-    if (a.bits == 8u) {   // ordinary stores of the packed words, as in the stochastic quantizer
-        hipLaunchKernelGGL((quantize_minmax_wave_kernel<R, WPB, NW, true>), grid, block, 0, stream, a);
-    } else {
-        hipLaunchKernelGGL((quantize_minmax_wave_kernel<R, WPB, NW, false>), grid, block, 0, stream, a);
-    }
+    hipLaunchKernelGGL((quantize_minmax_wave_kernel<R, WPB, NW>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
