@@ -25,13 +25,38 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
-# of known size (profiles/quantize_aggregate_100M_W8_b4_B1024_hbm_traffic.md).  Only the workload
-# that was profiled has an entry; any other reports null.
-MEASURED_TRAFFIC = {
-    # (n, workers, bits, bucket): (quantize bytes per launch, aggregate_update bytes per launch)
-    (100_000_000, 8, 4, 1024): (450.6e6, 1225.1e6),
-}
+PROFILES = os.path.join(ROOT, "profiles")
+TRAFFIC_PROFILE = os.path.join(PROFILES, "quantize_aggregate_100M_W8_b4_B1024_hbm_traffic.md")
+MACHINE_STATE_PROFILE = os.path.join(PROFILES, "machine_state_100M_W8_b4_B1024.md")
+
+
+def measured_traffic(n, W, bits, bucket):
+    """HBM bytes per launch of the two hot kernels as rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE read them
+    (scaled by a copy of known size), taken from the tracked summary of that measurement: its line
+    `traffic_json: {...}` names the workload and the commit it was measured at.  A workload that was
+    not profiled reports null."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("traffic_json:"):
+                d = json.loads(line[len("traffic_json:"):])
+                wl = d["workload"]
+                if (wl["n"], wl["workers"], wl["bits"], wl["bucket"]) == (n, W, bits, bucket):
+                    return d
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
+
+
+def load_clock_mhz():
+    """Engine clock under sustained load as the tracked machine-state summary recorded it (rocm-smi)."""
+    try:
+        for line in open(MACHINE_STATE_PROFILE):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 3 and cells[1] == "under load" and cells[2].isdigit():
+                return int(cells[2])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -91,6 +116,9 @@ def run_steps(wl, bits, bucket, lr, steps, iteration0, events=None):
 
 
 def time_config(wl, bits, bucket, lr, steps, warmup):
+    """`warmup` untimed steps, then exactly `steps` steps between two synchronizations.  Returns
+    (ms per step by the host clock, ms per quantize launch, ms per aggregate launch) with the launch
+    times from HIP events on the launch stream; time_config.last holds the spread of the per-step series."""
     import torch
     run_steps(wl, bits, bucket, lr, warmup, 0)
     torch.cuda.synchronize()
@@ -99,30 +127,110 @@ def time_config(wl, bits, bucket, lr, steps, warmup):
     run_steps(wl, bits, bucket, lr, steps, warmup, events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    q_all = sorted(e[0].elapsed_time(e[1]) / wl.W for e in events)           # per quantize launch, one value per step
-    a_all = sorted(e[1].elapsed_time(e[2]) for e in events)                  # per aggregate launch
+    q_series = [e[0].elapsed_time(e[1]) / wl.W for e in events]             # per quantize launch, one value per step
+    a_series = [e[1].elapsed_time(e[2]) for e in events]                    # per aggregate launch
+    q_all, a_all = sorted(q_series), sorted(a_series)
     q_ms, a_ms = sum(q_all) / steps, sum(a_all) / steps
+    head = min(5, steps)
     time_config.last = {"quantize_us_median": q_all[steps // 2] * 1e3, "quantize_us_min": q_all[0] * 1e3,
-                        "aggregate_us_median": a_all[steps // 2] * 1e3, "aggregate_us_min": a_all[0] * 1e3}
+                        "quantize_us_first5": sum(q_series[:head]) / head * 1e3,
+                        "aggregate_us_median": a_all[steps // 2] * 1e3, "aggregate_us_min": a_all[0] * 1e3,
+                        "aggregate_us_first5": sum(a_series[:head]) / head * 1e3}
     return (t1 - t0) / steps * 1e3, q_ms, a_ms
 
 
-def copy_ceiling(wl, reps=30):
-    """A plain device copy of one gradient buffer (4n bytes read + 4n written): what this machine's HBM
-    delivers to the simplest streaming kernel, the practical ceiling beside the 8 TB/s peak."""
+def condition(wl, bits, bucket, lr, ms):
+    """Untimed steps of the benchmark's own loop until `ms` milliseconds have passed.  After any idle gap
+    (even the half second a synchronize and a child process take) the chip runs about three steps at
+    boost clocks, drops into a throttled state and recovers over some 20 ms (profiles/transient_*.md): a
+    region timed right after input generation measures that state, not the one a training loop runs in."""
     import torch
+    t0 = time.perf_counter()
+    done = 0
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        run_steps(wl, bits, bucket, lr, 8, done)
+        done += 8
+        torch.cuda.synchronize()   # keeps the queue short so that the loop ends on time
+    return done, (time.perf_counter() - t0) * 1e3
+
+
+_bench_lib = None
+
+
+def bench_lib():
+    """libmqgrad_bench.so: streaming kernels with the hot kernels' read/write mix (csrc/bench_stream.hip)."""
+    global _bench_lib
+    if _bench_lib is None:
+        import ctypes as C
+        from paper_1804_08066_amd import build
+        L = C.CDLL(build.BENCH_LIB)
+        L.mqg_bench_stream_quantize.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.mqg_bench_stream_quantize.restype = C.c_int
+        L.mqg_bench_stream_update.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.mqg_bench_stream_update.restype = C.c_int
+        _bench_lib = L
+    return _bench_lib
+
+
+def stream_ceilings(wl, bits, bucket, steps=40, warmup=20):
+    """What this machine's HBM gives to the two kernels' read/write mixes: the benchmark's step with each
+    kernel replaced by a streaming kernel that moves the same bytes in the same launch shape with the same
+    cache hints and does no arithmetic (W reads of a gradient buffer + writes of n*bits/8 bytes, then one
+    pass that reads the W code streams and reads and writes the parameters).  Also a plain device copy of
+    one gradient buffer (torch's copy_), for reference."""
+    import ctypes as C
+    import torch
+    L = bench_lib()
+    n8 = wl.n // 8192 * 8192
+    outs = wl.outputs(bits, bucket)
+    pk = [o[0] for o in outs]
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    codes = (C.c_void_p * wl.W)(*[t.data_ptr() for t in pk])
+    best, best_u = None, None
+    for shape, label in ((0, "2048 floats per wave, 4 waves per workgroup"), (1, "1024 per wave, 4 waves"), (2, "2048 per wave, 2 waves")):
+        ev = []
+        for k in range(warmup + steps):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record()
+            for w in range(wl.W):
+                rc = L.mqg_bench_stream_quantize(wl.grads[w].data_ptr(), n8, bits, shape, pk[w].data_ptr(), stream)
+                assert rc == 0, rc
+            e[1].record()
+            rc = L.mqg_bench_stream_update(codes, wl.W, n8, bits, shape & 1, wl.params.data_ptr(), stream)
+            assert rc == 0, rc
+            e[2].record()
+            if k >= warmup:
+                ev.append(e)
+        torch.cuda.synchronize()
+        q = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev) / wl.W
+        u = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+        if best is None or q < best[0]:
+            best = (q, label)
+        if best_u is None or u < best_u[0]:
+            best_u = (u, "at most four waves per SIMD" if shape & 1 else "up to eight waves per SIMD")
+    (q_ms, q_shape), (u_ms, u_shape) = best, best_u
+    q_gbs = n8 * (4.0 + bits / 8.0) / (q_ms * 1e-3) / 1e9
+    u_gbs = n8 * (8.0 + wl.W * bits / 8.0) / (u_ms * 1e-3) / 1e9
     dst = torch.empty_like(wl.grads[0])
+    reps = 30
     for k in range(10):
         dst.copy_(wl.grads[k % wl.W])
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-    ev[0].record()
+    cev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    cev[0].record()
     for k in range(reps):
         dst.copy_(wl.grads[k % wl.W])
-        ev[k + 1].record()
+        cev[k + 1].record()
     torch.cuda.synchronize()
-    ts = sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(reps))
+    ts = sorted(cev[k].elapsed_time(cev[k + 1]) for k in range(reps))
     del dst
-    return 8.0 * wl.n / (ts[reps // 2] * 1e-3) / 1e9
+    copy_gbs = 8.0 * wl.n / (ts[reps // 2] * 1e-3) / 1e9
+    return {"quantize_mix": {"kernel": "stream_quantize_kernel (bench only), best of three launch shapes: " + q_shape,
+                             "us": q_ms * 1e3, "gbs": q_gbs,
+                             "frac_of_peak": q_gbs / HBM_PEAK_GBS},
+            "update_mix": {"kernel": "stream_update_kernel (bench only), best of two occupancy caps: " + u_shape,
+                           "us": u_ms * 1e3, "gbs": u_gbs,
+                           "frac_of_peak": u_gbs / HBM_PEAK_GBS},
+            "torch_copy": {"kernel": "torch copy_ of one gradient buffer", "gbs": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS}}
 
 
 def machine_state(wl, bits, bucket, seconds=2.0):
@@ -226,6 +334,22 @@ def transient(wl, bits, bucket, lr, steps):
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 compute units x 64 lanes per clock x 2.4 GHz, one-lane-op units
 
 
+def alu_row(kernel, ms, ops, extra=None):
+    """Roofline entry of a kernel bound by vector-ALU issue: against the nominal peak (2.4 GHz) and against
+    the peak at the engine clock that rocm-smi read under sustained load (tracked machine-state summary)."""
+    tops = ops / (ms * 1e-3) / 1e12
+    row = {"kernel": kernel, "avg_launch_us": ms * 1e3, "bound": "alu", "achieved": tops, "peak": VALU_PEAK_TOPS,
+           "unit": "T lane-ops/s", "frac": tops / VALU_PEAK_TOPS, "algorithmic_ops_per_launch": ops}
+    mhz = load_clock_mhz()
+    if mhz:
+        row["load_clock_mhz"] = mhz
+        row["peak_at_load_clock"] = 256 * 64 * mhz * 1e6 / 1e12
+        row["frac_at_load_clock"] = tops / row["peak_at_load_clock"]
+    if extra:
+        row.update(extra)
+    return row
+
+
 def time_exchange(wl, bits, bucket, lr, steps, warmup):
     """The second leg of Algorithm 1: mqg_aggregate_requantize (server) + mqg_dequantize_update (worker).
 
@@ -268,11 +392,8 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
         (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9,
          m_ms * 1e3, m_bytes / (m_ms * 1e-3) / 1e9))
     return {
-        "requantize": {"kernel": "requantize_wave_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
-                       "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T lane-ops/s",
-                       "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
-                       "algorithmic_ops_per_launch": r_ops, "algorithmic_bytes_per_launch": r_bytes,
-                       "hbm_gbs": r_bytes / (r_ms * 1e-3) / 1e9},
+        "requantize": alu_row("requantize_wave_kernel", r_ms, r_ops,
+                              {"algorithmic_bytes_per_launch": r_bytes, "hbm_gbs": r_bytes / (r_ms * 1e-3) / 1e9}),
         "dequantize_update": {"kernel": "aggregate_update_rows_kernel (W=1)", "avg_launch_us": d_ms * 1e3, "bound": "hbm",
                               "achieved": d_bytes / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": d_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -413,10 +534,7 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
             "aggregate_update_minmax": row("aggregate_update_minmax_kernel", a_bytes, a_ms),
             "sum_squares": row("sum_squares_kernel", s_bytes, s_ms),
             "quantize_minmax_tensor": row("tensor_range_kernel + quantize_minmax_wave_kernel", t_bytes, t_ms),
-            "requantize_minmax": {"kernel": "requantize_minmax_kernel", "avg_launch_us": r_ms * 1e3, "bound": "alu",
-                                  "achieved": r_ops / (r_ms * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS,
-                                  "unit": "T lane-ops/s", "frac": r_ops / (r_ms * 1e-3) / 1e12 / VALU_PEAK_TOPS,
-                                  "algorithmic_ops_per_launch": r_ops}}
+            "requantize_minmax": alu_row("requantize_minmax_kernel", r_ms, r_ops)}
 
 
 def cpu_baseline(bits, bucket, W, lr, sample_n, steps):
@@ -467,8 +585,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=100,
-                    help="untimed steps; the chip needs ~30 ms of sustained load before its clocks settle")
+    ap.add_argument("--warmup", type=int, default=100, help="untimed steps right before the timed region")
+    ap.add_argument("--condition-ms", type=float, default=100.0,
+                    help="milliseconds of untimed steps of the same loop before the counted warm-up (0: none); the "
+                         "same --steps / --warmup are also timed BEFORE them and reported as `cold`")
     ap.add_argument("--n", type=int, default=100_000_000)
     ap.add_argument("--workers", type=int, default=8)
     ap.add_argument("--bits", type=int, default=4)
@@ -511,18 +631,44 @@ def main():
     wl = Workload(n, W, dev)
 
     transient_series = transient(wl, bits, bucket, args.lr, args.transient) if args.transient > 0 else None
+    qb, ab = quantize_bytes(n, bits, bucket), aggregate_bytes(n, bits, bucket, W)
+
+    # Cold region: what the same flags measure with no conditioning, i.e. right after the inputs were
+    # generated; then untimed conditioning steps; then the counted warm-up and the timed region.
+    cold = None
+    conditioning = {"ms": 0.0, "steps": 0}
+    if args.condition_ms > 0:
+        c_ms, c_q, c_a = time_config(wl, bits, bucket, args.lr, args.steps, args.warmup)
+        c_spread = dict(time_config.last)
+        cold = {"what": "the same --steps / --warmup timed right after input generation, before the conditioning steps",
+                "ms_per_step": c_ms, "value": 4.0 * n * W / (c_ms * 1e-3) / 1e9,
+                "quantize_us": c_q * 1e3, "quantize_hbm_frac": qb / (c_q * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "aggregate_us": c_a * 1e3, "aggregate_hbm_frac": ab / (c_a * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "quantize_us_first5": c_spread["quantize_us_first5"], "quantize_us_median": c_spread["quantize_us_median"],
+                "quantize_us_min": c_spread["quantize_us_min"]}
+        log("cold (no conditioning): step %.3f ms | quantize %.1f us (%.1f%%) | aggregate %.1f us (%.1f%%)" %
+            (c_ms, c_q * 1e3, 100 * cold["quantize_hbm_frac"], c_a * 1e3, 100 * cold["aggregate_hbm_frac"]))
+        done, took = condition(wl, bits, bucket, args.lr, args.condition_ms)
+        conditioning = {"ms": took, "steps": done,
+                        "what": "untimed steps of the same loop between the cold region and the counted warm-up: after an "
+                                "idle gap the chip passes through a throttled state for about 20 ms (profiles/transient_*.md)"}
     ms_step, q_ms, a_ms = time_config(wl, bits, bucket, args.lr, args.steps, args.warmup)
     value = 4.0 * n * W / (ms_step * 1e-3) / 1e9
-    qb, ab = quantize_bytes(n, bits, bucket), aggregate_bytes(n, bits, bucket, W)
     q_gbs, a_gbs = qb / (q_ms * 1e-3) / 1e9, ab / (a_ms * 1e-3) / 1e9
-    log("step %.3f ms | quantize %.1f us/launch %.0f GB/s | aggregate %.1f us %.0f GB/s" %
-        (ms_step, q_ms * 1e3, q_gbs, a_ms * 1e3, a_gbs))
+    log("step %.3f ms | quantize %.1f us/launch %.0f GB/s (%.1f%%) | aggregate %.1f us %.0f GB/s (%.1f%%)" %
+        (ms_step, q_ms * 1e3, q_gbs, 100 * q_gbs / HBM_PEAK_GBS, a_ms * 1e3, a_gbs, 100 * a_gbs / HBM_PEAK_GBS))
 
     spread = dict(time_config.last)
-    copy_gbs = copy_ceiling(wl)
-    log("plain copy (torch copy_) of one gradient buffer: %.0f GB/s = %.1f%% of peak" % (copy_gbs, 100 * copy_gbs / HBM_PEAK_GBS))
+    ceil = stream_ceilings(wl, bits, bucket)
+    log("streaming ceilings: quantize mix %.1f us = %.0f GB/s (%.1f%% of peak), update mix %.1f us = %.0f GB/s (%.1f%%), "
+        "torch copy_ %.0f GB/s (%.1f%%)" %
+        (ceil["quantize_mix"]["us"], ceil["quantize_mix"]["gbs"], 100 * ceil["quantize_mix"]["frac_of_peak"],
+         ceil["update_mix"]["us"], ceil["update_mix"]["gbs"], 100 * ceil["update_mix"]["frac_of_peak"],
+         ceil["torch_copy"]["gbs"], 100 * ceil["torch_copy"]["frac_of_peak"]))
 
-    q_traffic, a_traffic = MEASURED_TRAFFIC.get((n, W, bits, bucket), (None, None))
+    traffic = measured_traffic(n, W, bits, bucket)
+    q_traffic = traffic["quantize_wave_kernel"] if traffic else None
+    a_traffic = traffic["aggregate_update_rows_kernel"] if traffic else None
     out = {
         "metric": "GB/s fp32 gradient quantize+pack and unpack+aggregate+update; % HBM peak",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -535,16 +681,21 @@ def main():
         # the quantize kernel runs W times per step and is the dominant kernel by time
         "roofline": {"bound": "hbm", "kernel": "quantize_wave_kernel", "achieved": q_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": q_gbs / HBM_PEAK_GBS, "traffic": q_traffic,
+                     "traffic_source": ("profiles/%s at commit %s" % (os.path.basename(TRAFFIC_PROFILE), traffic.get("commit"))) if traffic else None,
                      "algorithmic_bytes_per_launch": qb, "avg_launch_us": q_ms * 1e3,
                      "median_launch_us": spread["quantize_us_median"], "min_launch_us": spread["quantize_us_min"],
-                     "frac_of_copy_ceiling": q_gbs / copy_gbs},
+                     "first5_launch_us": spread["quantize_us_first5"],
+                     "frac_of_stream_ceiling": q_gbs / ceil["quantize_mix"]["gbs"]},
         "roofline_aggregate": {"bound": "hbm", "kernel": "aggregate_update_rows_kernel", "achieved": a_gbs,
                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a_gbs / HBM_PEAK_GBS, "traffic": a_traffic,
                                "algorithmic_bytes_per_launch": ab, "avg_launch_us": a_ms * 1e3,
                                "median_launch_us": spread["aggregate_us_median"], "min_launch_us": spread["aggregate_us_min"],
-                               "frac_of_copy_ceiling": a_gbs / copy_gbs},
+                               "first5_launch_us": spread["aggregate_us_first5"],
+                               "frac_of_stream_ceiling": a_gbs / ceil["update_mix"]["gbs"]},
         "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "copy_ceiling": {"kernel": "torch copy_ of one gradient buffer", "gbs": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS},
+        "conditioning": conditioning,
+        "cold": cold,
+        "stream_ceiling": ceil,
     }
 
     if transient_series is not None:
