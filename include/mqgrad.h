@@ -264,10 +264,10 @@ mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, con
 mqg_status mqg_sum_squares(const float* grad, uint64_t n, double* sumsq_out, void* stream);
 
 typedef struct {
-    uint32_t base_bits;     /* paper: 2 */
-    double norm_per_bit;    /* paper: 0.0005 */
-    uint32_t bits_min;      /* paper: 2 */
-    uint32_t bits_max;      /* paper: 8 */
+    uint32_t base_bits;     /* 2: this build's reading (the published Section 4.1 names the baseline, not its rule) */
+    double norm_per_bit;    /* 0.0005: this build's reading, as above */
+    uint32_t bits_min;      /* paper's range of widths: 2 */
+    uint32_t bits_max;      /* paper's range of widths: 8 */
 } mqg_adaptive_config;
 
 void mqg_adaptive_default_config(mqg_adaptive_config* cfg);
@@ -295,9 +295,11 @@ typedef struct {
     double eta;             /* SARSA step size; paper: 0.1 */
     double reward_scale;    /* gamma of the reward equation; paper: 300 */
     double discount;        /* gamma of the SARSA update; the paper gives no value */
+    uint32_t follow_taken_action;  /* 0 (paper): the state's width n_t moves by the greedy action (Transition);
+                                      1: by the action that was taken, so the announced width never drops back */
 } mqg_mdp_config;
 
-/* Fill cfg with the paper's values (Section 4.1) and discount = 0.9. */
+/* Fill cfg with the paper's values (Section 4.1), discount = 0.9 and follow_taken_action = 0. */
 void mqg_mdp_default_config(mqg_mdp_config* cfg);
 
 /* Create / destroy an agent.  Returns NULL for an invalid configuration
@@ -323,6 +325,17 @@ uint32_t mqg_mdp_current_bits(const mqg_mdp* agent);
 void mqg_mdp_smoothed_losses(const mqg_mdp* agent, double* out);
 double mqg_mdp_last_reward(const mqg_mdp* agent);
 uint64_t mqg_mdp_decisions(const mqg_mdp* agent);
+
+/* The parameter vector v of the Q network (Section 3.3, Q function), for checkpointing an agent and for
+ * tests of the SARSA update (Algorithm 2): mqg_mdp_num_weights doubles laid out as
+ * [W1: hidden x window, row by row | b1: hidden | W2: (bits_max - bits_min + 1) x hidden | b2].
+ * mqg_mdp_q_values evaluates the network as it stands: `input` holds `window` values (the smoothed
+ * losses divided by the first loss), `out` receives one value per bit width; Q(s, a) is
+ * out[n - bits_min + a].  NULL arguments are ignored. */
+uint32_t mqg_mdp_num_weights(const mqg_mdp* agent);
+void mqg_mdp_get_weights(const mqg_mdp* agent, double* out);
+void mqg_mdp_set_weights(mqg_mdp* agent, const double* in);
+void mqg_mdp_q_values(const mqg_mdp* agent, const double* input, double* out);
 
 #ifdef __cplusplus
 }

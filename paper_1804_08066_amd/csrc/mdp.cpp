@@ -106,8 +106,9 @@ struct mqg_mdp {
         std::vector<double> hid, q;
         const std::vector<double> in = network_input();
         const bool have_prev = decisions > 0;
-        // Transition: n_t follows the greedy action of the previous state
-        if (have_prev) n_t = prev_n + prev_greedy;
+        // Transition: n_t follows the greedy action of the previous state (or, when asked to, the action
+        // that was taken, which makes the announced width monotone)
+        if (have_prev) n_t = prev_n + (cfg.follow_taken_action ? prev_action : prev_greedy);
         // Reward of the previous action, from the losses and the time of the period just ended
         double reward = 0.0;
         if (have_prev) {
@@ -167,6 +168,7 @@ void mqg_mdp_default_config(mqg_mdp_config* cfg) {
     cfg->eta = 0.1;
     cfg->reward_scale = 300.0;
     cfg->discount = 0.9;
+    cfg->follow_taken_action = 0;
 }
 
 mqg_mdp* mqg_mdp_create(const mqg_mdp_config* cfg) {
@@ -254,6 +256,38 @@ void mqg_mdp_smoothed_losses(const mqg_mdp* agent, double* out) {
 double mqg_mdp_last_reward(const mqg_mdp* agent) { return agent ? agent->last_reward : 0.0; }
 
 uint64_t mqg_mdp_decisions(const mqg_mdp* agent) { return agent ? agent->decisions : 0u; }
+
+// ---- the Q network's parameter vector v, laid out [W1 row by row, b1, W2 row by row, b2] ------------
+
+uint32_t mqg_mdp_num_weights(const mqg_mdp* agent) {
+    if (!agent) return 0u;
+    return (uint32_t)(agent->w1.size() + agent->b1.size() + agent->w2.size() + agent->b2.size());
+}
+
+void mqg_mdp_get_weights(const mqg_mdp* agent, double* out) {
+    if (!agent || !out) return;
+    for (const std::vector<double>* part : {&agent->w1, &agent->b1, &agent->w2, &agent->b2}) {
+        for (double x : *part) *out++ = x;
+    }
+}
+
+void mqg_mdp_set_weights(mqg_mdp* agent, const double* in) {
+    if (!agent || !in) return;
+    for (std::vector<double>* part : {&agent->w1, &agent->b1, &agent->w2, &agent->b2}) {
+        for (double& x : *part) x = *in++;
+    }
+}
+
+void mqg_mdp_q_values(const mqg_mdp* agent, const double* input, double* out) {
+    if (!agent || !input || !out) return;
+    try {
+        const std::vector<double> in(input, input + agent->cfg.window);
+        std::vector<double> hid, q;
+        agent->forward(in, hid, q);
+        for (uint32_t o = 0; o < agent->n_out; ++o) out[o] = q[o];
+    } catch (...) {   // allocation failure: nothing crosses the C boundary
+    }
+}
 
 // ---- the "Adaptive" baseline's rule (Section 4.1): bits from the mean gradient norm ----------------
 

@@ -24,6 +24,7 @@ EXPORTS = [
     "mqg_adaptive_bits",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step", "mqg_mdp_step_workers",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
+    "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
 ]
 
 
@@ -37,7 +38,7 @@ class MdpConfig(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("bits_min", C.c_uint32), ("bits_max", C.c_uint32),
                 ("window", C.c_uint32), ("decide_every", C.c_uint32), ("hidden", C.c_uint32),
                 ("alpha", C.c_double), ("epsilon", C.c_double), ("eta", C.c_double),
-                ("reward_scale", C.c_double), ("discount", C.c_double)]
+                ("reward_scale", C.c_double), ("discount", C.c_double), ("follow_taken_action", C.c_uint32)]
 
 
 class AdaptiveConfig(C.Structure):
@@ -68,6 +69,9 @@ def lib():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build()
+    elif _build.needs_build():
+        import warnings
+        warnings.warn("libmqgrad.so is older than its sources: run paper_1804_08066_amd/build.py (loading the stale library)")
     L = C.CDLL(_build.LIB)
     vp, u32, u64, f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_float
     L.mqg_status_string.argtypes = [C.c_int]
@@ -130,6 +134,14 @@ def lib():
     L.mqg_mdp_last_reward.restype = C.c_double
     L.mqg_mdp_decisions.argtypes = [vp]
     L.mqg_mdp_decisions.restype = u64
+    L.mqg_mdp_num_weights.argtypes = [vp]
+    L.mqg_mdp_num_weights.restype = u32
+    L.mqg_mdp_get_weights.argtypes = [vp, C.POINTER(C.c_double)]
+    L.mqg_mdp_get_weights.restype = None
+    L.mqg_mdp_set_weights.argtypes = [vp, C.POINTER(C.c_double)]
+    L.mqg_mdp_set_weights.restype = None
+    L.mqg_mdp_q_values.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.mqg_mdp_q_values.restype = None
     _lib = L
     return L
 
@@ -525,6 +537,28 @@ class Mdp:
     @property
     def decisions(self):
         return int(lib().mqg_mdp_decisions(self._h))
+
+    @property
+    def weights(self):
+        """The Q network's parameter vector [W1 | b1 | W2 | b2] as a list of floats."""
+        out = (C.c_double * lib().mqg_mdp_num_weights(self._h))()
+        lib().mqg_mdp_get_weights(self._h, out)
+        return list(out)
+
+    @weights.setter
+    def weights(self, values):
+        count = lib().mqg_mdp_num_weights(self._h)
+        if len(values) != count:
+            raise ValueError("expected %d weights" % count)
+        lib().mqg_mdp_set_weights(self._h, (C.c_double * count)(*[float(v) for v in values]))
+
+    def q_values(self, network_input):
+        """One value per bit width for `window` inputs (smoothed losses divided by the first loss)."""
+        if len(network_input) != self.cfg.window:
+            raise ValueError("expected %d inputs" % self.cfg.window)
+        out = (C.c_double * (self.cfg.bits_max - self.cfg.bits_min + 1))()
+        lib().mqg_mdp_q_values(self._h, (C.c_double * self.cfg.window)(*[float(v) for v in network_input]), out)
+        return list(out)
 
     def close(self):
         if self._h:

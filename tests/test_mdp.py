@@ -1,16 +1,27 @@
-"""Host-side MDP agent (Section 3.3, Algorithm 2): the library's C++ against a hand-computed example,
-the paper's stated properties, and the plain numpy restatement in oracle/mdp_ref.py.  CPU only.
+"""Host-side MDP agent (Section 3.3, Algorithm 2).  CPU only.
 
-What stays unpinned: the learning dynamics depend on values the paper does not give (SARSA discount,
-weight initialisation, input normalisation); they are checked only for agreement between the two
-independent implementations of the same readings."""
+Both implementations -- the library's C++ and oracle/mdp_ref.py -- are checked against what the paper and
+the mathematics fix: Eq. (1), the regression slope and the reward against a hand-computed example; one
+SARSA step of Algorithm 2 (line 4) against three cases worked by hand on a tiny network
+(tests/golden/mdp_td_step.txt: which output is Q(s, a), the greedy action in the Transition against the
+taken one in the announced width, the dead ReLU unit, the maximum width); the update direction against
+central finite differences of Q for every weight; the paper's constants and stated properties.  What the
+paper does not give (discount, initialisation, input normalisation) are parameters of both."""
 import os
 
 import numpy as np
 import pytest
 
-from oracle import mdp_ref
 from paper_1804_08066_amd import mqgrad, workloads
+
+if os.environ.get("MQGRAD_MDP_REF"):
+    # load another copy of the reference (used to check that planted mistakes fail the checks below)
+    import importlib.util
+    _spec = importlib.util.spec_from_file_location("mdp_ref_override", os.environ["MQGRAD_MDP_REF"])
+    mdp_ref = importlib.util.module_from_spec(_spec)
+    _spec.loader.exec_module(mdp_ref)
+else:
+    from oracle import mdp_ref
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "mdp_worked_example.txt")
 
@@ -31,6 +42,18 @@ def test_reference_statistics_match_the_hand_computed_example():
     assert sm == g["smoothed"]
     assert abs(mdp_ref.slope(g["smoothed"]) - g["beta"][0]) < 1e-12
     assert abs(-(1 / g["cost_ms"][0]) * mdp_ref.slope(g["smoothed"]) * g["gamma"][0] - g["reward"][0]) < 1e-12
+
+
+def test_moving_average_weights_the_new_loss_by_alpha():
+    # alpha = 0.25: the two weights of Eq. (1) are not interchangeable
+    g = golden()
+    assert mdp_ref.moving_average(g["losses2"], g["alpha2"][0], g["start"][0]) == g["smoothed2"]
+    for make in (lambda **kw: mqgrad.Mdp(**kw), lambda **kw: mdp_ref.MdpRef(**kw)):
+        agent = make(alpha=g["alpha2"][0], window=3, decide_every=3)
+        for L in g["losses2"]:                 # the first loss equals the starting value of the average
+            agent.step(L, 1.0)
+        window = agent.smoothed_losses if hasattr(agent, "smoothed_losses") else agent.window
+        assert list(window) == g["smoothed2"]
 
 
 def test_library_moving_average_slope_and_reward_match_the_hand_computed_example():
@@ -98,6 +121,206 @@ def test_library_agent_matches_the_numpy_restatement(cfg):
         assert np.allclose(lib.smoothed_losses, ref.window, rtol=1e-13, atol=0)
         assert abs(lib.last_reward - ref.last_reward) <= 1e-9 * max(1.0, abs(ref.last_reward))
     assert lib.decisions == ref.decisions
+    assert np.allclose(np.array(lib.weights), ref.v, rtol=1e-9, atol=1e-12)   # 60 SARSA updates later
+
+
+TD_GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "mdp_td_step.txt")
+TINY = dict(window=2, hidden=2, bits_min=2, bits_max=3, decide_every=2, alpha=1.0, eta=0.1, discount=0.5,
+            reward_scale=300.0)
+
+
+class LibAgent:
+    """The library's agent behind the few calls the checks below need."""
+
+    def __init__(self, **cfg):
+        self.a = mqgrad.Mdp(**cfg)
+
+    def step(self, loss, ms):
+        return self.a.step(loss, ms)
+
+    n = property(lambda self: self.a.current_bits)
+    reward = property(lambda self: self.a.last_reward)
+    window = property(lambda self: self.a.smoothed_losses)
+
+    def get_v(self):
+        return np.array(self.a.weights)
+
+    def set_v(self, v):
+        self.a.weights = list(v)
+
+    def q(self, x):
+        return np.array(self.a.q_values(list(x)))
+
+
+class RefAgent:
+    def __init__(self, **cfg):
+        self.a = mdp_ref.MdpRef(**cfg)
+
+    def step(self, loss, ms):
+        return self.a.step(loss, ms)
+
+    n = property(lambda self: self.a.n_t)
+    reward = property(lambda self: self.a.last_reward)
+    window = property(lambda self: list(self.a.window))
+
+    def get_v(self):
+        return self.a.v.copy()
+
+    def set_v(self, v):
+        self.a.v = np.array(v, dtype=np.float64)
+
+    def q(self, x):
+        return mdp_ref.q_function(self.a.v, self.a.shape, np.array(x, dtype=np.float64))
+
+
+AGENTS = [LibAgent, RefAgent]
+
+
+def td_golden():
+    d = {}
+    for line in open(TD_GOLDEN):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        d[k] = [float(t) for t in v]
+    return d
+
+
+@pytest.mark.parametrize("Agent", AGENTS)
+@pytest.mark.parametrize("case", ["A", "B", "C"])
+def test_one_sarsa_step_matches_the_hand_computed_cases(Agent, case):
+    # Algorithm 2, line 4, with Q(s, a) = the output of width n + a (Section 4.1) and the Transition's
+    # greedy action: every number in the golden file is derived by hand in its comments
+    g = td_golden()
+    ag = Agent(seed=3, epsilon=g[case + ".epsilon"][0], **TINY)
+    ag.set_v(g[case + ".weights"])
+    bits, ns = [], []
+    for L, ms in zip(g["losses"], g["elapsed_ms"]):
+        bits.append(ag.step(L, ms))
+        ns.append(ag.n)
+    assert bits == g[case + ".bits"]
+    assert ns == g[case + ".n"]
+    assert abs(ag.reward - g["reward"][0]) < 1e-12
+    assert np.allclose(ag.get_v(), g[case + ".after"], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("Agent", AGENTS)
+@pytest.mark.parametrize("seed", [1, 4, 11])
+def test_update_direction_is_the_finite_difference_gradient_of_q(Agent, seed):
+    # v_new - v_old = eta * TD * dQ(s_{t-1}, a_{t-1})/dv: the right-hand side from central differences of
+    # the network's own output, weight by weight (Q is piecewise linear in each single weight, so the
+    # difference quotient is exact up to rounding).
+    cfg = dict(seed=seed, epsilon=0.5, decide_every=1, alpha=0.3, eta=0.1, discount=0.7, bits_min=2, bits_max=8)
+    ag = Agent(**cfg)
+    probe = Agent(**cfg)
+    losses = [2.0, 1.7, 1.9]
+    first = losses[0]
+    checked_dead = checked_live = False
+    prev = None
+    for m, L in enumerate(losses):
+        v_before = ag.get_v()
+        bits = ag.step(L, 7.0)
+        x = np.array(ag.window) / first
+        n = ag.n
+        cur = (x, n, bits - n)
+        if prev is not None:
+            x0, n0, a0 = prev
+            o0, o1 = n0 - 2 + a0, n - 2 + (bits - n)
+            probe.set_v(v_before)
+            td = ag.reward + 0.7 * probe.q(x)[o1] - probe.q(x0)[o0]
+            grad = np.zeros_like(v_before)
+            h = 1e-6
+            for i in range(len(v_before)):
+                e = np.zeros_like(v_before)
+                e[i] = h
+                probe.set_v(v_before + e)
+                up = probe.q(x0)[o0]
+                probe.set_v(v_before - e)
+                grad[i] = (up - probe.q(x0)[o0]) / (2 * h)
+            want = 0.1 * td * grad
+            got = ag.get_v() - v_before
+            assert np.allclose(got, want, rtol=0, atol=1e-9 * max(1.0, abs(td))), (m, np.abs(got - want).max())
+            assert abs(td) > 1e-3 and np.abs(want).max() > 1e-6          # the step is not vacuous
+            b1_grad = grad[10 * 5:10 * 5 + 10]                            # dQ/db1: zero exactly for dead units
+            checked_dead |= bool(np.any(b1_grad == 0.0))
+            checked_live |= bool(np.any(b1_grad != 0.0))
+        prev = cur
+    assert checked_live
+    if seed == 1:
+        assert checked_dead, "this seed is chosen so that some hidden unit is dead at the previous state"
+
+
+@pytest.mark.parametrize("Agent", AGENTS)
+def test_state_width_follows_the_greedy_action_and_the_sent_width_the_taken_one(Agent):
+    # epsilon = 1: every decision takes the action the greedy policy would NOT take.  The Transition
+    # moves n_t by argmax_a Q(s_{t-1}, a) all the same (Section 3.3), while Algorithm 2 returns n_t + a_t.
+    cfg = dict(seed=7, epsilon=1.0, decide_every=1, alpha=0.5, bits_min=2, bits_max=8)
+    ag = Agent(**cfg)
+    losses = workloads.synthetic_loss_sequence(40, seed=5)
+    first = losses[0]
+    expect_n = 2
+    differed = 0
+    for L in losses:
+        v = ag.get_v()
+        probe = Agent(**cfg)
+        probe.set_v(v)
+        bits = ag.step(L, 3.0)
+        assert ag.n == expect_n
+        q = probe.q(np.array(ag.window) / first)
+        greedy = 0 if expect_n == 8 else int(q[expect_n - 2 + 1] > q[expect_n - 2])
+        taken = 0 if expect_n == 8 else 1 - greedy
+        assert bits == expect_n + taken
+        differed += int(taken != greedy)
+        expect_n += greedy
+    assert differed >= 5
+
+
+@pytest.mark.parametrize("Agent", AGENTS)
+def test_equal_q_values_keep_the_width(Agent):
+    # Transition: "if Q(s, 0) >= Q(s, 1) MQGrad keeps n".  All weights 0.25 make every output equal.
+    ag = Agent(seed=0, epsilon=0.0, decide_every=1)
+    ag.set_v([0.25] * len(ag.get_v()))
+    assert ag.q([1.0] * 5)[0] == ag.q([1.0] * 5)[1]
+    assert ag.step(1.0, 1.0) == 2 and ag.n == 2
+    ag.set_v([0.25] * len(ag.get_v()))         # undo whatever the next update would do before it decides again
+    assert ag.step(1.0, 1.0) == 2 and ag.n == 2
+
+
+@pytest.mark.parametrize("Agent", AGENTS)
+def test_following_the_taken_action_makes_the_sent_width_monotone(Agent):
+    ag = Agent(seed=2, epsilon=0.5, decide_every=1, follow_taken_action=1)
+    prev = 0
+    for L in workloads.synthetic_loss_sequence(120, seed=2):
+        bits = ag.step(L, 4.0)
+        assert bits >= prev and 2 <= bits <= 8
+        prev = bits
+    assert prev > 2
+
+
+def test_reference_gradient_is_the_finite_difference_of_its_q_function():
+    rng = np.random.default_rng(0)
+    shape = (5, 10, 7)
+    v = rng.uniform(-0.5, 0.5, size=5 * 10 + 10 + 7 * 10 + 7)
+    x = rng.uniform(0.2, 1.2, size=5)
+    for o in range(7):
+        g = mdp_ref.q_gradient(v, shape, x, o)
+        for i in range(len(v)):
+            e = np.zeros_like(v)
+            e[i] = 1e-6
+            fd = (mdp_ref.q_function(v + e, shape, x)[o] - mdp_ref.q_function(v - e, shape, x)[o]) / 2e-6
+            assert abs(fd - g[i]) < 1e-8
+
+
+def test_weight_vector_round_trips_through_the_library():
+    a = mqgrad.Mdp(seed=5)
+    v = a.weights
+    assert len(v) == 10 * 5 + 10 + 7 * 10 + 7 and all(-0.1 <= x < 0.1 for x in v)
+    # the same generator on both sides: the reference starts from the same vector
+    assert np.array_equal(np.array(v), mdp_ref.MdpRef(seed=5).v)
+    a.weights = [0.25] * len(v)
+    assert a.weights == [0.25] * len(v)
+    # all weights 0.25, inputs 1: hidden = 5 * 0.25 + 0.25 = 1.5, every output 10 * 0.25 * 1.5 + 0.25 = 4
+    assert a.q_values([1.0] * 5) == [4.0] * 7
 
 
 def test_width_is_capped_at_the_maximum():
