@@ -263,6 +263,25 @@ mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, con
  * n = 0 stores 0. */
 mqg_status mqg_sum_squares(const float* grad, uint64_t n, double* sumsq_out, void* stream);
 
+/* The same sum for up to MQG_MAX_SUMSQ_TENSORS tensors in one call -- the W workers' gradients of an
+ * iteration, or a model's layers (the Adaptive rule takes the norm of every worker's gradient, Section
+ * 4.1) -- and reproducible to the bit: every workgroup stores one partial sum and a finishing kernel adds
+ * the partial sums of a tensor in a fixed order, so sumsq_out[k] depends on (items[k].n, the values) only.
+ *   items       HOST array of `count` tensors (read during the call only); n = 0 gives 0.
+ *   workspace   device, mqg_sum_squares_workspace_bytes(count) bytes of scratch memory, 8-byte aligned;
+ *               contents on entry are of no interest, contents on return are unspecified.  Calls that
+ *               share a workspace must not overlap.
+ *   sumsq_out   device, `count` doubles, 8-byte aligned, overwritten.
+ * Errors: MQG_EINVAL (count > MQG_MAX_SUMSQ_TENSORS, NULL pointer), MQG_EALIGN, MQG_ELAUNCH. */
+#define MQG_MAX_SUMSQ_TENSORS 64u
+typedef struct {
+    const float* grad;   /* device, n floats */
+    uint64_t n;
+} mqg_sumsq_item;
+size_t mqg_sum_squares_workspace_bytes(uint32_t count);
+mqg_status mqg_sum_squares_batch(const mqg_sumsq_item* items, uint32_t count, void* workspace, double* sumsq_out,
+                                 void* stream);
+
 typedef struct {
     uint32_t base_bits;     /* 2: this build's reading (the published Section 4.1 names the baseline, not its rule) */
     double norm_per_bit;    /* 0.0005: this build's reading, as above */

@@ -463,4 +463,30 @@ mqg_status mqg_sum_squares(const float* grad, uint64_t n, double* sumsq_out, voi
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 
+size_t mqg_sum_squares_workspace_bytes(uint32_t count) {
+    return (size_t)count * mqg::sum_squares_batch_blocks() * sizeof(double);
+}
+
+mqg_status mqg_sum_squares_batch(const mqg_sumsq_item* items, uint32_t count, void* workspace, double* sumsq_out,
+                                 void* stream) {
+    if (count == 0u) return MQG_OK;
+    if (items == nullptr || workspace == nullptr || sumsq_out == nullptr || count > MQG_MAX_SUMSQ_TENSORS) return MQG_EINVAL;
+    mqg::SumSquaresBatch b;
+    for (uint32_t k = 0; k < count; ++k) {
+        if (items[k].n > 0 && items[k].grad == nullptr) return MQG_EINVAL;
+        if (items[k].n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+        if (items[k].n > 0 && misaligned4(items[k].grad)) return MQG_EALIGN;
+        b.grad[k] = items[k].grad;
+        b.n[k] = items[k].n;
+    }
+    for (uint32_t k = count; k < mqg::kMaxSumTensors; ++k) {
+        b.grad[k] = nullptr;
+        b.n[k] = 0;
+    }
+    if (misaligned8(workspace) || misaligned8(sumsq_out)) return MQG_EALIGN;
+    const hipError_t err = mqg::launch_sum_squares_batch(b, count, static_cast<double*>(workspace), sumsq_out,
+                                                         static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
 }  // extern "C"

@@ -104,4 +104,13 @@ hipError_t launch_requantize_minmax(const RequantArgs& a, hipStream_t stream);
 hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, hipStream_t stream);
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream);
 
+// Sums of squares of several tensors in one launch, each added up in a fixed order.
+constexpr uint32_t kMaxSumTensors = 64;
+struct SumSquaresBatch {
+    const float* grad[kMaxSumTensors];
+    uint64_t n[kMaxSumTensors];
+};
+uint32_t sum_squares_batch_blocks();   // partial sums (doubles of scratch memory) per tensor
+hipError_t launch_sum_squares_batch(const SumSquaresBatch& b, uint32_t count, double* partials, double* out, hipStream_t stream);
+
 }  // namespace mqg

@@ -418,23 +418,26 @@ __global__ __launch_bounds__(kSumThreads) void tensor_range_kernel(const float* 
 
 // ---- sum of squares -------------------------------------------------------------------------------
 // Squares of fp32 values are exact in fp64; every lane adds its share in fp64, lanes and waves are
-// combined by a butterfly and through LDS, and each workgroup adds one fp64 number to *out (whose
-// rounding depends on the order in which the workgroups arrive: about 1e-16 relative).
+// combined by a butterfly and through LDS.  Two ways to finish: mqg_sum_squares adds one fp64 number
+// per workgroup to *out with an atomic (its rounding depends on the order in which the workgroups
+// arrive: about 1e-16 relative); the batched form stores one partial sum per workgroup and a second
+// kernel adds them in a fixed order, which makes the result reproducible to the bit.
 
 __global__ void clear_f64_kernel(double* out) { *out = 0.0; }
 
-__global__ __launch_bounds__(kSumThreads) void sum_squares_kernel(const float* __restrict__ g, const uint64_t n,
-                                                                  double* out) {
-    __shared__ double s_part[kSumThreads / 64];
+// The calling workgroup's share of sum g[i]^2 (workgroup `block` of `nblocks`); the value is returned
+// in thread 0.  The order of every addition is a function of (n, nblocks) only.
+__device__ __forceinline__ double block_sum_squares(const float* __restrict__ g, const uint64_t n, const uint32_t block,
+                                                    const uint32_t nblocks, double* s_part) {
     const uint32_t tid = threadIdx.x;
-    const uint64_t gtid = (uint64_t)blockIdx.x * kSumThreads + tid;
-    const uint64_t stride = (uint64_t)gridDim.x * kSumThreads;
+    const uint64_t gtid = (uint64_t)block * kSumThreads + tid;
+    const uint64_t stride = (uint64_t)nblocks * kSumThreads;
     double acc = 0.0;
     const v4f_a4* __restrict__ g4 = reinterpret_cast<const v4f_a4*>(g);   // 128-bit loads need dword alignment only
     const uint64_t nq = n >> 2;
-    // a workgroup reads 32 KB contiguous pieces (four float4 per lane in flight), pieces gridDim.x apart
+    // a workgroup reads 32 KB contiguous pieces (four float4 per lane in flight), pieces nblocks apart
     const uint64_t pieces = nq / (4u * kSumThreads);
-    for (uint64_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
+    for (uint64_t pc = block; pc < pieces; pc += nblocks) {
         const v4f_a4* __restrict__ src = g4 + pc * (4u * kSumThreads) + tid;
         v4f t[4];
 #pragma unroll
@@ -458,12 +461,39 @@ __global__ __launch_bounds__(kSumThreads) void sum_squares_kernel(const float* _
     for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
     if ((tid & 63u) == 0u) s_part[tid >> 6] = acc;
     __syncthreads();
+    double t = 0.0;
     if (tid == 0u) {
-        double t = 0.0;
 #pragma unroll
         for (int w = 0; w < kSumThreads / 64; ++w) t += s_part[w];
-        atomicAdd(out, t);
     }
+    return t;
+}
+
+__global__ __launch_bounds__(kSumThreads) void sum_squares_kernel(const float* __restrict__ g, const uint64_t n,
+                                                                  double* out) {
+    __shared__ double s_part[kSumThreads / 64];
+    const double t = block_sum_squares(g, n, blockIdx.x, gridDim.x, s_part);
+    if (threadIdx.x == 0u) atomicAdd(out, t);
+}
+
+// Batched, ordered form.  blockIdx.y = tensor, blockIdx.x = workgroup of the tensor; every workgroup
+// stores its partial sum (0 for a workgroup that has nothing to read), nothing is accumulated in memory.
+__global__ __launch_bounds__(kSumThreads) void sum_squares_partial_kernel(const SumSquaresBatch b, double* __restrict__ partials) {
+    __shared__ double s_part[kSumThreads / 64];
+    const uint32_t k = blockIdx.y;
+    const double t = block_sum_squares(b.grad[k], b.n[k], blockIdx.x, gridDim.x, s_part);
+    if (threadIdx.x == 0u) partials[(uint64_t)k * gridDim.x + blockIdx.x] = t;
+}
+
+// One wave per tensor: lane l adds partials l, l + 64, ... in that order, then the butterfly.
+__global__ __launch_bounds__(64) void sum_squares_finish_kernel(const double* __restrict__ partials, const uint32_t nblocks,
+                                                                double* __restrict__ out) {
+    const double* __restrict__ p = partials + (uint64_t)blockIdx.x * nblocks;
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < nblocks; i += 64u) acc += p[i];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if (threadIdx.x == 0u) out[blockIdx.x] = acc;
 }
 
 template <int R, int NT>
@@ -554,6 +584,18 @@ hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, 
     hipLaunchKernelGGL(range_finish_kernel, dim3(1), dim3(1), 0, stream, keys);
     return hipGetLastError();
 }
+uint32_t sum_squares_batch_blocks() { return kSumBlocks; }
+
+// partials: count * kSumBlocks doubles of scratch memory; out: count doubles
+hipError_t launch_sum_squares_batch(const SumSquaresBatch& b, uint32_t count, double* partials, double* out, hipStream_t stream) {
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(sum_squares_partial_kernel, dim3(kSumBlocks, count), dim3(kSumThreads), 0, stream, b, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sum_squares_finish_kernel, dim3(count), dim3(64), 0, stream, partials, (uint32_t)kSumBlocks, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream) {
     hipLaunchKernelGGL(clear_f64_kernel, dim3(1), dim3(1), 0, stream, out);
     hipError_t e = hipGetLastError();

@@ -25,6 +25,7 @@ EXPORTS = [
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step", "mqg_mdp_step_workers",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
     "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
+    "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch",
 ]
 
 
@@ -44,6 +45,10 @@ class MdpConfig(C.Structure):
 class AdaptiveConfig(C.Structure):
     _fields_ = [("base_bits", C.c_uint32), ("norm_per_bit", C.c_double), ("bits_min", C.c_uint32),
                 ("bits_max", C.c_uint32)]
+
+
+class SumsqItem(C.Structure):
+    _fields_ = [("grad", C.c_void_p), ("n", C.c_uint64)]
 
 
 class QuantizeItem(C.Structure):
@@ -112,6 +117,10 @@ def lib():
     L.mqg_aggregate_mean.restype = C.c_int
     L.mqg_sum_squares.argtypes = [vp, u64, vp, vp]
     L.mqg_sum_squares.restype = C.c_int
+    L.mqg_sum_squares_workspace_bytes.argtypes = [u32]
+    L.mqg_sum_squares_workspace_bytes.restype = C.c_size_t
+    L.mqg_sum_squares_batch.argtypes = [C.POINTER(SumsqItem), u32, vp, vp, vp]
+    L.mqg_sum_squares_batch.restype = C.c_int
     L.mqg_adaptive_default_config.argtypes = [C.POINTER(AdaptiveConfig)]
     L.mqg_adaptive_default_config.restype = None
     L.mqg_adaptive_bits.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(AdaptiveConfig), C.POINTER(u32)]
@@ -476,6 +485,33 @@ def mqg_sum_squares(grad, out=None, stream=None):
     st = lib().mqg_sum_squares(grad.data_ptr(), grad.numel(), out.data_ptr(), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_sum_squares")
+    return out
+
+
+def mqg_sum_squares_workspace_bytes(count):
+    return int(lib().mqg_sum_squares_workspace_bytes(int(count)))
+
+
+def mqg_sum_squares_batch(grads, workspace=None, out=None, stream=None):
+    """Sums of squares of several gradients in one call, each reproducible to the bit; returns a float64
+    device tensor with one entry per gradient.  `workspace`: a device tensor of at least
+    mqg_sum_squares_workspace_bytes(len(grads)) bytes (allocated here when not given)."""
+    count = len(grads)
+    for g in grads:
+        _check(g, torch.float32, "grad")
+    dev = grads[0].device if count else "cuda"
+    if workspace is None:
+        workspace = torch.empty(max(1, mqg_sum_squares_workspace_bytes(count) // 8), dtype=torch.float64, device=dev)
+    if out is None:
+        out = torch.empty(max(1, count), dtype=torch.float64, device=dev)[:count]
+    _check(out, torch.float64, "out")
+    items = (SumsqItem * max(1, count))()
+    for k, g in enumerate(grads):
+        items[k].grad = g.data_ptr()
+        items[k].n = g.numel()
+    st = lib().mqg_sum_squares_batch(items, count, workspace.data_ptr(), out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_sum_squares_batch")
     return out
 
 

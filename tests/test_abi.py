@@ -153,6 +153,21 @@ def test_multi_tensor_and_minmax_arguments_are_rejected_before_any_launch():
     assert L.mqg_sum_squares(fake, 10, None, None) == mqgrad.MQG_EINVAL
     assert L.mqg_sum_squares(None, 10, fake, None) == mqgrad.MQG_EINVAL
     assert L.mqg_sum_squares(fake, 10, vp(0x1004), None) == mqgrad.MQG_EALIGN
+    items = (mqgrad.SumsqItem * 65)()
+    for it in items:
+        it.grad, it.n = 0x1000, 10
+    assert L.mqg_sum_squares_workspace_bytes(3) == 3 * 512 * 8
+    assert L.mqg_sum_squares_batch(items, 0, None, None, None) == mqgrad.MQG_OK
+    assert L.mqg_sum_squares_batch(items, 65, fake, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_sum_squares_batch(None, 2, fake, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_sum_squares_batch(items, 2, None, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_sum_squares_batch(items, 2, fake, None, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_sum_squares_batch(items, 2, vp(0x1004), fake, None) == mqgrad.MQG_EALIGN
+    assert L.mqg_sum_squares_batch(items, 2, fake, vp(0x1004), None) == mqgrad.MQG_EALIGN
+    items[1].grad = 0x1002
+    assert L.mqg_sum_squares_batch(items, 2, fake, fake, None) == mqgrad.MQG_EALIGN
+    items[1].grad = None
+    assert L.mqg_sum_squares_batch(items, 2, fake, fake, None) == mqgrad.MQG_EINVAL
 
 
 def test_adaptive_rule_matches_the_oracle_rule():

@@ -118,6 +118,38 @@ def test_sum_squares_matches_exact_sum(n):
         assert abs(out2.item() - e2) <= 1e-12 * e2
 
 
+def exact_sum_squares(t):
+    x = t.cpu().numpy().astype(np.float64)
+    return math.fsum(float(v) * float(v) for v in x) if x.size <= (1 << 20) else float(np.sum(x * x))
+
+
+def test_batched_sum_squares_is_exact_and_reproducible_to_the_bit():
+    # several tensors in one call (ragged sizes, an empty one, a view off a 16-byte boundary); each sum
+    # within 1e-12 of the exactly rounded one, equal bit for bit between calls and whatever else is in
+    # the batch, and within rounding of the single-tensor entry point
+    sizes = [0, 1, 3, 5, 1023, 2048 * 512 + 9, (1 << 22) + 7, 4097]
+    grads = [workloads.normal(max(n, 1), 10.0 ** (-1 - (k % 4)), 50 + k, DEV)[:n] for k, n in enumerate(sizes)]
+    grads.append(grads[6][1:])
+    out = mqgrad.mqg_sum_squares_batch(grads)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert got[0] == 0.0
+    for k, g in enumerate(grads):
+        exact = exact_sum_squares(g)
+        assert abs(got[k] - exact) <= 1e-12 * exact
+    ws = torch.full((mqgrad.mqg_sum_squares_workspace_bytes(len(grads)) // 8,), float("nan"), dtype=torch.float64, device=DEV)
+    again = mqgrad.mqg_sum_squares_batch(grads, workspace=ws).cpu().numpy()
+    assert again.tobytes() == got.tobytes()
+    alone = mqgrad.mqg_sum_squares_batch(grads[6:7]).cpu().numpy()
+    assert alone[0] == got[6]
+    reversed_batch = mqgrad.mqg_sum_squares_batch(grads[::-1]).cpu().numpy()
+    assert reversed_batch[::-1].tobytes() == got.tobytes()
+    single = mqgrad.mqg_sum_squares(grads[6]).item()
+    assert abs(single - got[6]) <= 1e-14 * got[6]
+    full = mqgrad.mqg_sum_squares_batch([grads[5]] * 64).cpu().numpy()      # the largest batch
+    assert np.all(full == got[5])
+
+
 def test_adaptive_rule_from_gpu_norms():
     # Z = mean over workers of the gradient norm; the width follows the oracle's statement of the rule
     W, n = 4, 200000
