@@ -282,6 +282,16 @@ size_t mqg_sum_squares_workspace_bytes(uint32_t count);
 mqg_status mqg_sum_squares_batch(const mqg_sumsq_item* items, uint32_t count, void* workspace, double* sumsq_out,
                                  void* stream);
 
+/* mqg_sum_squares_batch for callers that cannot allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: no workspace argument; the partial sums live in
+ * a device array that the library itself holds (256 KB on every GPU it runs on, until the process ends).
+ * The call allocates and frees nothing.  Results are bit-identical to mqg_sum_squares_batch.
+ *   count   at most MQG_MAX_SUMSQ_TENSORS (the array's size); more is MQG_EINVAL.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different streams,
+ * different threads) race and must be serialised by the caller.  Nothing has to be cleared between
+ * calls (every partial sum is written before it is read).  Other arguments and errors as above. */
+mqg_status mqg_sum_squares_batch_static(const mqg_sumsq_item* items, uint32_t count, double* sumsq_out, void* stream);
+
 typedef struct {
     uint32_t base_bits;     /* 2: this build's reading (the published Section 4.1 names the baseline, not its rule) */
     double norm_per_bit;    /* 0.0005: this build's reading, as above */

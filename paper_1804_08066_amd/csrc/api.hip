@@ -54,6 +54,24 @@ mqg_status quantize_impl(const float* grad, uint64_t n, uint32_t bits, uint32_t 
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 
+// shared argument checks of the two batched forms; fills b
+mqg_status sumsq_batch_args(const mqg_sumsq_item* items, uint32_t count, const double* sumsq_out, mqg::SumSquaresBatch& b) {
+    if (items == nullptr || sumsq_out == nullptr || count > MQG_MAX_SUMSQ_TENSORS) return MQG_EINVAL;
+    for (uint32_t k = 0; k < count; ++k) {
+        if (items[k].n > 0 && items[k].grad == nullptr) return MQG_EINVAL;
+        if (items[k].n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+        if (items[k].n > 0 && misaligned4(items[k].grad)) return MQG_EALIGN;
+        b.grad[k] = items[k].grad;
+        b.n[k] = items[k].n;
+    }
+    for (uint32_t k = count; k < mqg::kMaxSumTensors; ++k) {
+        b.grad[k] = nullptr;
+        b.n[k] = 0;
+    }
+    if (misaligned8(sumsq_out)) return MQG_EALIGN;
+    return MQG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -470,22 +488,22 @@ size_t mqg_sum_squares_workspace_bytes(uint32_t count) {
 mqg_status mqg_sum_squares_batch(const mqg_sumsq_item* items, uint32_t count, void* workspace, double* sumsq_out,
                                  void* stream) {
     if (count == 0u) return MQG_OK;
-    if (items == nullptr || workspace == nullptr || sumsq_out == nullptr || count > MQG_MAX_SUMSQ_TENSORS) return MQG_EINVAL;
+    if (workspace == nullptr) return MQG_EINVAL;
     mqg::SumSquaresBatch b;
-    for (uint32_t k = 0; k < count; ++k) {
-        if (items[k].n > 0 && items[k].grad == nullptr) return MQG_EINVAL;
-        if (items[k].n > (UINT64_MAX >> 4)) return MQG_EINVAL;
-        if (items[k].n > 0 && misaligned4(items[k].grad)) return MQG_EALIGN;
-        b.grad[k] = items[k].grad;
-        b.n[k] = items[k].n;
-    }
-    for (uint32_t k = count; k < mqg::kMaxSumTensors; ++k) {
-        b.grad[k] = nullptr;
-        b.n[k] = 0;
-    }
-    if (misaligned8(workspace) || misaligned8(sumsq_out)) return MQG_EALIGN;
+    const mqg_status st = sumsq_batch_args(items, count, sumsq_out, b);
+    if (st != MQG_OK) return st;
+    if (misaligned8(workspace)) return MQG_EALIGN;
     const hipError_t err = mqg::launch_sum_squares_batch(b, count, static_cast<double*>(workspace), sumsq_out,
                                                          static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_sum_squares_batch_static(const mqg_sumsq_item* items, uint32_t count, double* sumsq_out, void* stream) {
+    if (count == 0u) return MQG_OK;
+    mqg::SumSquaresBatch b;
+    const mqg_status st = sumsq_batch_args(items, count, sumsq_out, b);   // count > MQG_MAX_SUMSQ_TENSORS: MQG_EINVAL
+    if (st != MQG_OK) return st;
+    const hipError_t err = mqg::launch_sum_squares_batch_static(b, count, sumsq_out, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 

@@ -112,5 +112,7 @@ struct SumSquaresBatch {
 };
 uint32_t sum_squares_batch_blocks();   // partial sums (doubles of scratch memory) per tensor
 hipError_t launch_sum_squares_batch(const SumSquaresBatch& b, uint32_t count, double* partials, double* out, hipStream_t stream);
+// the same with the partial sums in a device array the library holds (no allocation, no workspace argument)
+hipError_t launch_sum_squares_batch_static(const SumSquaresBatch& b, uint32_t count, double* out, hipStream_t stream);
 
 }  // namespace mqg

@@ -12,6 +12,8 @@
 // from HBM once), ranges go through LDS with order-preserving integer keys, codes are packed through
 // LDS and whole words are stored coalesced.
 
+#include <mutex>
+
 #include "decode.h"
 #include "encode.h"
 #include "kernels.h"
@@ -594,6 +596,45 @@ hipError_t launch_sum_squares_batch(const SumSquaresBatch& b, uint32_t count, do
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sum_squares_finish_kernel, dim3(count), dim3(64), 0, stream, partials, (uint32_t)kSumBlocks, out);
     return hipGetLastError();
+}
+
+// ---- the same with the partial sums in memory that the library itself holds ------------------------
+// For callers that cannot allocate (code under graph capture, serving loops): a file-scope device array
+// takes the place of the workspace.  Every GPU the library runs on holds its own copy of the array, at
+// its own address, until the process ends; the array's name is a host-side handle, not a device address,
+// so the address is asked for once per device (with that device current) and kept.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) double scratch[kMaxSumTensors * kSumBlocks];   // 256 KB per GPU
+
+static std::mutex g_scratch_mutex;
+static double* g_scratch_ptr[kMaxDevices];   // per device; nullptr until first use on that device
+
+static hipError_t static_scratch(double** ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        double* p = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+// No allocation anywhere on this path; the partial sums are all overwritten before they are read, so
+// nothing has to be cleared between calls.
+hipError_t launch_sum_squares_batch_static(const SumSquaresBatch& b, uint32_t count, double* out, hipStream_t stream) {
+    if (count == 0) return hipSuccess;
+    if (count > kMaxSumTensors) return hipErrorInvalidValue;
+    double* partials = nullptr;
+    const hipError_t e = static_scratch(&partials);
+    if (e != hipSuccess) return e;
+    return launch_sum_squares_batch(b, count, partials, out, stream);
 }
 
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream) {

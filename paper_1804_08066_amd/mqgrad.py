@@ -25,7 +25,7 @@ EXPORTS = [
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step", "mqg_mdp_step_workers",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
     "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
-    "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch",
+    "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch", "mqg_sum_squares_batch_static",
 ]
 
 
@@ -121,6 +121,8 @@ def lib():
     L.mqg_sum_squares_workspace_bytes.restype = C.c_size_t
     L.mqg_sum_squares_batch.argtypes = [C.POINTER(SumsqItem), u32, vp, vp, vp]
     L.mqg_sum_squares_batch.restype = C.c_int
+    L.mqg_sum_squares_batch_static.argtypes = [C.POINTER(SumsqItem), u32, vp, vp]
+    L.mqg_sum_squares_batch_static.restype = C.c_int
     L.mqg_adaptive_default_config.argtypes = [C.POINTER(AdaptiveConfig)]
     L.mqg_adaptive_default_config.restype = None
     L.mqg_adaptive_bits.argtypes = [C.POINTER(C.c_double), u32, C.POINTER(AdaptiveConfig), C.POINTER(u32)]
@@ -512,6 +514,25 @@ def mqg_sum_squares_batch(grads, workspace=None, out=None, stream=None):
     st = lib().mqg_sum_squares_batch(items, count, workspace.data_ptr(), out.data_ptr(), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_sum_squares_batch")
+    return out
+
+
+def mqg_sum_squares_batch_static(grads, out, stream=None):
+    """mqg_sum_squares_batch with the partial sums in the library's own device array: allocates nothing
+    (`out`, a float64 device tensor with one entry per gradient, is the caller's)."""
+    count = len(grads)
+    for g in grads:
+        _check(g, torch.float32, "grad")
+    _check(out, torch.float64, "out")
+    if out.numel() < count:
+        raise ValueError("out holds fewer entries than there are gradients")
+    items = (SumsqItem * max(1, count))()
+    for k, g in enumerate(grads):
+        items[k].grad = g.data_ptr()
+        items[k].n = g.numel()
+    st = lib().mqg_sum_squares_batch_static(items, count, out.data_ptr(), _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_sum_squares_batch_static")
     return out
 
 
