@@ -59,13 +59,7 @@ struct CodeRegs {
 // the same line, and a streaming load would fetch it from L2 once per wave: there the loads are
 // ordinary ones, so that the vector L1 serves the neighbours (measured at 100 M elements, W = 8:
 // 7-11 % faster at 1, 2, 3, 5, 7 bits; 6 bits is 2 % faster with the hint).
-#if defined(MQG_XONCE) && MQG_XONCE == 0
-inline __host__ __device__ bool codes_read_once(uint32_t b) { return false; }
-#elif defined(MQG_XONCE) && MQG_XONCE == 1
-inline __host__ __device__ bool codes_read_once(uint32_t b) { return true; }
-#else
 inline __host__ __device__ bool codes_read_once(uint32_t b) { return b >= 4u && (b & 1u) == 0u; }
-#endif
 
 // Fetch the first code word of each of the lane's quads for workers [w0, min(w0 + CH, W)): one
 // aligned dword load per worker and quad, all issued before any is consumed.  Adjacent lanes read
@@ -193,6 +187,56 @@ __device__ __forceinline__ void accumulate_quad_bytes(uint32_t lo, float d, floa
     acc.y = __builtin_fmaf(__builtin_fmaf(k1, 2.0f, -255.0f), d, acc.y);
     acc.z = __builtin_fmaf(__builtin_fmaf(k2, 2.0f, -255.0f), d, acc.z);
     acc.w = __builtin_fmaf(__builtin_fmaf(k3, 2.0f, -255.0f), d, acc.w);
+}
+
+// Widths 1, 2 and 3 (and 4) through a table of multipliers in LDS.  The multiplier (float)(2c - L) depends on the code alone, so the pairs
+// (2 c0 - L, 2 c1 - L) of two adjacent codes are tabulated once per workgroup -- 4^bits entries of two
+// floats: 32, 128 or 512 bytes -- and a lane fetches the two pairs of its quad with two 64-bit LDS reads
+// (the LDS pipe, not the vector ALU).  What is left for the vector ALU is one rotation per quad, the two
+// table offsets, and the chain's own fma per code -- an fp32 fma whose multiplicand is a register, which
+// this chip issues alongside other vector work.  Results are those of the all-fp32 form bit for bit: the
+// table holds the same multiplier, and the chain's fma is the same instruction.
+constexpr uint32_t kLutFloats = 512;   // 4^4 entries of two floats
+__device__ __forceinline__ void build_pair_lut(float* lut, uint32_t b, uint32_t tid) {
+    const uint32_t L = (1u << b) - 1u;
+    if (b == 1u) {
+        // one bit: a whole quad indexes the table (16 entries of four floats), one 128-bit read per quad
+        if (tid < 64u) lut[tid] = ((tid >> 2) >> (tid & 3u)) & 1u ? 1.0f : -1.0f;
+    } else if (tid < (1u << (2u * b))) {
+        lut[2u * tid] = (float)(2 * (int)(tid & L) - (int)L);
+        lut[2u * tid + 1u] = (float)(2 * (int)(tid >> b) - (int)L);
+    }
+}
+// B = bits (1, 2, 4: a quad lies inside one word; 3: it may spill into the next lane's word)
+template <int B>
+__device__ __forceinline__ void accumulate_quad_lut(uint32_t lo, uint32_t sh, const float* lut, float d, float4& acc) {
+    if (B == 1) {
+        const uint32_t r = __builtin_amdgcn_alignbit(lo, lo, (sh - 4u) & 31u);   // rotate: bit sh moves to bit 4
+        const float4 m = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(lut) + (r & 0xF0u));
+        acc.x = __builtin_fmaf(m.x, d, acc.x);
+        acc.y = __builtin_fmaf(m.y, d, acc.y);
+        acc.z = __builtin_fmaf(m.z, d, acc.z);
+        acc.w = __builtin_fmaf(m.w, d, acc.w);
+        return;
+    }
+    constexpr uint32_t kMask = ((1u << (2 * B)) - 1u) << 3;   // a pair's index times the entry size
+    uint32_t oa, ob;
+    if (B == 3) {
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, kDppWaveShl1, 0xF, 0xF, false);
+        const uint32_t v = __builtin_amdgcn_alignbit(hi, lo, sh);   // the quad's 12 bits at bit 0
+        oa = (v << 3) & kMask;
+        ob = (v >> 3) & kMask;
+    } else {
+        const uint32_t r = __builtin_amdgcn_alignbit(lo, lo, (sh - 3u) & 31u);   // rotate: bit sh moves to bit 3
+        oa = r & kMask;
+        ob = (r >> (2 * B)) & kMask;
+    }
+    const float2 ma = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(lut) + oa);
+    const float2 mb = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(lut) + ob);
+    acc.x = __builtin_fmaf(ma.x, d, acc.x);
+    acc.y = __builtin_fmaf(ma.y, d, acc.y);
+    acc.z = __builtin_fmaf(mb.x, d, acc.z);
+    acc.w = __builtin_fmaf(mb.y, d, acc.w);
 }
 
 // Dispatch on the width class: WIDTH = 1 or 8 select the three-operation forms above, 0 the general one.

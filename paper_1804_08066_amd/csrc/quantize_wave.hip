@@ -791,22 +791,10 @@ auto with_wave_shape_w(uint32_t bucket, uint32_t bits, F f) {
         case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
         case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{}, free{}, early{});
         default:   // 32 .. 1024
-#ifndef MQG_XR
-#define MQG_XR 8
-#endif
-#ifndef MQG_XNW
-#define MQG_XNW 4
-#endif
-#ifndef MQG_XOCC_LO
-#define MQG_XOCC_LO 8
-#endif
-#ifndef MQG_XOCC_HI
-#define MQG_XOCC_HI 5
-#endif
             if constexpr (!EIGHT) {
-                if (bits <= 3u) return f(integral_constant<int, MQG_XR>{}, integral_constant<int, 1>{}, integral_constant<int, MQG_XNW>{}, integral_constant<int, MQG_XOCC_LO>{}, late{});
+                if (bits <= 3u) return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, free{}, late{});
             }
-            return f(integral_constant<int, MQG_XR>{}, integral_constant<int, 1>{}, integral_constant<int, MQG_XNW>{}, integral_constant<int, MQG_XOCC_HI>{}, late{});
+            return f(integral_constant<int, 8>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{}, integral_constant<int, 5>{}, late{});
     }
 }
 template <class F>

@@ -21,13 +21,7 @@ __device__ __forceinline__ float4 load_f4_stream(const float* p) {
 }
 __device__ __forceinline__ void store_f4_stream(float* p, const float4& r) {
     v4f t = {r.x, r.y, r.z, r.w};
-#if defined(MQG_XPST) && MQG_XPST == 1
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(t) : "memory");
-#elif defined(MQG_XPST) && MQG_XPST == 2
-    *reinterpret_cast<v4f_a4*>(p) = t;
-#else
     __builtin_nontemporal_store(t, reinterpret_cast<v4f_a4*>(p));
-#endif
 }
 
 template <int R>

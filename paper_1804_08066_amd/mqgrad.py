@@ -72,12 +72,15 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
-        _build.build()
-    elif _build.needs_build():
-        import warnings
-        warnings.warn("libmqgrad.so is older than its sources: run paper_1804_08066_amd/build.py (loading the stale library)")
-    L = C.CDLL(_build.LIB)
+    path = os.environ.get("MQGRAD_LIB")   # another build of the library (A/B timing of kernel variants)
+    if path is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        elif _build.needs_build():
+            import warnings
+            warnings.warn("libmqgrad.so is older than its sources: run paper_1804_08066_amd/build.py (loading the stale library)")
+    L = C.CDLL(path)
     vp, u32, u64, f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_float
     L.mqg_status_string.argtypes = [C.c_int]
     L.mqg_status_string.restype = C.c_char_p

@@ -158,6 +158,23 @@ def test_many_workers(W):
         assert_aggregate_parity(pks, scs, n, bits, bucket, 0.2, p, label="W=%d b=%d" % (W, bits))
 
 
+@pytest.mark.parametrize("W", [9, 16, 17])
+@pytest.mark.parametrize("bucket", [128, 384, 1024])
+def test_more_than_eight_workers_on_the_wave_local_server_kernel(W, bucket):
+    # buckets that are multiples of 128 with more than eight workers: widths 1..3 decode through the
+    # multiplier table in LDS; several tiles and a ragged tail
+    n = 3 * 2048 + 777
+    for bits in (1, 2, 3, 4):
+        pks, scs = [], []
+        for w in range(W):
+            g = workloads.laplace(n, 1e-3 * (1 + w % 5), 700 + 31 * w + bits, DEV)
+            pk, sc = assert_quantize_parity(g, bits, bucket, seed=11, iteration=bits, worker=w)
+            pks.append(pk)
+            scs.append(sc)
+        p = workloads.uniform(n, -0.05, 0.05, 9, "cpu").numpy()
+        assert_aggregate_parity(pks, scs, n, bits, bucket, 0.3, p, label="W=%d b=%d B=%d" % (W, bits, bucket))
+
+
 def test_outputs_are_fully_overwritten_and_neighbours_untouched():
     n, bits, bucket = 5000, 3, 512
     g = workloads.normal(n, 0.01, 1, DEV)
