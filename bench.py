@@ -491,9 +491,10 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
     mpk = torch.empty_like(pk[0])
     mrg = torch.empty_like(rg[0])
     trg = torch.zeros(2, dtype=torch.float32, device=wl.device)
+    trs = [torch.tensor([-0.06, 0.06], dtype=torch.float32, device=wl.device) for _ in range(W)]   # one range per worker
     ev = []
     for k in range(warmup + steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
         e[0].record()
         for w in range(W):
             mqgrad.mqg_quantize_minmax(wl.grads[w], bits, bucket, pk[w], rg[w])
@@ -507,6 +508,8 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
         e[4].record()
         mqgrad.mqg_quantize_minmax_tensor(wl.grads[k % W], bits, mpk, trg)
         e[5].record()
+        mqgrad.mqg_aggregate_requantize_minmax_tensor(pk, trs, n, bits, mpk, trg)
+        e[6].record()
         if k >= warmup:
             ev.append(e)
     torch.cuda.synchronize()
@@ -515,6 +518,8 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
     s_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / len(ev) / W
     r_ms = sum(e[3].elapsed_time(e[4]) for e in ev) / len(ev)
     t_ms = sum(e[4].elapsed_time(e[5]) for e in ev) / len(ev)
+    rt_ms = sum(e[5].elapsed_time(e[6]) for e in ev) / len(ev)
+    rt_bytes = (2 * W + 1) * n * bits / 8.0   # the W streams are read twice (range of the sum, then the encode)
     nb = (n + bucket - 1) // bucket
     q_bytes = n * (4.0 + bits / 8.0) + 8.0 * nb
     a_bytes = W * (n * bits / 8.0 + 8.0 * nb) + 8.0 * n
@@ -534,7 +539,11 @@ def time_minmax(wl, bits, bucket, lr, steps, warmup):
             "aggregate_update_minmax": row("aggregate_update_minmax_kernel", a_bytes, a_ms),
             "sum_squares": row("sum_squares_kernel", s_bytes, s_ms),
             "quantize_minmax_tensor": row("tensor_range_kernel + quantize_minmax_wave_kernel", t_bytes, t_ms),
-            "requantize_minmax": alu_row("requantize_minmax_kernel", r_ms, r_ops)}
+            "requantize_minmax": alu_row("requantize_minmax_kernel", r_ms, r_ops),
+            "requantize_minmax_tensor": alu_row("range_init + sum_range_minmax_tensor + range_finish + "
+                                                "requantize_minmax_tensor + range_divide kernels", rt_ms,
+                                                n * (8.0 * W + 14.0),   # two decodes of W workers, min/max, encode
+                                                {"algorithmic_bytes_per_launch": rt_bytes, "hbm_gbs": rt_bytes / (rt_ms * 1e-3) / 1e9})}
 
 
 def cpu_baseline(bits, bucket, W, lr, sample_n, steps):

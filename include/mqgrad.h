@@ -246,13 +246,25 @@ mqg_status mqg_aggregate_requantize_minmax(const uint32_t* const* packed, const 
  *   one (mn, mx) for every element -- two passes over the gradient, on the same stream.
  * mqg_aggregate_update_minmax_tensor: the server step with one (mn, mx) pair per worker.
  *   ranges  HOST array of W device pointers, each to 2 floats (8-byte aligned).
- * Arithmetic, packed layout and errors as for the bucketed calls. */
+ * Arithmetic, packed layout and errors as for the bucketed calls.
+ * mqg_aggregate_requantize_minmax_tensor: the server's re-encoding step of Algorithm 1 as printed
+ *   (ReceiveQGThenSendQG with the footnote's encoder): the W streams are de-quantized and added in worker
+ *   order, the sum is encoded over its own whole-tensor [mn, mx], and range_out receives (mn / W, mx / W),
+ *   so that what a worker de-quantizes (mqg_aggregate_update_minmax_tensor with W = 1) is the mean.  The
+ *   range of the sum is known only after every element has been decoded, so the W streams are read twice
+ *   ((2 W + 1) * bits / 8 bytes per element; no fp32 copy of the sum is written).  Five launches on the stream.
+ *   ranges      HOST array of W device pointers, each to 2 floats (8-byte aligned).
+ *   packed_out  device, mqg_packed_words(n, bits) words;  range_out: device, 2 floats, 8-byte aligned.
+ */
 mqg_status mqg_tensor_range(const float* grad, uint64_t n, float* range_out, void* stream);
 mqg_status mqg_quantize_minmax_tensor(const float* grad, uint64_t n, uint32_t bits,
                                       uint32_t* packed_out, float* range_out, void* stream);
 mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, const float* const* ranges,
                                               uint32_t W, uint64_t n, uint32_t bits,
                                               float lr, float* params, void* stream);
+mqg_status mqg_aggregate_requantize_minmax_tensor(const uint32_t* const* packed, const float* const* ranges,
+                                                  uint32_t W, uint64_t n, uint32_t bits,
+                                                  uint32_t* packed_out, float* range_out, void* stream);
 
 /* ---- the "Adaptive" baseline's bit rule (Section 4.1; idea in Section 2: the larger the gradient's
  * norm, the more bits) ------------------------------------------------------------------------------

@@ -284,6 +284,13 @@ def nearest_code(x, mn, mx, bits):
     return int(lib().orc_nearest_code(float(np.float32(x)), float(np.float32(mn)), float(np.float32(mx)), bits))
 
 
+def encode_minmax_given_range(values, bits, mn, mx):
+    """Packed words of `values` encoded over the given [mn, mx] (one nearest-level call per element)."""
+    v = _f32(values).reshape(-1)
+    codes = np.array([nearest_code(x, mn, mx, bits) for x in v], dtype=np.uint8)
+    return pack(codes, bits)
+
+
 def minmax_level_value(k, mn, mx, bits):
     return np.float32(lib().orc_minmax_level_value(int(k), float(np.float32(mn)), float(np.float32(mx)), bits))
 

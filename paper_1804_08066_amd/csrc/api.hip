@@ -473,6 +473,33 @@ mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, con
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 
+mqg_status mqg_aggregate_requantize_minmax_tensor(const uint32_t* const* packed, const float* const* ranges,
+                                                  uint32_t W, uint64_t n, uint32_t bits,
+                                                  uint32_t* packed_out, float* range_out, void* stream) {
+    if (bits < 1u || bits > 8u) return MQG_EINVAL;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (n == 0) return MQG_OK;
+    if (packed == nullptr || ranges == nullptr || packed_out == nullptr || range_out == nullptr) return MQG_EINVAL;
+    if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+    if (misaligned4(packed_out) || misaligned8(range_out)) return MQG_EALIGN;
+    mqg::RequantArgs ra = {};
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
+        ra.packed[w] = packed[w];
+        ra.scales[w] = ranges[w];
+    }
+    ra.W = W;
+    ra.q.n = n;
+    ra.q.bits = bits;
+    ra.q.bucket = 1024u;            // tiling only: one range for the whole tensor
+    ra.q.bucket_shift = 10;
+    ra.q.packed = packed_out;
+    ra.q.scales = range_out;
+    const hipError_t err = mqg::launch_requantize_minmax_tensor(ra, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
 mqg_status mqg_sum_squares(const float* grad, uint64_t n, double* sumsq_out, void* stream) {
     if (sumsq_out == nullptr || (n > 0 && grad == nullptr)) return MQG_EINVAL;
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;

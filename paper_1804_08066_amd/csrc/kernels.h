@@ -101,6 +101,7 @@ hipError_t launch_aggregate_mean(const AggregateArgs& a, hipStream_t stream);   
 hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream);
 hipError_t launch_requantize_minmax(const RequantArgs& a, hipStream_t stream);
+hipError_t launch_requantize_minmax_tensor(const RequantArgs& a, hipStream_t stream);   // one range per worker and for the mean
 hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, hipStream_t stream);
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream);
 

@@ -77,7 +77,9 @@ __device__ __forceinline__ void clear_shared(Shared<R, NT>& sm, uint32_t tile_co
 // The tile, once its values are in registers; enters right after the barrier that follows
 // clear_shared.  range_div: the stored range is [mn, mx] / range_div (1 for a plain encode, W for the
 // server's mean).
-template <int R, int NT, bool FULL>
+// GIVEN: one (min, max) pair for every element, read from a.scales_in (the whole-tensor range found by
+// an earlier pass); no range is reduced and none is stored.
+template <int R, int NT, bool FULL, bool GIVEN = false>
 __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const uint64_t tile_base,
                                                    const uint32_t tile_count, const float4 (&x)[R],
                                                    const float range_div, Shared<R, NT>& sm) {
@@ -86,13 +88,13 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
     const uint32_t b = a.bits;
     const uint32_t nwords = (tile_count * b + 31u) >> 5;
 
-    const uint32_t nbt = Shared<R, NT>::kOneBucket ? 1u : (tile_count + a.bucket - 1u) / a.bucket;   // buckets in the tile
-    const uint64_t kb0 = tile_base / a.bucket;
+    const uint32_t nbt = (GIVEN || Shared<R, NT>::kOneBucket) ? 1u : (tile_count + a.bucket - 1u) / a.bucket;   // buckets in the tile
+    const uint64_t kb0 = GIVEN ? 0u : tile_base / a.bucket;
     uint32_t bl[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const uint32_t el = 4u * (j * NT + tid);
-        bl[j] = Shared<R, NT>::kOneBucket ? 0u : (a.bucket_shift >= 0 ? (el >> a.bucket_shift) : (el / a.bucket));
+        bl[j] = (GIVEN || Shared<R, NT>::kOneBucket) ? 0u : (a.bucket_shift >= 0 ? (el >> a.bucket_shift) : (el / a.bucket));
     }
 
     // ---- bucket range: 8-lane cells by DPP; whole waves when a wave's row lies in one bucket -------
@@ -101,7 +103,7 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
     constexpr bool kOne = Shared<R, NT>::kOneBucket;
     const uint32_t lane = tid & 63u;
     const bool row_in_bucket = kOne || (a.bucket & 255u) == 0u;   // uniform over the launch
-    {
+    if (!GIVEN) {
     float lo[R], hi[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -159,11 +161,18 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
 
     const float Lf = (float)((1u << b) - 1u);
     if (tid < nbt) {
-        float mn = key_value(sm.kmin[tid]), mx = key_value(sm.kmax[tid]);
-        if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
-        if (mx == 0.0f) mx = 0.0f;
-        a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
-        a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
+        float mn, mx;
+        if (GIVEN) {
+            mn = a.scales_in[0];
+            mx = a.scales_in[1];
+        } else {
+            mn = key_value(sm.kmin[tid]);
+            mx = key_value(sm.kmax[tid]);
+            if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
+            if (mx == 0.0f) mx = 0.0f;
+            a.scales[2u * (kb0 + tid)] = (range_div == 1.0f) ? mn : mn / range_div;
+            a.scales[2u * (kb0 + tid) + 1u] = (range_div == 1.0f) ? mx : mx / range_div;
+        }
         const float r = mx - mn;
         sm.mn[tid] = mn;
         sm.a[tid] = (r >= 0x1p-96f) ? Lf / r : 0.0f;   // IEEE-correct fp32 division, once per bucket
@@ -285,6 +294,112 @@ __global__ __launch_bounds__(NT) void requantize_minmax_kernel(const RequantArgs
     } else {
         encode_minmax_tile<R, NT, false>(a, tile_base, tile_count, x, Wf, sm);   // ignores elements past the end
     }
+}
+
+// ---- the same with ONE range for the whole tensor, as the paper encodes -----------------------------
+// The range of the sum is not known until every element has been decoded, so the step takes two passes
+// over the W code streams (the fp32 sum still never exists in memory: (2 W + 1) * bits / 8 bytes per
+// element in all): pass 1 decodes and folds the tile's min / max into two integer keys (exact and order
+// independent; a workgroup first looks whether its values can move a key at all, since same-address
+// atomics serialize); pass 2 decodes again and encodes over that range.
+// Every worker has one (min, max) pair; s_tab[w] = (step, min) of worker w.
+template <int NT, bool STRADDLE, bool ONCE>
+__device__ __forceinline__ void decode_sum_tile_tensor(const RequantArgs& ra, const uint64_t tile_base, float2* s_tab,
+                                                       float4 (&x)[4]) {
+    constexpr int R = 4;
+    constexpr int CH = 8;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t b = ra.q.bits;
+    const float Lf = (float)((1u << b) - 1u);
+    const decode::CodeWindows<R> cw = decode::code_windows<R, NT>(ra.q.n, tile_base, b, tid);
+    decode::CodeRegs<R, CH> c;
+    decode::fetch_codes<R, CH, ONCE>(ra.packed, ra.W, 0u, cw, c);   // in flight while the table is filled
+    if (tid < ra.W) {
+        const float2 rg = *reinterpret_cast<const float2*>(ra.scales[tid]);   // (min, max) of worker tid
+        s_tab[tid] = make_float2((rg.y - rg.x) / Lf, rg.x);                   // IEEE-correct fp32 division
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < R; ++j) x[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (uint32_t w0 = 0; w0 < ra.W; w0 += CH) {
+        if (w0 > 0) decode::fetch_codes<R, CH, ONCE>(ra.packed, ra.W, w0, cw, c);
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            if (w0 + t < ra.W) {
+                const float2 sl = s_tab[w0 + t];
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    decode::accumulate_quad_minmax<STRADDLE>(c.lo[t][j], cw.sh, b, sl.x, sl.y, x[j]);
+                }
+            }
+        }
+    }
+}
+
+template <int NT, bool STRADDLE, bool ONCE>
+__global__ __launch_bounds__(NT) void sum_range_minmax_tensor_kernel(const RequantArgs ra, uint32_t* keys) {
+    constexpr int R = 4;
+    constexpr uint32_t kCap = 4u * NT * R;
+    __shared__ float2 s_tab[MQG_MAX_WORKERS];
+    __shared__ uint32_t s_lo[NT / 64], s_hi[NT / 64];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t tile_base = (uint64_t)blockIdx.x * kCap;
+    const uint64_t left = ra.q.n - tile_base;
+    const uint32_t tile_count = left < kCap ? (uint32_t)left : kCap;
+    float4 x[R];
+    decode_sum_tile_tensor<NT, STRADDLE, ONCE>(ra, tile_base, s_tab, x);
+    const float inf = __builtin_inff();
+    float lo = inf, hi = -inf;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {   // elements past the end take no part
+        const uint32_t el = 4u * (j * NT + tid);
+        if (el + 0u < tile_count) { lo = fminf(lo, x[j].x); hi = fmaxf(hi, x[j].x); }
+        if (el + 1u < tile_count) { lo = fminf(lo, x[j].y); hi = fmaxf(hi, x[j].y); }
+        if (el + 2u < tile_count) { lo = fminf(lo, x[j].z); hi = fmaxf(hi, x[j].z); }
+        if (el + 3u < tile_count) { lo = fminf(lo, x[j].w); hi = fmaxf(hi, x[j].w); }
+    }
+    uint32_t kl = wave_min_from_cells_u32(cell_min_u32(order_key(lo)), tid & 63u);
+    uint32_t kh = wave_max_from_cells_u32(cell_max_u32(order_key(hi)), tid & 63u);
+    if ((tid & 63u) == 0u) {
+        s_lo[tid >> 6] = kl;
+        s_hi[tid >> 6] = kh;
+    }
+    __syncthreads();
+    if (tid == 0u) {
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) {
+            kl = min(kl, s_lo[w]);
+            kh = max(kh, s_hi[w]);
+        }
+        // the keys only ever move one way, so a stale read can cause a needless atomic but never a wrong skip
+        if (kl < __atomic_load_n(&keys[0], __ATOMIC_RELAXED)) atomicMin(&keys[0], kl);
+        if (kh > __atomic_load_n(&keys[1], __ATOMIC_RELAXED)) atomicMax(&keys[1], kh);
+    }
+}
+
+template <int NT, bool STRADDLE, bool ONCE>
+__global__ __launch_bounds__(NT) void requantize_minmax_tensor_kernel(const RequantArgs ra) {
+    constexpr int R = 4;
+    constexpr uint32_t kCap = Shared<R, NT>::kCap;
+    __shared__ Shared<R, NT> sm;
+    __shared__ float2 s_tab[MQG_MAX_WORKERS];
+    const uint64_t tile_base = (uint64_t)blockIdx.x * kCap;
+    const uint64_t left = ra.q.n - tile_base;
+    const uint32_t tile_count = left < kCap ? (uint32_t)left : kCap;
+    clear_shared<R, NT>(sm, tile_count, ra.q.bits);
+    float4 x[R];
+    decode_sum_tile_tensor<NT, STRADDLE, ONCE>(ra, tile_base, s_tab, x);   // its barrier also covers clear_shared
+    if (tile_count == kCap) {
+        encode_minmax_tile<R, NT, true, true>(ra.q, tile_base, tile_count, x, 1.0f, sm);
+    } else {
+        encode_minmax_tile<R, NT, false, true>(ra.q, tile_base, tile_count, x, 1.0f, sm);
+    }
+}
+
+// range[0..1] <- range[0..1] / W: the grid of the mean is the grid of the sum scaled by 1 / W
+__global__ void range_divide_kernel(float* range, float Wf) {
+    range[0] = range[0] / Wf;
+    range[1] = range[1] / Wf;
 }
 
 // ---- server step --------------------------------------------------------------------------------
@@ -573,6 +688,42 @@ hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
     const bool straddle = (32u % a.bits) != 0u;
     return straddle ? launch_aggregate_s<true>(a, stream) : launch_aggregate_s<false>(a, stream);
+}
+
+// ra.scales[w]: worker w's one (min, max) pair; ra.q.scales: the (min, max) pair of the mean (2 floats).
+// Five launches on the stream: prime the keys, pass 1, keys -> floats, pass 2, divide the range by W.
+hipError_t launch_requantize_minmax_tensor(const RequantArgs& ra_in, hipStream_t stream) {
+    if (ra_in.q.n == 0) return hipSuccess;
+    constexpr int NT = 256;
+    constexpr uint32_t kCap = Shared<4, NT>::kCap;
+    const uint64_t tiles = (ra_in.q.n + kCap - 1) / kCap;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    RequantArgs ra = ra_in;
+    ra.q.scales_in = ra.q.scales;   // pass 2 reads the range of the sum from where pass 1 left it
+    uint32_t* keys = reinterpret_cast<uint32_t*>(ra.q.scales);
+    const dim3 grid((uint32_t)tiles), block(NT);
+    const bool straddle = (32u % ra.q.bits) != 0u;
+    const bool once = decode::codes_read_once(ra.q.bits);
+    hipLaunchKernelGGL(range_init_kernel, dim3(1), dim3(1), 0, stream, keys);
+    if (straddle) {
+        if (once) hipLaunchKernelGGL((sum_range_minmax_tensor_kernel<NT, true, true>), grid, block, 0, stream, ra, keys);
+        else hipLaunchKernelGGL((sum_range_minmax_tensor_kernel<NT, true, false>), grid, block, 0, stream, ra, keys);
+    } else {
+        if (once) hipLaunchKernelGGL((sum_range_minmax_tensor_kernel<NT, false, true>), grid, block, 0, stream, ra, keys);
+        else hipLaunchKernelGGL((sum_range_minmax_tensor_kernel<NT, false, false>), grid, block, 0, stream, ra, keys);
+    }
+    hipLaunchKernelGGL(range_finish_kernel, dim3(1), dim3(1), 0, stream, keys);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (straddle) {
+        if (once) hipLaunchKernelGGL((requantize_minmax_tensor_kernel<NT, true, true>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_minmax_tensor_kernel<NT, true, false>), grid, block, 0, stream, ra);
+    } else {
+        if (once) hipLaunchKernelGGL((requantize_minmax_tensor_kernel<NT, false, true>), grid, block, 0, stream, ra);
+        else hipLaunchKernelGGL((requantize_minmax_tensor_kernel<NT, false, false>), grid, block, 0, stream, ra);
+    }
+    hipLaunchKernelGGL(range_divide_kernel, dim3(1), dim3(1), 0, stream, ra.q.scales, (float)ra.W);
+    return hipGetLastError();
 }
 
 hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, hipStream_t stream) {

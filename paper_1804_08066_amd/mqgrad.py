@@ -20,7 +20,7 @@ EXPORTS = [
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
     "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_aggregate_mean", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
     "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax",
-    "mqg_tensor_range", "mqg_quantize_minmax_tensor", "mqg_aggregate_update_minmax_tensor", "mqg_sum_squares", "mqg_adaptive_default_config",
+    "mqg_tensor_range", "mqg_quantize_minmax_tensor", "mqg_aggregate_update_minmax_tensor", "mqg_aggregate_requantize_minmax_tensor", "mqg_sum_squares", "mqg_adaptive_default_config",
     "mqg_adaptive_bits",
     "mqg_mdp_default_config", "mqg_mdp_create", "mqg_mdp_destroy", "mqg_mdp_step", "mqg_mdp_step_workers",
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
@@ -116,6 +116,8 @@ def lib():
     L.mqg_quantize_minmax_tensor.restype = C.c_int
     L.mqg_aggregate_update_minmax_tensor.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, f32, vp, vp]
     L.mqg_aggregate_update_minmax_tensor.restype = C.c_int
+    L.mqg_aggregate_requantize_minmax_tensor.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, vp, vp, vp]
+    L.mqg_aggregate_requantize_minmax_tensor.restype = C.c_int
     L.mqg_aggregate_mean.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, vp, vp]
     L.mqg_aggregate_mean.restype = C.c_int
     L.mqg_sum_squares.argtypes = [vp, u64, vp, vp]
@@ -479,6 +481,34 @@ def mqg_aggregate_update_minmax_tensor(packed, ranges, n, bits, lr, params, stre
     st = lib().mqg_aggregate_update_minmax_tensor(pa, ra, W, n, bits, lr, params.data_ptr(), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_update_minmax_tensor")
+
+
+def mqg_aggregate_requantize_minmax_tensor(packed, ranges, n, bits, packed_out=None, range_out=None, stream=None):
+    """Server side of the full exchange with ONE [min, max] range per tensor. Returns (packed, range) of the mean."""
+    W = len(packed)
+    if W != len(ranges):
+        raise ValueError("packed and ranges must have one entry per worker")
+    for p, r in zip(packed, ranges):
+        _check(p, torch.int32, "packed[w]")
+        _check(r, torch.float32, "ranges[w]")
+        if p.numel() < mqg_packed_words(n, bits) or r.numel() < 2:
+            raise ValueError("a worker's buffers are too small for n")
+    dev = packed[0].device
+    if packed_out is None:
+        packed_out = torch.empty(mqg_packed_words(n, bits), dtype=torch.int32, device=dev)
+    if range_out is None:
+        range_out = torch.zeros(2, dtype=torch.float32, device=dev)
+    _check(packed_out, torch.int32, "packed_out")
+    _check(range_out, torch.float32, "range_out")
+    if packed_out.numel() < mqg_packed_words(n, bits) or range_out.numel() < 2:
+        raise ValueError("output buffers too small")
+    pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
+    ra = (C.c_void_p * max(W, 1))(*[r.data_ptr() for r in ranges])
+    st = lib().mqg_aggregate_requantize_minmax_tensor(pa, ra, W, n, bits, packed_out.data_ptr(), range_out.data_ptr(),
+                                                      _stream_handle(stream))
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_requantize_minmax_tensor")
+    return packed_out, range_out
 
 
 def mqg_sum_squares(grad, out=None, stream=None):

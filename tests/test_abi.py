@@ -150,6 +150,12 @@ def test_multi_tensor_and_minmax_arguments_are_rejected_before_any_launch():
     assert L.mqg_aggregate_update_minmax_tensor(one, one, 0, 10, 4, 0.1, fake, None) == mqgrad.MQG_EINVAL
     assert L.mqg_aggregate_update_minmax_tensor(one, (vp * 1)(0x1004), 1, 10, 4, 0.1, fake, None) == mqgrad.MQG_EALIGN
     assert L.mqg_aggregate_update_minmax_tensor(one, one, 1, 0, 4, 0.1, None, None) == mqgrad.MQG_OK
+    assert L.mqg_aggregate_requantize_minmax_tensor(one, one, 0, 10, 4, fake, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_aggregate_requantize_minmax_tensor(one, one, 1, 10, 9, fake, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_aggregate_requantize_minmax_tensor(one, one, 1, 10, 4, None, fake, None) == mqgrad.MQG_EINVAL
+    assert L.mqg_aggregate_requantize_minmax_tensor(one, one, 1, 10, 4, fake, vp(0x1004), None) == mqgrad.MQG_EALIGN
+    assert L.mqg_aggregate_requantize_minmax_tensor(one, (vp * 1)(0x1004), 1, 10, 4, fake, fake, None) == mqgrad.MQG_EALIGN
+    assert L.mqg_aggregate_requantize_minmax_tensor(one, one, 1, 0, 4, None, None, None) == mqgrad.MQG_OK
     assert L.mqg_sum_squares(fake, 10, None, None) == mqgrad.MQG_EINVAL
     assert L.mqg_sum_squares(None, 10, fake, None) == mqgrad.MQG_EINVAL
     assert L.mqg_sum_squares(fake, 10, vp(0x1004), None) == mqgrad.MQG_EALIGN

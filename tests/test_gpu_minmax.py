@@ -233,6 +233,57 @@ def test_per_tensor_encoding_matches_oracle(bits, n, W):
     assert ulp_distance(params.cpu().numpy(), p1).max() == 0
 
 
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("n,W", [(7, 1), (5000, 3), (100003, 9), (2 * (1 << 20) + 5, 4)])
+def test_per_tensor_exchange_matches_oracle(bits, n, W):
+    # Algorithm 1 as printed with the footnote's encoder and one range per tensor: workers encode, the
+    # server re-encodes the sum over its own whole-tensor range (stored divided by W), a worker decodes
+    # and updates.  The oracle with one bucket that covers the tensor defines every step.
+    grads = [workloads.normal_with_outliers(n, 0.01, 1e-3, 25.0, 13 * w + bits, DEV) - 1e-3 * w for w in range(W)]
+    q = [mqgrad.mqg_quantize_minmax_tensor(g, bits) for g in grads]
+    sentinel = torch.full((mqgrad.mqg_packed_words(n, bits) + 4,), -1, dtype=torch.int32, device=DEV)
+    mean_pk, mean_rg = mqgrad.mqg_aggregate_requantize_minmax_tensor([x[0] for x in q], [x[1] for x in q], n, bits,
+                                                                     packed_out=sentinel)
+    params = workloads.uniform(n, -0.05, 0.05, 5, DEV)
+    p0 = params.cpu().numpy().copy()
+    mqgrad.mqg_aggregate_update_minmax_tensor([mean_pk], [mean_rg], n, bits, 0.2, params)
+    torch.cuda.synchronize()
+    want = [ref.quantize_minmax(g.cpu().numpy(), bits, n) for g in grads]
+    m_pk, m_rg = ref.aggregate_requantize_minmax([x[0] for x in want], [x[1] for x in want], n, bits, n)
+    words = mqgrad.mqg_packed_words(n, bits)
+    assert mean_rg.cpu().numpy().tobytes() == m_rg.tobytes(), (mean_rg.cpu().numpy(), m_rg)
+    assert np.array_equal(to_u32(mean_pk[:words]), m_pk), first_mismatch(to_u32(mean_pk[:words]), m_pk)
+    assert np.all(sentinel[words:].cpu().numpy() == -1)
+    p1 = ref.aggregate_update_minmax([m_pk], [m_rg], n, bits, n, 0.2, p0)
+    assert ulp_distance(params.cpu().numpy(), p1).max() == 0
+
+
+def test_per_tensor_exchange_at_full_size_on_sampled_ranges():
+    # 100 M elements, W = 8: the range of the mean against the oracle's fp32 sum on sampled pieces (a lower
+    # bound on the spread) and the code words of sampled 4096-element tiles against the oracle's encoder
+    # given the GPU's range of the sum
+    n, W, bits = 100_000_000, 8, 4
+    grads = [workloads.config4_grad(w, n, DEV) for w in range(W)]
+    q = [mqgrad.mqg_quantize_minmax_tensor(g, bits) for g in grads]
+    del grads
+    mean_pk, mean_rg = mqgrad.mqg_aggregate_requantize_minmax_tensor([x[0] for x in q], [x[1] for x in q], n, bits)
+    torch.cuda.synchronize()
+    rg = mean_rg.cpu().numpy()
+    ranges = [x[1].cpu().numpy() for x in q]
+    lo_seen, hi_seen = np.inf, -np.inf
+    for start in (0, 4096 * 977, 4096 * 20001, n - 4096 - (n % 4096), n - (n % 4096)):
+        cnt = min(4096, n - start)
+        w0, w1 = start * bits // 32, (start + cnt) * bits // 32 + (1 if ((start + cnt) * bits) % 32 else 0)
+        pieces = [to_u32(x[0][w0:w1]) for x in q]
+        s = ref.aggregate_sum_minmax(pieces, ranges, cnt, bits, cnt)
+        lo_seen, hi_seen = min(lo_seen, float(s.min())), max(hi_seen, float(s.max()))
+        # encode the oracle's sum of the piece over the GPU's range of the whole sum (range * W, exact for W = 8)
+        full = (rg * np.float32(W)).astype(np.float32)
+        want = ref.encode_minmax_given_range(s, bits, full[0], full[1])
+        assert np.array_equal(to_u32(mean_pk[w0:w1]), want), start
+    assert rg[0] * W <= lo_seen and rg[1] * W >= hi_seen and rg[0] < 0 < rg[1]
+
+
 def test_per_tensor_encoding_of_an_unaligned_view():
     base = workloads.normal(50000, 0.01, 3, DEV)
     g = base[3:3 + 40001]

@@ -280,10 +280,13 @@ def test_gradient_norm_is_numpy_norm():
 
 # ---- full exchange with the [min, max] encoding ------------------------------------------------------
 
+@pytest.mark.parametrize("whole_tensor", [False, True])
 @pytest.mark.parametrize("W,bits", [(1, 3), (4, 2), (8, 8), (3, 5)])
-def test_requantized_mean_is_within_half_a_step_of_the_mean(W, bits):
+def test_requantized_mean_is_within_half_a_step_of_the_mean(W, bits, whole_tensor):
+    # whole_tensor: one bucket that covers the tensor -- Algorithm 1 as printed, one range per tensor
     r = rng(W * 13 + bits)
-    n, bucket = 6000 + 5, 256
+    n = 6000 + 5
+    bucket = n if whole_tensor else 256
     grads = [r.normal(2e-3 * w, 1e-2, n).astype(np.float32) for w in range(W)]
     q = [ref.quantize_minmax(g, bits, bucket) for g in grads]
     deq = [ref.dequantize_minmax(x[0], x[1], n, bits, bucket).astype(np.float64) for x in q]
