@@ -178,11 +178,20 @@ typedef struct {
     uint64_t elem_base;    /* multiple of 8: the layer's offset in the model's random stream */
     uint32_t* packed_out;  /* device, mqg_packed_words(n, bits) words */
     float* scales_out;     /* device, mqg_num_buckets(n, bucket) floats */
+    const float* scales_in; /* NULL: the layer's scales are computed; else device, mqg_num_buckets(n, bucket)
+                               floats that are read instead (and copied to scales_out), as in
+                               mqg_quantize_with_scales */
 } mqg_quantize_item;
 
-/* mqg_quantize for `count` layers of one worker.  `items` is a HOST array, read during the call. */
+/* mqg_quantize for `count` layers of one worker.  `items` is a HOST array, read during the call.
+ * mqg_quantize_tensors_mode: the same with the bucket range of mqg_quantize_mode (MQG_SCALE_L2: the
+ * bucket's L2 norm) for the layers whose scales are computed.  Results are bit-identical to the
+ * per-layer calls mqg_quantize / mqg_quantize_mode / mqg_quantize_with_scales. */
 mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
                                 uint64_t seed, uint32_t iteration, uint32_t worker, void* stream);
+mqg_status mqg_quantize_tensors_mode(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
+                                     mqg_scale_mode mode, uint64_t seed, uint32_t iteration, uint32_t worker,
+                                     void* stream);
 
 typedef struct {
     uint64_t n;

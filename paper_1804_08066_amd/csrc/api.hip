@@ -235,7 +235,14 @@ mqg_status mqg_dequantize_update(const uint32_t* packed, const float* scales, ui
 
 mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
                                 uint64_t seed, uint32_t iteration, uint32_t worker, void* stream) {
+    return mqg_quantize_tensors_mode(items, count, bits, bucket, MQG_SCALE_MAXABS, seed, iteration, worker, stream);
+}
+
+mqg_status mqg_quantize_tensors_mode(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
+                                     mqg_scale_mode mode, uint64_t seed, uint32_t iteration, uint32_t worker,
+                                     void* stream) {
     if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (mode != MQG_SCALE_MAXABS && mode != MQG_SCALE_L2) return MQG_EINVAL;
     if (count > MQG_MAX_TENSORS) return MQG_EINVAL;
     if (count == 0) return MQG_OK;
     if (items == nullptr) return MQG_EINVAL;
@@ -245,7 +252,7 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
     a.common.bits = bits;
     a.common.bucket = bucket;
     a.common.bucket_shift = log2_if_pow2(bucket);
-    a.common.scale_mode = MQG_SCALE_MAXABS;
+    a.common.scale_mode = mode;
     a.common.key0 = (uint32_t)seed;
     a.common.key1 = (uint32_t)(seed >> 32);
     a.common.iteration = iteration;
@@ -260,15 +267,17 @@ mqg_status mqg_quantize_tensors(const mqg_quantize_item* items, uint32_t count, 
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
         a.tile_start[i] = (uint32_t)tiles;
         mqg::BatchQuantizeArgs::Tensor& t = a.t[i];
-        t = mqg::BatchQuantizeArgs::Tensor{nullptr, 0, 0, nullptr, nullptr};
+        t = mqg::BatchQuantizeArgs::Tensor{nullptr, 0, 0, nullptr, nullptr, nullptr};
         if (i >= count) continue;
         const mqg_quantize_item& it = items[i];
         if ((it.elem_base & 7u) != 0u) return MQG_EINVAL;
         if (it.n == 0) continue;
         if (it.grad == nullptr || it.packed_out == nullptr || it.scales_out == nullptr) return MQG_EINVAL;
         if (it.n > (UINT64_MAX >> 4) || it.elem_base > UINT64_MAX - it.n) return MQG_EINVAL;
-        if (misaligned4(it.grad) || misaligned4(it.packed_out) || misaligned4(it.scales_out)) return MQG_EALIGN;
-        t = mqg::BatchQuantizeArgs::Tensor{it.grad, it.n, it.elem_base, it.packed_out, it.scales_out};
+        if (misaligned4(it.grad) || misaligned4(it.packed_out) || misaligned4(it.scales_out) || misaligned4(it.scales_in)) {
+            return MQG_EALIGN;
+        }
+        t = mqg::BatchQuantizeArgs::Tensor{it.grad, it.n, it.elem_base, it.packed_out, it.scales_out, it.scales_in};
         tiles += (it.n + a.tile_elems - 1) / a.tile_elems;
         if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
     }

@@ -71,6 +71,7 @@ struct BatchQuantizeArgs {
         uint64_t elem_base;
         uint32_t* packed;
         float* scales;
+        const float* scales_in;   // nullable: the layer's scales are read, not computed
     };
     QuantizeArgs common;      // bits, bucket, stream selection; per-tensor fields are taken from t[]
     uint32_t count;

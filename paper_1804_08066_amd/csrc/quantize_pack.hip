@@ -381,6 +381,7 @@ __global__ __launch_bounds__(kThreads) void quantize_tensors_kernel(const BatchQ
     a.elem_base = ba.t[lo].elem_base;
     a.packed = ba.t[lo].packed;
     a.scales = ba.t[lo].scales;
+    a.scales_in = ba.t[lo].scales_in;
     const uint64_t tile_base = (uint64_t)(blockIdx.x - ba.tile_start[lo]) * ba.tile_elems;
     const uint64_t left = a.n - tile_base;
     const uint32_t tile_count = left < ba.tile_elems ? (uint32_t)left : ba.tile_elems;

@@ -420,6 +420,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
     a.elem_base = ba.t[lo].elem_base;
     a.packed = ba.t[lo].packed;
     a.scales = ba.t[lo].scales;
+    a.scales_in = ba.t[lo].scales_in;
     quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x - ba.tile_start[lo], sm);
 }
 

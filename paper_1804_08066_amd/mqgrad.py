@@ -18,7 +18,7 @@ MQG_MAX_WORKERS = 64
 EXPORTS = [
     "mqg_status_string", "mqg_num_buckets", "mqg_packed_words",
     "mqg_quantize", "mqg_quantize_mode", "mqg_quantize_with_scales", "mqg_aggregate_update",
-    "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_aggregate_mean", "mqg_quantize_tensors", "mqg_aggregate_update_tensors",
+    "mqg_aggregate_requantize", "mqg_dequantize_update", "mqg_aggregate_mean", "mqg_quantize_tensors", "mqg_quantize_tensors_mode", "mqg_aggregate_update_tensors",
     "mqg_quantize_minmax", "mqg_aggregate_update_minmax", "mqg_aggregate_requantize_minmax",
     "mqg_tensor_range", "mqg_quantize_minmax_tensor", "mqg_aggregate_update_minmax_tensor", "mqg_aggregate_requantize_minmax_tensor", "mqg_sum_squares", "mqg_adaptive_default_config",
     "mqg_adaptive_bits",
@@ -53,7 +53,7 @@ class SumsqItem(C.Structure):
 
 class QuantizeItem(C.Structure):
     _fields_ = [("grad", C.c_void_p), ("n", C.c_uint64), ("elem_base", C.c_uint64),
-                ("packed_out", C.c_void_p), ("scales_out", C.c_void_p)]
+                ("packed_out", C.c_void_p), ("scales_out", C.c_void_p), ("scales_in", C.c_void_p)]
 
 
 class UpdateItem(C.Structure):
@@ -102,6 +102,8 @@ def lib():
     L.mqg_dequantize_update.restype = C.c_int
     L.mqg_quantize_tensors.argtypes = [C.POINTER(QuantizeItem), u32, u32, u32, u64, u32, u32, vp]
     L.mqg_quantize_tensors.restype = C.c_int
+    L.mqg_quantize_tensors_mode.argtypes = [C.POINTER(QuantizeItem), u32, u32, u32, C.c_int, u64, u32, u32, vp]
+    L.mqg_quantize_tensors_mode.restype = C.c_int
     L.mqg_aggregate_update_tensors.argtypes = [C.POINTER(UpdateItem), u32, u32, u32, u32, f32, vp]
     L.mqg_aggregate_update_tensors.restype = C.c_int
     L.mqg_quantize_minmax.argtypes = [vp, u64, u32, u32, vp, vp, vp]
@@ -310,10 +312,14 @@ def mqg_dequantize_update(packed, scales, n, bits, bucket, lr, params, stream=No
     return params
 
 
-def mqg_quantize_tensors(grads, bits, bucket, seed, iteration=0, worker=0, elem_bases=None, outputs=None, stream=None):
+def mqg_quantize_tensors(grads, bits, bucket, seed, iteration=0, worker=0, elem_bases=None, outputs=None, stream=None,
+                         scale_mode=MQG_SCALE_MAXABS, scales_in=None):
     """mqg_quantize for a list of layer tensors of one worker in one launch.
-    Returns a list of (packed, scales) per layer."""
+    scale_mode: the bucket range of the layers whose scales are computed; scales_in: optional list with, per
+    layer, None or a float32 tensor of scales to use instead.  Returns a list of (packed, scales) per layer."""
     count = len(grads)
+    if scales_in is None:
+        scales_in = [None] * count
     if elem_bases is None:
         elem_bases = [0] * count
     if outputs is None:
@@ -326,8 +332,15 @@ def mqg_quantize_tensors(grads, bits, bucket, seed, iteration=0, worker=0, elem_
         _check(s, torch.float32, "scales_out")
         if p.numel() < mqg_packed_words(g.numel(), bits) or s.numel() < mqg_num_buckets(g.numel(), bucket):
             raise ValueError("output buffers too small")
-        items[i] = QuantizeItem(g.data_ptr(), g.numel(), elem_bases[i], p.data_ptr(), s.data_ptr())
-    st = lib().mqg_quantize_tensors(items, count, bits, bucket, seed, iteration, worker, _stream_handle(stream))
+        si = scales_in[i]
+        if si is not None:
+            _check(si, torch.float32, "scales_in")
+            if si.numel() < mqg_num_buckets(g.numel(), bucket):
+                raise ValueError("scales_in too small")
+        items[i] = QuantizeItem(g.data_ptr(), g.numel(), elem_bases[i], p.data_ptr(), s.data_ptr(),
+                                si.data_ptr() if si is not None else None)
+    st = lib().mqg_quantize_tensors_mode(items, count, bits, bucket, int(scale_mode), seed, iteration, worker,
+                                         _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_quantize_tensors")
     return outputs

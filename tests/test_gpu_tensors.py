@@ -31,6 +31,41 @@ def test_batched_quantize_equals_per_tensor_and_oracle(bucket):
             assert np.array_equal(outs[i][1].cpu().numpy(), sc_o), "layer %d b=%d" % (i, bits)
 
 
+@pytest.mark.parametrize("bucket", [96, 512, 4096])
+def test_batched_quantize_with_l2_scales_and_injected_scales(bucket):
+    # the bucket's L2 norm as the range, and layers whose scales are given: bit-identical to the per-layer
+    # calls; codes equal the oracle's once the oracle's L2 scales are injected (its norms are summed in fp64)
+    sizes = [4800, 102400, 64, 40000 + 3, 7]
+    bases, run = [], 0
+    for n in sizes:
+        bases.append(run)
+        run += (n + bucket - 1) // bucket * bucket
+    grads = [workloads.laplace(n, 3e-3, 170 + i, DEV) for i, n in enumerate(sizes)]
+    bits = 3
+    outs = mqgrad.mqg_quantize_tensors(grads, bits, bucket, seed=6, iteration=1, worker=3, elem_bases=bases,
+                                       scale_mode=mqgrad.MQG_SCALE_L2)
+    torch.cuda.synchronize()
+    for i, g in enumerate(grads):
+        pk1, sc1 = mqgrad.mqg_quantize(g, bits, bucket, 6, 1, 3, bases[i], mode=mqgrad.MQG_SCALE_L2)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[i][0], pk1) and torch.equal(outs[i][1], sc1), "layer %d" % i
+        sc_o = ref.bucket_scales(g.cpu().numpy(), bucket, ref.SCALE_L2)
+        assert np.all(np.abs(sc1.cpu().numpy() - sc_o) <= 1e-6 * sc_o)
+    # scales of the oracle injected into layers 0, 1 and 3; layers 2 and 4 compute their own (max-abs)
+    inject = [torch.from_numpy(ref.bucket_scales(g.cpu().numpy(), bucket, ref.SCALE_L2)).to(DEV) if i in (0, 1, 3) else None
+              for i, g in enumerate(grads)]
+    outs = mqgrad.mqg_quantize_tensors(grads, bits, bucket, seed=6, iteration=1, worker=3, elem_bases=bases, scales_in=inject)
+    torch.cuda.synchronize()
+    for i, g in enumerate(grads):
+        gh = g.cpu().numpy()
+        if inject[i] is not None:
+            pk_o, sc_o = ref.quantize(gh, bits, bucket, 6, 1, 3, bases[i], scales_in=inject[i].cpu().numpy())
+        else:
+            pk_o, sc_o = ref.quantize(gh, bits, bucket, 6, 1, 3, bases[i])
+        assert np.array_equal(to_u32(outs[i][0]), pk_o), "layer %d" % i
+        assert np.array_equal(outs[i][1].cpu().numpy(), sc_o), "layer %d" % i
+
+
 def test_unaligned_layer_views_in_a_batch():
     base = workloads.normal(30000, 0.01, 5, DEV)
     grads = [base[1:5001], base[6000:6000 + 7000], base[14003:14003 + 999]]
