@@ -53,13 +53,13 @@ struct CodeRegs {
     uint32_t lo[CH][R];
 };
 
-// A wave's code words of one row and worker are 32*bits contiguous bytes.  At 4 and 8 bits that is
-// one or two whole 128-byte lines which no other wave touches, and the load carries the streaming
-// hint like every other read-once access.  At the other widths neighbouring waves read the rest of
-// the same line, and a streaming load would fetch it from L2 once per wave: there the loads are
-// ordinary ones, so that the vector L1 serves the neighbours (measured at 100 M elements, W = 8:
-// 7-11 % faster at 1, 2, 3, 5, 7 bits; 6 bits is 2 % faster with the hint).
-inline __host__ __device__ bool codes_read_once(uint32_t b) { return b >= 4u && (b & 1u) == 0u; }
+// A wave's code words of one row and worker are 32*bits contiguous bytes.  From 4 bits on the loads
+// carry the streaming hint like every other read-once access; below that neighbouring waves read the
+// rest of the same 128-byte line and a streaming load would fetch it from L2 once per wave, so the loads
+// are ordinary ones and the vector L1 serves the neighbours.  Measured at 100 M elements, W = 8, with the
+// code words written by the quantizer's agent-scope stores just before: the hint is 6-8 % faster at 5
+// and 7 bits, level at 4, 6 and 8, and 7-9 % slower at 2 and 3 bits.
+inline __host__ __device__ bool codes_read_once(uint32_t b) { return b >= 4u; }
 
 // Fetch the first code word of each of the lane's quads for workers [w0, min(w0 + CH, W)): one
 // aligned dword load per worker and quad, all issued before any is consumed.  Adjacent lanes read
