@@ -52,7 +52,7 @@ __global__ __launch_bounds__(64 * NW) void stream_quantize_kernel(const float* _
 // One workgroup per 2048 parameters (2 float4 per lane, streaming loads and stores, as the server
 // kernel moves them); each lane also reads, per worker and row, the dword that holds its quad's codes
 // (a wave's request is one contiguous run of 32 * bits bytes; the loads of eight workers are issued
-// together; streaming loads where a wave's run is whole cache lines, as in the server kernel).  All
+// together; streaming loads from 4 bits on, as in the server kernel).  All
 // values are folded into what is stored.
 constexpr int kMaxW = 64;
 struct UpdateArgs {
@@ -133,7 +133,7 @@ int mqg_bench_stream_update(const uint32_t* const* codes, uint32_t W, uint64_t n
     a.params = params;
     const dim3 grid((uint32_t)(n / 2048u)), block(256);
     hipStream_t st = (hipStream_t)stream;
-    const bool once = bits == 4u || bits == 6u || bits == 8u;
+    const bool once = bits >= 4u;   // the server kernel's rule: streaming loads of the code words from 4 bits on
     if (once && shape == 0u) hipLaunchKernelGGL((stream_update_kernel<true, 8>), grid, block, 0, st, a);
     if (once && shape == 1u) hipLaunchKernelGGL((stream_update_kernel<true, 4>), grid, block, 0, st, a);
     if (!once && shape == 0u) hipLaunchKernelGGL((stream_update_kernel<false, 8>), grid, block, 0, st, a);
