@@ -275,6 +275,28 @@ mqg_status mqg_aggregate_requantize_minmax_tensor(const uint32_t* const* packed,
                                                   uint32_t W, uint64_t n, uint32_t bits,
                                                   uint32_t* packed_out, float* range_out, void* stream);
 
+/* Several layer tensors per launch with this encoding (Section 4.1: the two large fully connected layers
+ * are encoded, each over its own range, and the other layers travel as fp32) -- the [min, max] forms of
+ * mqg_quantize_tensors and mqg_aggregate_update_tensors, with the same limits (MQG_MAX_TENSORS,
+ * MQG_MAX_TENSOR_POINTERS).  Results are bit-identical to the per-layer calls.
+ *
+ * mqg_quantize_minmax_tensors: `items` is a HOST array, read during the call.
+ *   bucket > 0   mqg_quantize_minmax for every layer in ONE launch; items[i].scales_out receives the
+ *                layer's 2 * mqg_num_buckets(n, bucket) floats.
+ *   bucket == 0  one range per layer, as the paper encodes: mqg_quantize_minmax_tensor for every layer --
+ *                a batched range reduction, then a batched encode (four launches for any number of
+ *                layers); items[i].scales_out receives the layer's 2 floats.
+ *   items[i].scales_out must be 8-byte aligned; items[i].scales_in must be NULL (MQG_EINVAL otherwise);
+ *   items[i].elem_base is not read (no random numbers are drawn).
+ * mqg_aggregate_update_minmax_tensors: mqg_aggregate_update_minmax (bucket > 0) or
+ *   mqg_aggregate_update_minmax_tensor (bucket == 0) for `count` layers in one launch; items[i].scales[w]
+ *   is worker w's range array of layer i (8-byte aligned); a layer with packed == NULL is uncompressed
+ *   and updated as in mqg_aggregate_update_tensors. */
+mqg_status mqg_quantize_minmax_tensors(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
+                                       void* stream);
+mqg_status mqg_aggregate_update_minmax_tensors(const mqg_update_item* items, uint32_t count, uint32_t W,
+                                               uint32_t bits, uint32_t bucket, float lr, void* stream);
+
 /* ---- the "Adaptive" baseline's bit rule (Section 4.1; idea in Section 2: the larger the gradient's
  * norm, the more bits) ------------------------------------------------------------------------------
  *

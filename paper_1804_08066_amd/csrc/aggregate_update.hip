@@ -188,25 +188,7 @@ __device__ __forceinline__ void aggregate_tile_lds(const uint32_t* const* packed
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 
     if (raw != nullptr) {
-        // uncompressed layer: plain fp32 sum in worker order
-        for (uint32_t w = 0; w < W; ++w) {
-            const float* __restrict__ g = raw[w] + tile_base;
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const uint32_t el = 4u * (j * kThreads + tid);
-                if (full || el + 4u <= tile_count) {
-                    const float4 t = load_f4_stream(g + el);
-                    acc[j].x = acc[j].x + t.x;
-                    acc[j].y = acc[j].y + t.y;
-                    acc[j].z = acc[j].z + t.z;
-                    acc[j].w = acc[j].w + t.w;
-                } else {
-                    if (el + 0u < tile_count) acc[j].x = acc[j].x + g[el + 0];
-                    if (el + 1u < tile_count) acc[j].y = acc[j].y + g[el + 1];
-                    if (el + 2u < tile_count) acc[j].z = acc[j].z + g[el + 2];
-                }
-            }
-        }
+        tile_io::accumulate_raw<R>(raw, W, tile_base, tile_count, full, acc);   // uncompressed layer: plain fp32 sum in worker order
         update_params<R>(p, tile_count, full, neg_c, x, acc);
         return;
     }

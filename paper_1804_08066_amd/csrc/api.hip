@@ -72,6 +72,63 @@ mqg_status sumsq_batch_args(const mqg_sumsq_item* items, uint32_t count, const d
     return MQG_OK;
 }
 
+// Fills the launch table of a batched server step; `minmax`: the scale arrays hold (min, max) pairs and
+// must be 8-byte aligned.  MQG_OK with *tiles_out == 0 when there is nothing to do.
+mqg_status update_batch_args(const mqg_update_item* items, uint32_t count, uint32_t W, uint32_t bits,
+                                    uint32_t bucket, float lr, bool minmax, uint32_t tile,
+                                    mqg::BatchAggregateArgs& a, uint32_t* tiles_out) {
+    *tiles_out = 0;
+    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    if (count > MQG_MAX_TENSORS) return MQG_EINVAL;
+    if (count == 0) return MQG_OK;
+    if (items == nullptr) return MQG_EINVAL;
+    a.count = count;
+    a.W = W;
+    a.bits = bits;
+    a.bucket = bucket;
+    a.bucket_shift = log2_if_pow2(bucket);
+    a.neg_c = -(lr / (float)W);
+    a.per_tensor = 0u;
+    for (uint32_t i = 0; i < mqg::kMaxBatchPointers; ++i) a.ptrs[i] = nullptr;
+    uint64_t tiles = 0;
+    uint32_t used = 0;
+    for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
+        a.tile_start[i] = (uint32_t)tiles;
+        a.t[i] = mqg::BatchAggregateArgs::Tensor{0, nullptr, 0, 0};
+        if (i >= count) continue;
+        const mqg_update_item& it = items[i];
+        if (it.n == 0) continue;
+        if (it.params == nullptr || it.n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+        if (misaligned4(it.params)) return MQG_EALIGN;
+        const bool raw = it.packed == nullptr;
+        const uint32_t need = raw ? W : 2u * W;
+        if (used + need > mqg::kMaxBatchPointers) return MQG_EINVAL;
+        if (raw) {
+            if (it.raw == nullptr) return MQG_EINVAL;
+            for (uint32_t w = 0; w < W; ++w) {
+                if (it.raw[w] == nullptr) return MQG_EINVAL;
+                if (misaligned4(it.raw[w])) return MQG_EALIGN;
+                a.ptrs[used + w] = it.raw[w];
+            }
+        } else {
+            if (it.scales == nullptr) return MQG_EINVAL;
+            for (uint32_t w = 0; w < W; ++w) {
+                if (it.packed[w] == nullptr || it.scales[w] == nullptr) return MQG_EINVAL;
+                if (misaligned4(it.packed[w]) || (minmax ? misaligned8(it.scales[w]) : misaligned4(it.scales[w]))) return MQG_EALIGN;
+                a.ptrs[used + w] = it.packed[w];
+                a.ptrs[used + W + w] = it.scales[w];
+            }
+        }
+        a.t[i] = mqg::BatchAggregateArgs::Tensor{it.n, it.params, used, raw ? 1u : 0u};
+        used += need;
+        tiles += (it.n + tile - 1) / tile;
+        if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
+    }
+    a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
+    *tiles_out = (uint32_t)tiles;
+    return MQG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -289,55 +346,73 @@ mqg_status mqg_quantize_tensors_mode(const mqg_quantize_item* items, uint32_t co
 mqg_status mqg_aggregate_update_tensors(const mqg_update_item* items, uint32_t count, uint32_t W,
                                         uint32_t bits, uint32_t bucket, float lr, void* stream) {
     if (!valid_common(bits, bucket)) return MQG_EINVAL;
-    if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
+    mqg::BatchAggregateArgs a;
+    uint32_t tiles = 0;
+    const mqg_status st = update_batch_args(items, count, W, bits, bucket, lr, false, mqg::aggregate_batch_tile(), a, &tiles);
+    if (st != MQG_OK || tiles == 0) return st;
+    const hipError_t err = mqg::launch_aggregate_tensors(a, tiles, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_aggregate_update_minmax_tensors(const mqg_update_item* items, uint32_t count, uint32_t W,
+                                               uint32_t bits, uint32_t bucket, float lr, void* stream) {
+    const bool per_tensor = bucket == 0u;
+    if (per_tensor ? (bits < 1u || bits > 8u) : !valid_common(bits, bucket)) return MQG_EINVAL;
+    mqg::BatchAggregateArgs a;
+    uint32_t tiles = 0;
+    const mqg_status st = update_batch_args(items, count, W, bits, per_tensor ? 1024u : bucket, lr, true,
+                                            mqg::aggregate_minmax_batch_tile(), a, &tiles);
+    if (st != MQG_OK || tiles == 0) return st;
+    a.per_tensor = per_tensor ? 1u : 0u;
+    const hipError_t err = mqg::launch_aggregate_minmax_tensors(a, tiles, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
+}
+
+mqg_status mqg_quantize_minmax_tensors(const mqg_quantize_item* items, uint32_t count, uint32_t bits, uint32_t bucket,
+                                       void* stream) {
+    const bool per_tensor = bucket == 0u;
+    if (per_tensor ? (bits < 1u || bits > 8u) : !valid_common(bits, bucket)) return MQG_EINVAL;
     if (count > MQG_MAX_TENSORS) return MQG_EINVAL;
     if (count == 0) return MQG_OK;
     if (items == nullptr) return MQG_EINVAL;
-    mqg::BatchAggregateArgs a;
+    mqg::BatchQuantizeArgs a;
+    a.common = mqg::QuantizeArgs{};
+    a.common.bits = bits;
+    a.common.bucket = per_tensor ? 1024u : bucket;      // a given range: the bucket only shapes the launch
+    a.common.bucket_shift = log2_if_pow2(a.common.bucket);
     a.count = count;
-    a.W = W;
-    a.bits = bits;
-    a.bucket = bucket;
-    a.bucket_shift = log2_if_pow2(bucket);
-    a.neg_c = -(lr / (float)W);
-    for (uint32_t i = 0; i < mqg::kMaxBatchPointers; ++i) a.ptrs[i] = nullptr;
-    const uint32_t tile = mqg::aggregate_batch_tile();
+    a.tile_elems = mqg::quantize_minmax_batch_tile(a.common.bucket, a.common.bucket_shift);
+    mqg::TensorRangeBatch rb;
     uint64_t tiles = 0;
-    uint32_t used = 0;
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
         a.tile_start[i] = (uint32_t)tiles;
-        a.t[i] = mqg::BatchAggregateArgs::Tensor{0, nullptr, 0, 0};
+        a.t[i] = mqg::BatchQuantizeArgs::Tensor{nullptr, 0, 0, nullptr, nullptr, nullptr};
+        rb.grad[i] = nullptr;
+        rb.n[i] = 0;
+        rb.range[i] = nullptr;
         if (i >= count) continue;
-        const mqg_update_item& it = items[i];
+        const mqg_quantize_item& it = items[i];
+        if (it.scales_in != nullptr) return MQG_EINVAL;   // this encoder derives every range from the data
         if (it.n == 0) continue;
-        if (it.params == nullptr || it.n > (UINT64_MAX >> 4)) return MQG_EINVAL;
-        if (misaligned4(it.params)) return MQG_EALIGN;
-        const bool raw = it.packed == nullptr;
-        const uint32_t need = raw ? W : 2u * W;
-        if (used + need > mqg::kMaxBatchPointers) return MQG_EINVAL;
-        if (raw) {
-            if (it.raw == nullptr) return MQG_EINVAL;
-            for (uint32_t w = 0; w < W; ++w) {
-                if (it.raw[w] == nullptr) return MQG_EINVAL;
-                if (misaligned4(it.raw[w])) return MQG_EALIGN;
-                a.ptrs[used + w] = it.raw[w];
-            }
+        if (it.grad == nullptr || it.packed_out == nullptr || it.scales_out == nullptr) return MQG_EINVAL;
+        if (it.n > (UINT64_MAX >> 4)) return MQG_EINVAL;
+        if (misaligned4(it.grad) || misaligned4(it.packed_out) || misaligned8(it.scales_out)) return MQG_EALIGN;
+        if (per_tensor) {
+            a.t[i] = mqg::BatchQuantizeArgs::Tensor{it.grad, it.n, 0, it.packed_out, nullptr, it.scales_out};
+            rb.grad[i] = it.grad;
+            rb.n[i] = it.n;
+            rb.range[i] = it.scales_out;
         } else {
-            if (it.scales == nullptr) return MQG_EINVAL;
-            for (uint32_t w = 0; w < W; ++w) {
-                if (it.packed[w] == nullptr || it.scales[w] == nullptr) return MQG_EINVAL;
-                if (misaligned4(it.packed[w]) || misaligned4(it.scales[w])) return MQG_EALIGN;
-                a.ptrs[used + w] = it.packed[w];
-                a.ptrs[used + W + w] = it.scales[w];
-            }
+            a.t[i] = mqg::BatchQuantizeArgs::Tensor{it.grad, it.n, 0, it.packed_out, it.scales_out, nullptr};
         }
-        a.t[i] = mqg::BatchAggregateArgs::Tensor{it.n, it.params, used, raw ? 1u : 0u};
-        used += need;
-        tiles += (it.n + tile - 1) / tile;
+        tiles += (it.n + a.tile_elems - 1) / a.tile_elems;
         if (tiles > 0x7FFFFFFFull) return MQG_EINVAL;
     }
     a.tile_start[mqg::kMaxBatchTensors] = (uint32_t)tiles;
-    const hipError_t err = mqg::launch_aggregate_tensors(a, (uint32_t)tiles, static_cast<hipStream_t>(stream));
+    if (tiles == 0) return MQG_OK;
+    hipError_t err = hipSuccess;
+    if (per_tensor) err = mqg::launch_tensor_range_batch(rb, count, static_cast<hipStream_t>(stream));
+    if (err == hipSuccess) err = mqg::launch_quantize_minmax_tensors(a, (uint32_t)tiles, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
 

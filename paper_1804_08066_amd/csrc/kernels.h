@@ -59,6 +59,7 @@ struct BatchAggregateArgs {
     uint32_t count, W, bits, bucket;
     int bucket_shift;
     float neg_c;
+    uint32_t per_tensor;      // [min, max] encoding only: ONE (min, max) pair per worker and tensor
     uint32_t tile_start[kMaxBatchTensors + 1];   // prefix sums of the tensors' tile counts
     Tensor t[kMaxBatchTensors];
     const void* ptrs[kMaxBatchPointers];
@@ -104,6 +105,19 @@ hipError_t launch_aggregate_minmax(const AggregateArgs& a, hipStream_t stream);
 hipError_t launch_requantize_minmax(const RequantArgs& a, hipStream_t stream);
 hipError_t launch_requantize_minmax_tensor(const RequantArgs& a, hipStream_t stream);   // one range per worker and for the mean
 hipError_t launch_tensor_range(const float* grad, uint64_t n, float* range_out, hipStream_t stream);
+// the same for several layer tensors per launch
+struct TensorRangeBatch {
+    const float* grad[kMaxBatchTensors];
+    uint64_t n[kMaxBatchTensors];
+    float* range[kMaxBatchTensors];   // 2 floats each; nullptr: no such tensor (or an empty one)
+};
+hipError_t launch_tensor_range_batch(const TensorRangeBatch& b, uint32_t count, hipStream_t stream);
+uint32_t quantize_minmax_wave_block_elems(uint32_t bucket);                                       // quantize_wave.hip
+hipError_t launch_quantize_minmax_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream);
+uint32_t quantize_minmax_batch_tile(uint32_t bucket, int bucket_shift);   // elements per workgroup
+hipError_t launch_quantize_minmax_tensors(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream);
+uint32_t aggregate_minmax_batch_tile();
+hipError_t launch_aggregate_minmax_tensors(const BatchAggregateArgs& a, uint32_t tiles, hipStream_t stream);
 hipError_t launch_sum_squares(const float* grad, uint64_t n, double* out, hipStream_t stream);
 
 // Sums of squares of several tensors in one launch, each added up in a fixed order.

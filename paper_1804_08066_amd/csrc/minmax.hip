@@ -215,9 +215,9 @@ __device__ __forceinline__ void encode_minmax_tile(const QuantizeArgs& a, const 
 
 // Bucket sizes that are not powers of two (the others take the wave-local kernel in quantize_wave.hip).
 template <int R, int NT>
-__global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
-    __shared__ Shared<R, NT> sm;
-    const uint64_t tile_base = (uint64_t)blockIdx.x * tile_elems;
+__device__ __forceinline__ void quantize_minmax_tile(const QuantizeArgs& a, const uint32_t tile, const uint32_t tile_elems,
+                                                     Shared<R, NT>& sm) {
+    const uint64_t tile_base = (uint64_t)tile * tile_elems;
     const uint64_t left = a.n - tile_base;
     const uint32_t tile_count = left < tile_elems ? (uint32_t)left : tile_elems;
     float4 x[R];
@@ -232,6 +232,30 @@ __global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs 
         __syncthreads();
         encode_minmax_tile<R, NT, false>(a, tile_base, tile_count, x, 1.0f, sm);
     }
+}
+
+template <int R, int NT>
+__global__ __launch_bounds__(NT) void quantize_minmax_kernel(const QuantizeArgs a, const uint32_t tile_elems) {
+    __shared__ Shared<R, NT> sm;
+    quantize_minmax_tile<R, NT>(a, blockIdx.x, tile_elems, sm);
+}
+
+// Several layer tensors in one launch: workgroup -> (tensor, tile of the tensor) through the prefix
+// table of tile counts.
+template <int R, int NT>
+__global__ __launch_bounds__(NT) void quantize_minmax_tensors_kernel(const BatchQuantizeArgs ba) {
+    __shared__ Shared<R, NT> sm;
+    uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= ba.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    QuantizeArgs a = ba.common;
+    a.grad = ba.t[lo].grad;
+    a.n = ba.t[lo].n;
+    a.packed = ba.t[lo].packed;
+    a.scales = ba.t[lo].scales;
+    quantize_minmax_tile<R, NT>(a, blockIdx.x - ba.tile_start[lo], ba.tile_elems, sm);
 }
 
 // The server's re-encoding step of the full exchange (ReceiveQGThenSendQG): the tile's values are the
@@ -407,28 +431,48 @@ constexpr int kAggR = 2;
 constexpr uint32_t kAggTile = 1024u * kAggR;
 constexpr uint32_t kMaxBuckets = kAggTile / 32u + 1u;   // buckets a tile can touch
 
+// One tile of one tensor.  The fields of `a` that name the tensor (n, params, packed, scales) are not
+// read: the tensor comes in through the arguments, so that one launch can serve several.  raw != nullptr:
+// an uncompressed layer whose W fp32 gradients are added in worker order instead of decoded.
+struct TileTensor {
+    const uint32_t* const* packed;
+    const float* const* scales;
+    const float* const* raw;
+    uint64_t n;
+    float* params;
+};
+struct TileCommon {
+    uint32_t W, bits, bucket;
+    int bucket_shift;
+    uint32_t per_tensor;
+    float neg_c;
+};
 template <bool STRADDLE, bool ONCE>
-__global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const AggregateArgs a) {
-    extern __shared__ float2 s_tab[];   // [W][nbt]: (step, min) of each worker's buckets of the tile
+__device__ __forceinline__ void aggregate_minmax_tile(const TileCommon& a, const TileTensor& t, const uint64_t tile_base,
+                                                      float2* s_tab) {
     constexpr int R = kAggR;
     const uint32_t tid = threadIdx.x;
-    const uint64_t tile_base = (uint64_t)blockIdx.x * kAggTile;
-    const uint64_t left = a.n - tile_base;
+    const uint64_t left = t.n - tile_base;
     const uint32_t tile_count = left < kAggTile ? (uint32_t)left : kAggTile;
     const bool full = tile_count == kAggTile;
-    float* __restrict__ p = a.params + tile_base;
+    float* __restrict__ p = t.params + tile_base;
 
     float4 x[R];
     tile_io::load_params<R>(p, tile_count, full, x);
     float4 acc[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) acc[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (t.raw != nullptr) {
+        tile_io::accumulate_raw<R>(t.raw, a.W, tile_base, tile_count, full, acc);
+        tile_io::update_params<R>(p, tile_count, full, a.neg_c, x, acc);
+        return;
+    }
 
     const uint32_t b = a.bits;
     const float Lf = (float)((1u << b) - 1u);
-    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(a.n, tile_base, b, tid);
+    const decode::CodeWindows<R> cw = decode::code_windows<R, kThreads>(t.n, tile_base, b, tid);
     decode::CodeRegs<R, kChunk> c;
-    decode::fetch_codes<R, kChunk, ONCE>(a.packed, a.W, 0u, cw, c);   // in flight while the table is filled
+    decode::fetch_codes<R, kChunk, ONCE>(t.packed, a.W, 0u, cw, c);   // in flight while the table is filled
 
     const uint64_t kb0 = tile_base / a.bucket;
     const uint32_t nbt = (uint32_t)((tile_base + tile_count - 1u) / a.bucket - kb0) + 1u;   // <= kMaxBuckets
@@ -442,13 +486,13 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
     }
     for (uint32_t i = tid; i < a.W * nbt; i += kThreads) {
         const uint32_t w = i / nbt, kb = i - w * nbt;
-        const float2 rg = reinterpret_cast<const float2*>(a.scales[w])[a.per_tensor ? 0u : kb0 + kb];   // (min, max)
+        const float2 rg = reinterpret_cast<const float2*>(t.scales[w])[a.per_tensor ? 0u : kb0 + kb];   // (min, max)
         s_tab[i] = make_float2((rg.y - rg.x) / Lf, rg.x);                           // IEEE-correct fp32 division
     }
     __syncthreads();
 
     for (uint32_t w0 = 0; w0 < a.W; w0 += kChunk) {
-        if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(a.packed, a.W, w0, cw, c);
+        if (w0 > 0) decode::fetch_codes<R, kChunk, ONCE>(t.packed, a.W, w0, cw, c);
 #pragma unroll
         for (int t = 0; t < kChunk; ++t) {
             if (w0 + t < a.W) {
@@ -462,6 +506,37 @@ __global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const
         }
     }
     tile_io::update_params<R>(p, tile_count, full, a.neg_c, x, acc);
+}
+
+template <bool STRADDLE, bool ONCE>
+__global__ __launch_bounds__(kThreads) void aggregate_update_minmax_kernel(const AggregateArgs a) {
+    extern __shared__ float2 s_tab[];   // [W][nbt]: (step, min) of each worker's buckets of the tile
+    const TileCommon c = {a.W, a.bits, a.bucket, a.bucket_shift, a.per_tensor, a.neg_c};
+    const TileTensor t = {a.packed, a.scales, nullptr, a.n, a.params};
+    aggregate_minmax_tile<STRADDLE, ONCE>(c, t, (uint64_t)blockIdx.x * kAggTile, s_tab);
+}
+
+// Several tensors of a model in one launch: block -> (tensor, tile) through the prefix table of tile
+// counts.  A tensor is either encoded (W packed + W range pointers) or raw (W fp32 gradients).
+template <bool STRADDLE, bool ONCE>
+__global__ __launch_bounds__(kThreads) void aggregate_update_minmax_tensors_kernel(const BatchAggregateArgs a) {
+    extern __shared__ float2 s_tab[];
+    uint32_t lo = 0, hi = a.count;           // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= a.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    const BatchAggregateArgs::Tensor& bt = a.t[lo];
+    const void* const* ptrs = a.ptrs + bt.first_ptr;
+    const TileCommon c = {a.W, a.bits, a.bucket, a.bucket_shift, a.per_tensor, a.neg_c};
+    TileTensor t = {nullptr, nullptr, nullptr, bt.n, bt.params};
+    if (bt.raw) {
+        t.raw = reinterpret_cast<const float* const*>(ptrs);
+    } else {
+        t.packed = reinterpret_cast<const uint32_t* const*>(ptrs);
+        t.scales = reinterpret_cast<const float* const*>(ptrs + a.W);
+    }
+    aggregate_minmax_tile<STRADDLE, ONCE>(c, t, (uint64_t)(blockIdx.x - a.tile_start[lo]) * kAggTile, s_tab);
 }
 
 // ---- whole-tensor range ---------------------------------------------------------------------------
@@ -482,17 +557,17 @@ __global__ void range_finish_kernel(uint32_t* keys) {
     keys[1] = __builtin_bit_cast(uint32_t, mx);
 }
 
-__global__ __launch_bounds__(kSumThreads) void tensor_range_kernel(const float* __restrict__ g, const uint64_t n,
-                                                                   uint32_t* keys) {
-    __shared__ uint32_t s_lo[kSumThreads / 64], s_hi[kSumThreads / 64];
+// The calling workgroup (`block` of `nblocks`) folds its share of g[0..n) into keys[0..1].
+__device__ __forceinline__ void block_range(const float* __restrict__ g, const uint64_t n, const uint32_t block,
+                                            const uint32_t nblocks, uint32_t* keys, uint32_t* s_lo, uint32_t* s_hi) {
     const uint32_t tid = threadIdx.x;
-    const uint64_t gtid = (uint64_t)blockIdx.x * kSumThreads + tid;
-    const uint64_t stride = (uint64_t)gridDim.x * kSumThreads;
+    const uint64_t gtid = (uint64_t)block * kSumThreads + tid;
+    const uint64_t stride = (uint64_t)nblocks * kSumThreads;
     float lo = __builtin_inff(), hi = -__builtin_inff();
     const v4f_a4* __restrict__ g4 = reinterpret_cast<const v4f_a4*>(g);   // 128-bit loads need dword alignment only
     const uint64_t nq = n >> 2;
     const uint64_t pieces = nq / (4u * kSumThreads);   // contiguous 32 KB pieces, four float4 per lane in flight
-    for (uint64_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
+    for (uint64_t pc = block; pc < pieces; pc += nblocks) {
         const v4f_a4* __restrict__ src = g4 + pc * (4u * kSumThreads) + tid;
         v4f t[4];
 #pragma unroll
@@ -530,6 +605,38 @@ __global__ __launch_bounds__(kSumThreads) void tensor_range_kernel(const float* 
         // stale read can cause a needless atomic but never a wrong skip.
         if (kl < __atomic_load_n(&keys[0], __ATOMIC_RELAXED)) atomicMin(&keys[0], kl);
         if (kh > __atomic_load_n(&keys[1], __ATOMIC_RELAXED)) atomicMax(&keys[1], kh);
+    }
+}
+
+__global__ __launch_bounds__(kSumThreads) void tensor_range_kernel(const float* __restrict__ g, const uint64_t n,
+                                                                   uint32_t* keys) {
+    __shared__ uint32_t s_lo[kSumThreads / 64], s_hi[kSumThreads / 64];
+    block_range(g, n, blockIdx.x, gridDim.x, keys, s_lo, s_hi);
+}
+
+// The ranges of several tensors: grid (blocks, tensors); thread k of the one-workgroup kernels before
+// and after primes / converts the keys of tensor k.  Empty tensors have no range array.
+__global__ void range_init_batch_kernel(const TensorRangeBatch b, uint32_t count) {
+    if (threadIdx.x < count && b.range[threadIdx.x] != nullptr) {
+        uint32_t* keys = reinterpret_cast<uint32_t*>(b.range[threadIdx.x]);
+        keys[0] = 0xFFFFFFFFu;
+        keys[1] = 0u;
+    }
+}
+__global__ __launch_bounds__(kSumThreads) void tensor_range_batch_kernel(const TensorRangeBatch b) {
+    __shared__ uint32_t s_lo[kSumThreads / 64], s_hi[kSumThreads / 64];
+    const uint32_t k = blockIdx.y;
+    if (b.range[k] == nullptr) return;
+    block_range(b.grad[k], b.n[k], blockIdx.x, gridDim.x, reinterpret_cast<uint32_t*>(b.range[k]), s_lo, s_hi);
+}
+__global__ void range_finish_batch_kernel(const TensorRangeBatch b, uint32_t count) {
+    if (threadIdx.x < count && b.range[threadIdx.x] != nullptr) {
+        uint32_t* keys = reinterpret_cast<uint32_t*>(b.range[threadIdx.x]);
+        float mn = key_value(keys[0]), mx = key_value(keys[1]);
+        if (mn == 0.0f) mn = 0.0f;   // a zero bound is stored as +0
+        if (mx == 0.0f) mx = 0.0f;
+        keys[0] = __builtin_bit_cast(uint32_t, mn);
+        keys[1] = __builtin_bit_cast(uint32_t, mx);
     }
 }
 
@@ -681,6 +788,61 @@ hipError_t launch_quantize_minmax(const QuantizeArgs& a, hipStream_t stream) {
     if (a.bucket <= 4096u) return launch_quantize_r<4, 256>(a, stream);
     if (a.bucket <= 8192u) return launch_quantize_r<4, 512>(a, stream);
     return launch_quantize_r<4, 1024>(a, stream);
+}
+
+// The general tile of the batched encoder: R = 4 with the workgroup size that the bucket needs.
+uint32_t quantize_minmax_batch_tile(uint32_t bucket, int bucket_shift) {
+    if (bucket_shift >= 5) return quantize_minmax_wave_block_elems(bucket);
+    const uint32_t cap = bucket <= 4096u ? Shared<4, 256>::kCap : (bucket <= 8192u ? Shared<4, 512>::kCap : Shared<4, 1024>::kCap);
+    return (cap / bucket) * bucket;
+}
+
+// a.t[i].scales: (min, max) pairs of tensor i's buckets; a.t[i].scales_in: nullptr, or the ONE (min, max)
+// pair of tensor i (then nothing is written to scales and the bucket only shapes the launch: it must be
+// a power of two)
+hipError_t launch_quantize_minmax_tensors(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream) {
+    if (tiles == 0) return hipSuccess;
+    if (a.common.bucket_shift >= 5) return launch_quantize_minmax_tensors_wave(a, tiles, stream);
+    const dim3 grid(tiles);
+    if (a.common.bucket <= 4096u) hipLaunchKernelGGL((quantize_minmax_tensors_kernel<4, 256>), grid, dim3(256), 0, stream, a);
+    else if (a.common.bucket <= 8192u) hipLaunchKernelGGL((quantize_minmax_tensors_kernel<4, 512>), grid, dim3(512), 0, stream, a);
+    else hipLaunchKernelGGL((quantize_minmax_tensors_kernel<4, 1024>), grid, dim3(1024), 0, stream, a);
+    return hipGetLastError();
+}
+
+// range[k][0..1] <- min, max of tensor k; three launches on the stream
+hipError_t launch_tensor_range_batch(const TensorRangeBatch& b, uint32_t count, hipStream_t stream) {
+    uint64_t most = 0;
+    for (uint32_t k = 0; k < count; ++k) {
+        if (b.range[k] != nullptr && b.n[k] > most) most = b.n[k];
+    }
+    if (most == 0) return hipSuccess;
+    uint64_t blocks = ((most >> 2) + kSumThreads - 1) / kSumThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > kSumBlocks) blocks = kSumBlocks;
+    hipLaunchKernelGGL(range_init_batch_kernel, dim3(1), dim3(64), 0, stream, b, count);
+    hipLaunchKernelGGL(tensor_range_batch_kernel, dim3((uint32_t)blocks, count), dim3(kSumThreads), 0, stream, b);
+    hipLaunchKernelGGL(range_finish_batch_kernel, dim3(1), dim3(64), 0, stream, b, count);
+    return hipGetLastError();
+}
+
+uint32_t aggregate_minmax_batch_tile() { return kAggTile; }
+
+// a.ptrs: per encoded tensor [W packed][W range arrays], per raw tensor [W fp32 gradients]
+hipError_t launch_aggregate_minmax_tensors(const BatchAggregateArgs& a, uint32_t tiles, hipStream_t stream) {
+    if (tiles == 0) return hipSuccess;
+    const dim3 grid(tiles), block(kThreads);
+    const size_t lds = sizeof(float2) * a.W * kMaxBuckets;
+    const bool straddle = (32u % a.bits) != 0u;
+    const bool once = decode::codes_read_once(a.bits);
+    if (straddle) {
+        if (once) hipLaunchKernelGGL((aggregate_update_minmax_tensors_kernel<true, true>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((aggregate_update_minmax_tensors_kernel<true, false>), grid, block, lds, stream, a);
+    } else {
+        if (once) hipLaunchKernelGGL((aggregate_update_minmax_tensors_kernel<false, true>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((aggregate_update_minmax_tensors_kernel<false, false>), grid, block, lds, stream, a);
+    }
+    return hipGetLastError();
 }
 
 // a.scales[w]: worker w's (min, max) pairs

@@ -720,16 +720,15 @@ __device__ __forceinline__ void encode_minmax_and_pack(const QuantizeArgs& a, ui
 }
 
 template <int R, int WPB, int NW>
-__global__ __launch_bounds__(64 * NW) void quantize_minmax_wave_kernel(const QuantizeArgs a) {
+__device__ __forceinline__ void quantize_minmax_wave_block(const QuantizeArgs& a, const uint32_t block, WaveShared<R, NW>& sm,
+                                                           WaveLows<R, NW>& lw) {
     constexpr uint32_t CH = 256u * R;
     static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
-    __shared__ WaveShared<R, NW> sm;
-    __shared__ WaveLows<R, NW> lw;
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
-    const uint64_t chunk = (uint64_t)blockIdx.x * NW + wave;
+    const uint64_t chunk = (uint64_t)block * NW + wave;
     const uint64_t cb = chunk * CH;
     const bool active = cb < a.n;                   // waves past the end only keep the barrier company
     const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
@@ -766,6 +765,32 @@ __global__ __launch_bounds__(64 * NW) void quantize_minmax_wave_kernel(const Qua
     } else {
         encode_minmax_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
     }
+}
+
+template <int R, int WPB, int NW>
+__global__ __launch_bounds__(64 * NW) void quantize_minmax_wave_kernel(const QuantizeArgs a) {
+    __shared__ WaveShared<R, NW> sm;
+    __shared__ WaveLows<R, NW> lw;
+    quantize_minmax_wave_block<R, WPB, NW>(a, blockIdx.x, sm, lw);
+}
+
+// Several layer tensors in one launch, as quantize_tensors_wave_kernel maps them.
+template <int R, int WPB, int NW>
+__global__ __launch_bounds__(64 * NW) void quantize_minmax_tensors_wave_kernel(const BatchQuantizeArgs ba) {
+    __shared__ WaveShared<R, NW> sm;
+    __shared__ WaveLows<R, NW> lw;
+    uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= ba.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    QuantizeArgs a = ba.common;
+    a.grad = ba.t[lo].grad;
+    a.n = ba.t[lo].n;
+    a.packed = ba.t[lo].packed;
+    a.scales = ba.t[lo].scales;
+    a.scales_in = ba.t[lo].scales_in;
+    quantize_minmax_wave_block<R, WPB, NW>(a, blockIdx.x - ba.tile_start[lo], sm, lw);
 }
 
 // The measured choice of (R, WPB, NW) per bucket size (100 M elements, every width): buckets up to 1024
@@ -853,16 +878,38 @@ hipError_t launch_minmax_wave(const QuantizeArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_minmax_wave(const QuantizeArgs& a, hipStream_t stream) {
-    // With no random numbers to draw this encoder is light on the vector ALU, and 1024 elements per wave
-    // beat 2048 at every bucket size up to 1024 (63-65 us against 70 us at 1 bit, 100 M elements).
-    switch (a.bucket) {
-        case 2048: return launch_minmax_wave<4, 2, 4>(a, stream);
-        case 4096: return launch_minmax_wave<4, 4, 4>(a, stream);
-        case 8192: return launch_minmax_wave<4, 8, 8>(a, stream);
-        case 16384: return launch_minmax_wave<8, 8, 8>(a, stream);
-        default: return launch_minmax_wave<4, 1, 4>(a, stream);   // 32 .. 1024
+// With no random numbers to draw this encoder is light on the vector ALU, and 1024 elements per wave
+// beat 2048 at every bucket size up to 1024 (63-65 us against 70 us at 1 bit, 100 M elements).
+// Calls f(R, WPB, NW) with the shape as compile-time constants.
+template <class F>
+auto with_minmax_wave_shape(uint32_t bucket, F f) {
+    using std::integral_constant;
+    switch (bucket) {
+        case 2048: return f(integral_constant<int, 4>{}, integral_constant<int, 2>{}, integral_constant<int, 4>{});
+        case 4096: return f(integral_constant<int, 4>{}, integral_constant<int, 4>{}, integral_constant<int, 4>{});
+        case 8192: return f(integral_constant<int, 4>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
+        case 16384: return f(integral_constant<int, 8>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
+        default: return f(integral_constant<int, 4>{}, integral_constant<int, 1>{}, integral_constant<int, 4>{});   // 32 .. 1024
     }
+}
+
+hipError_t launch_quantize_minmax_wave(const QuantizeArgs& a, hipStream_t stream) {
+    return with_minmax_wave_shape(a.bucket, [&](auto r, auto wpb, auto nw) {
+        return launch_minmax_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value>(a, stream);
+    });
+}
+
+// elements per workgroup of the wave-local [min, max] encoder at this bucket size
+uint32_t quantize_minmax_wave_block_elems(uint32_t bucket) {
+    return with_minmax_wave_shape(bucket, [](auto r, auto, auto nw) { return (uint32_t)(decltype(nw)::value * 256 * decltype(r)::value); });
+}
+
+hipError_t launch_quantize_minmax_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream) {
+    return with_minmax_wave_shape(a.common.bucket, [&](auto r, auto wpb, auto nw) {
+        constexpr int R = decltype(r)::value, WPB = decltype(wpb)::value, NW = decltype(nw)::value;
+        hipLaunchKernelGGL((quantize_minmax_tensors_wave_kernel<R, WPB, NW>), dim3(blocks), dim3(64 * NW), 0, stream, a);
+        return hipGetLastError();
+    });
 }
 
 // The re-quantizing server step takes the wave-local kernel for power-of-two buckets of 128 elements

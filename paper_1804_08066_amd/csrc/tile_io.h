@@ -65,5 +65,30 @@ __device__ __forceinline__ void update_params(float* __restrict__ p, uint32_t ti
     }
 }
 
+// An uncompressed layer: acc <- sum over the W workers' fp32 gradients of the tile, in worker order.
+template <int R>
+__device__ __forceinline__ void accumulate_raw(const float* const* raw, uint32_t W, uint64_t tile_base, uint32_t tile_count,
+                                               bool full, float4 (&acc)[R]) {
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t w = 0; w < W; ++w) {
+        const float* __restrict__ g = raw[w] + tile_base;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const uint32_t el = 4u * (j * kThreads + tid);
+            if (full || el + 4u <= tile_count) {
+                const float4 t = load_f4_stream(g + el);
+                acc[j].x = acc[j].x + t.x;
+                acc[j].y = acc[j].y + t.y;
+                acc[j].z = acc[j].z + t.z;
+                acc[j].w = acc[j].w + t.w;
+            } else {
+                if (el + 0u < tile_count) acc[j].x = acc[j].x + g[el + 0];
+                if (el + 1u < tile_count) acc[j].y = acc[j].y + g[el + 1];
+                if (el + 2u < tile_count) acc[j].z = acc[j].z + g[el + 2];
+            }
+        }
+    }
+}
+
 }  // namespace tile_io
 }  // namespace mqg

@@ -26,6 +26,7 @@ EXPORTS = [
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
     "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
     "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch", "mqg_sum_squares_batch_static",
+    "mqg_quantize_minmax_tensors", "mqg_aggregate_update_minmax_tensors",
 ]
 
 
@@ -106,6 +107,10 @@ def lib():
     L.mqg_quantize_tensors_mode.restype = C.c_int
     L.mqg_aggregate_update_tensors.argtypes = [C.POINTER(UpdateItem), u32, u32, u32, u32, f32, vp]
     L.mqg_aggregate_update_tensors.restype = C.c_int
+    L.mqg_aggregate_update_minmax_tensors.argtypes = [C.POINTER(UpdateItem), u32, u32, u32, u32, f32, vp]
+    L.mqg_aggregate_update_minmax_tensors.restype = C.c_int
+    L.mqg_quantize_minmax_tensors.argtypes = [C.POINTER(QuantizeItem), u32, u32, u32, vp]
+    L.mqg_quantize_minmax_tensors.restype = C.c_int
     L.mqg_quantize_minmax.argtypes = [vp, u64, u32, u32, vp, vp, vp]
     L.mqg_quantize_minmax.restype = C.c_int
     L.mqg_aggregate_update_minmax.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, vp]
@@ -351,6 +356,16 @@ def mqg_aggregate_update_tensors(layers, W, bits, bucket, lr, stream=None):
 
     Each layer is a dict with "params" and either ("packed": [W tensors], "scales": [W tensors]) for a
     quantized layer or "raw": [W fp32 gradient tensors] for a layer sent uncompressed."""
+    items, keep = _update_items(layers, W, bits, bucket, 0)
+    st = lib().mqg_aggregate_update_tensors(items, len(layers), W, bits, bucket, lr, _stream_handle(stream))
+    del keep
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_update_tensors")
+
+
+def _update_items(layers, W, bits, bucket, ranges):
+    """The HOST table of a batched server step.  ranges: 0 = one scale per bucket, 1 = a (min, max) pair per
+    bucket, 2 = one (min, max) pair per layer.  Returns (items, objects to keep alive during the call)."""
     count = len(layers)
     items = (UpdateItem * max(count, 1))()
     keep = []
@@ -370,14 +385,53 @@ def mqg_aggregate_update_tensors(layers, W, bits, bucket, lr, stream=None):
             keep.append(ra)
             items[i] = UpdateItem(n, params.data_ptr(), None, None, ra)
         else:
-            Wn, pa, sa = _worker_arrays(layer["packed"], layer["scales"], n, bits, bucket)
-            if Wn != W:
+            packed, scales = layer["packed"], layer["scales"]
+            if len(packed) != W or len(scales) != W:
                 raise ValueError("packed/scales must have one entry per worker")
+            need = mqg_num_buckets(n, bucket) if ranges == 0 else (2 * mqg_num_buckets(n, bucket) if ranges == 1 else 2)
+            for pk, sc in zip(packed, scales):
+                _check(pk, torch.int32, "packed[w]")
+                _check(sc, torch.float32, "scales[w]")
+                if pk.numel() < mqg_packed_words(n, bits) or sc.numel() < need:
+                    raise ValueError("a worker's buffers are too small for n")
+            pa = (C.c_void_p * W)(*[t.data_ptr() for t in packed])
+            sa = (C.c_void_p * W)(*[t.data_ptr() for t in scales])
             keep.extend([pa, sa])
             items[i] = UpdateItem(n, params.data_ptr(), pa, sa, None)
-    st = lib().mqg_aggregate_update_tensors(items, count, W, bits, bucket, lr, _stream_handle(stream))
+    return items, keep
+
+
+def mqg_quantize_minmax_tensors(grads, bits, bucket, outputs=None, stream=None):
+    """mqg_quantize_minmax for a list of layer tensors in one launch; bucket = 0: one range per layer
+    (mqg_quantize_minmax_tensor for every layer).  Returns a list of (packed, ranges) per layer."""
+    count = len(grads)
+    nr = (lambda n: 2 * mqg_num_buckets(n, bucket)) if bucket else (lambda n: 2)
+    if outputs is None:
+        outputs = [(torch.empty(mqg_packed_words(g.numel(), bits), dtype=torch.int32, device=g.device),
+                    torch.empty(nr(g.numel()), dtype=torch.float32, device=g.device)) for g in grads]
+    items = (QuantizeItem * max(count, 1))()
+    for i, g in enumerate(grads):
+        _check(g, torch.float32, "grads[%d]" % i)
+        p, r = outputs[i]
+        _check(p, torch.int32, "packed_out")
+        _check(r, torch.float32, "ranges_out")
+        if p.numel() < mqg_packed_words(g.numel(), bits) or r.numel() < nr(g.numel()):
+            raise ValueError("output buffers too small")
+        items[i] = QuantizeItem(g.data_ptr(), g.numel(), 0, p.data_ptr(), r.data_ptr(), None)
+    st = lib().mqg_quantize_minmax_tensors(items, count, bits, bucket, _stream_handle(stream))
     if st != MQG_OK:
-        raise MqgError(st, "mqg_aggregate_update_tensors")
+        raise MqgError(st, "mqg_quantize_minmax_tensors")
+    return outputs
+
+
+def mqg_aggregate_update_minmax_tensors(layers, W, bits, bucket, lr, stream=None):
+    """mqg_aggregate_update_minmax for a list of layers in one launch (bucket = 0: one (min, max) pair per worker
+    and layer).  Layers as in mqg_aggregate_update_tensors, "scales" holding the range arrays."""
+    items, keep = _update_items(layers, W, bits, bucket, 1 if bucket else 2)
+    st = lib().mqg_aggregate_update_minmax_tensors(items, len(layers), W, bits, bucket, lr, _stream_handle(stream))
+    del keep
+    if st != MQG_OK:
+        raise MqgError(st, "mqg_aggregate_update_minmax_tensors")
 
 
 def mqg_quantize_minmax(grad, bits, bucket, packed_out=None, ranges_out=None, stream=None):

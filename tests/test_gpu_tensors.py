@@ -123,3 +123,74 @@ def test_batch_limits_are_reported():
     with pytest.raises(mqgrad.MqgError):
         mqgrad.mqg_aggregate_update_tensors(layers, W, 4, 32, 0.1)
     torch.cuda.synchronize()
+
+
+# ---- the [min, max] encoding (Section 3.2 footnote) with several layers per launch -------------------
+
+MINMAX_SIZES = [n for _, n in workloads.SMALL_CNN_SHAPES] + [0, 1, 40000 + 3, 3 * 16384 + 4096 + 37]
+
+
+@pytest.mark.parametrize("bucket", [96, 512, 2048, 8192, 16384, 0])
+def test_batched_minmax_encode_equals_the_oracle_per_layer(bucket):
+    # bucket 0: one range per layer, as the paper encodes (the oracle with one bucket that covers the layer)
+    grads = [workloads.normal_with_outliers(n, 0.01, 1e-3, 25.0, 90 + i, DEV) + 1e-3 * i if n else torch.empty(0, device=DEV)
+             for i, n in enumerate(MINMAX_SIZES)]
+    for bits in (1, 3, 4, 8):
+        outs = mqgrad.mqg_quantize_minmax_tensors(grads, bits, bucket)
+        torch.cuda.synchronize()
+        for i, g in enumerate(grads):
+            n = MINMAX_SIZES[i]
+            if n == 0:
+                continue
+            pk_o, rg_o = ref.quantize_minmax(g.cpu().numpy(), bits, bucket if bucket else n)
+            assert outs[i][1].cpu().numpy().tobytes() == rg_o.tobytes(), "ranges of layer %d b=%d" % (i, bits)
+            assert np.array_equal(to_u32(outs[i][0]), pk_o), "layer %d b=%d" % (i, bits)
+
+
+@pytest.mark.parametrize("bucket", [160, 1024, 0])
+@pytest.mark.parametrize("bits", [2, 5, 8])
+def test_batched_minmax_server_step_with_raw_small_layers(bits, bucket):
+    # the paper's selective quantization with the footnote's encoder: large layers encoded, small ones raw;
+    # one encode call per worker and one update launch
+    W, lr = 3, 0.1
+    shapes = workloads.SMALL_CNN_SHAPES
+    encoded = [n >= 4096 for _, n in shapes]
+    e_idx = [i for i, e in enumerate(encoded) if e]
+    grads = [[workloads.laplace(n, 2e-3, 1000 * w + i, DEV) + 5e-4 * w for i, (_, n) in enumerate(shapes)] for w in range(W)]
+    params = [workloads.uniform(n, -0.05, 0.05, 40 + i, DEV) for i, (_, n) in enumerate(shapes)]
+    p0 = [p.cpu().numpy().copy() for p in params]
+    outs = [mqgrad.mqg_quantize_minmax_tensors([grads[w][i] for i in e_idx], bits, bucket) for w in range(W)]
+    layers = []
+    for i in range(len(shapes)):
+        if encoded[i]:
+            k = e_idx.index(i)
+            layers.append({"params": params[i], "packed": [outs[w][k][0] for w in range(W)],
+                           "scales": [outs[w][k][1] for w in range(W)]})
+        else:
+            layers.append({"params": params[i], "raw": [grads[w][i] for w in range(W)]})
+    mqgrad.mqg_aggregate_update_minmax_tensors(layers, W, bits, bucket, lr)
+    torch.cuda.synchronize()
+    for i, (_, n) in enumerate(shapes):
+        if encoded[i]:
+            B = bucket if bucket else n
+            want = [ref.quantize_minmax(grads[w][i].cpu().numpy(), bits, B) for w in range(W)]
+            p1 = ref.aggregate_update_minmax([x[0] for x in want], [x[1] for x in want], n, bits, B, lr, p0[i])
+        else:
+            p1 = ref.average_update_raw([grads[w][i].cpu().numpy() for w in range(W)], lr, p0[i])
+        assert ulp_distance(params[i].cpu().numpy(), p1).max() == 0, "layer %d" % i
+
+
+def test_batched_minmax_calls_report_bad_arguments():
+    g = [workloads.normal(64, 0.01, i, DEV) for i in range(33)]
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_quantize_minmax_tensors(g, 4, 32)            # more than MQG_MAX_TENSORS layers
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_quantize_minmax_tensors(g[:2], 9, 32)        # bits outside 1..8
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_quantize_minmax_tensors(g[:2], 4, 48)        # bucket not a multiple of 32
+    outs = mqgrad.mqg_quantize_minmax_tensors(g[:1], 4, 0)
+    layers = [{"params": torch.zeros(64, device=DEV), "packed": [outs[0][0]] * 8, "scales": [outs[0][1]] * 8}] * 17
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_aggregate_update_minmax_tensors(layers, 8, 4, 0, 0.1)   # 272 pointers
+    mqgrad.mqg_aggregate_update_minmax_tensors(layers[:16], 8, 4, 0, 0.1)
+    torch.cuda.synchronize()
