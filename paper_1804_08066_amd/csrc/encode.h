@@ -28,6 +28,11 @@ typedef v4u v4u_a4 __attribute__((aligned(4)));
 // once and the line stays valid in L2.  HIP has no builtin for a scoped 128-bit store.  `base` must be
 // wave-uniform (it travels in scalar registers), `byte_off` is the lane's offset from it.  The
 // instruction reads its operands when it issues, so the registers are free right after it.
+// (One dword with the same scope: for the odd words beside such stores -- ordinary stores into cache
+// lines that also receive agent-scope stores are very slow.)
+__device__ __forceinline__ void store_u32_agent(const void* base, uint32_t byte_off, uint32_t w) {
+    asm volatile("global_store_dword %0, %1, %2 sc1" ::"v"(byte_off), "v"(w), "s"(base) : "memory");
+}
 __device__ __forceinline__ void store_v4u_agent(const void* base, uint32_t byte_off, v4u w) {
     asm volatile("global_store_dwordx4 %0, %1, %2 sc1" ::"v"(byte_off), "v"(w), "s"(base) : "memory");
 }

@@ -92,6 +92,9 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_requantize(const RequantArgs& a, hipStream_t stream);
 bool quantize_wave_supported(const QuantizeArgs& a);          // quantize_wave.hip
 hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream);
+bool quantize_cells_supported(const QuantizeArgs& a);         // quantize_wave.hip: other multiples of 32 up to 4064
+hipError_t launch_quantize_cells(const QuantizeArgs& a, hipStream_t stream);
+uint32_t quantize_cells_tile_elems(uint32_t bucket);
 bool quantize_minmax_wave_supported(const QuantizeArgs& a);   // quantize_wave.hip
 hipError_t launch_quantize_minmax_wave(const QuantizeArgs& a, hipStream_t stream);
 bool requantize_wave_supported(const RequantArgs& a);         // quantize_wave.hip

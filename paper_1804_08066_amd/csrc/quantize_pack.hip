@@ -437,6 +437,7 @@ hipError_t launch_requant_r(const RequantArgs& ra, hipStream_t stream) {
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
     if (quantize_wave_supported(a)) return launch_quantize_wave(a, stream);
+    if (quantize_cells_supported(a)) return launch_quantize_cells(a, stream);
     if (a.bucket <= 4096u) return launch_r<4>(a, stream);
     if (a.bucket <= 8192u) return launch_r<8>(a, stream);
     return launch_r<16>(a, stream);

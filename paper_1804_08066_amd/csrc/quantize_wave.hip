@@ -106,7 +106,7 @@ __device__ __forceinline__ void segment_sum_dispatch(double (&q)[R], uint32_t rp
 // (except wave_max, which is what the WPB > 1 barrier is for).
 template <int R, int NW>
 struct WaveShared {
-    alignas(16) uint32_t words[NW][64 * R + 4];   // packed output of a chunk: 8*R*bits <= 64*R words
+    alignas(16) uint32_t words[NW][64 * R + 8];   // packed output of a chunk: 8*R*bits <= 64*R words (+ 1 for a straddling code, + 3 of shift)
     float smax[NW][8 * R];            // per-bucket max |g| of the chunk (<= CH/32 buckets)
     float ainv[NW][8 * R];            // per-bucket (L/2)/s
     float wave_max[NW];               // chunk maximum, for buckets that span several waves
@@ -235,6 +235,66 @@ __device__ __forceinline__ void store_chunk_words(uint32_t* __restrict__ out, ui
     }
 }
 
+// a2..a4 for the chunk's rows: grid position, stochastic rounding, packing into the wave's LDS area.
+// sm.ainv[wave][slot[j]] holds the factor of row j's quad.  TAIL: which parts of the chunk can lie past
+// `count` -- none, whole quads only (count is a multiple of 4), or single elements.
+constexpr int kTailNone = 0, kTailQuads = 1, kTailElements = 2;
+template <int R, int NW, int TAIL>
+__device__ __forceinline__ void round_and_pack_rows(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
+                                                    uint32_t wave, const uint32_t (&slot)[R], const float4 (&x)[R],
+                                                    WaveShared<R, NW>& sm, const FixedGrid& fg, const Draws<R>* drawn,
+                                                    const uint32_t word_shift = 0u) {
+    // word_shift (0..3): the chunk's word i is kept at sm.words[wave][word_shift + i]
+    const uint32_t b = a.bits;
+    const uint32_t odd = lane & 1u;
+    const uint32_t cell_bit = 4u * b * (lane & 7u);            // this lane's bit offset in its 32-element cell
+    const uint32_t sh = cell_bit & 31u;
+    const uint32_t word_in_cell = cell_bit >> 5;
+    const bool straddle = sh + 4u * b > 32u;
+
+#pragma unroll
+    for (int jp = 0; jp < R; jp += 2) {
+        // The lane pair's call for rows jp and jp + 1 (made here unless it was made earlier); each lane
+        // then takes the half it needs from its partner.  The swaps run with every lane active (a lane
+        // swap under a divergent branch would read switched-off partners); the selects that follow
+        // keep the half each lane needs.
+        uint32_t o[4];
+        if (drawn != nullptr) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = drawn->o[jp / 2][i];
+        } else {
+            draw_pair(a, cb, lane, jp, o);
+        }
+        const uint32_t p0 = swap_adjacent(o[0]), p1 = swap_adjacent(o[1]);
+        const uint32_t p2 = swap_adjacent(o[2]), p3 = swap_adjacent(o[3]);
+        const uint32_t rw[2][2] = {{odd ? p2 : o[0], odd ? p3 : o[1]},    // row jp: the even lane's call
+                                   {odd ? o[2] : p0, odd ? o[3] : p1}};   // row jp+1: the odd lane's call
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int j = jp + t;
+            const uint32_t ql = j * 64u + lane;
+            const uint32_t el = 4u * ql;
+            const float ainv = sm.ainv[wave][slot[j]];
+            uint32_t t0 = round_code_hi(x[j].x, ainv, fg, rw[t][0] & 0xFFFFu);
+            uint32_t t1 = round_code_hi(x[j].y, ainv, fg, rw[t][0] >> 16);
+            uint32_t t2 = round_code_hi(x[j].z, ainv, fg, rw[t][1] & 0xFFFFu);
+            uint32_t t3 = round_code_hi(x[j].w, ainv, fg, rw[t][1] >> 16);
+            if (TAIL == kTailElements) {   // elements past the end contribute zero bits
+                if (el + 0u >= count) t0 = 0u;
+                if (el + 1u >= count) t1 = 0u;
+                if (el + 2u >= count) t2 = 0u;
+                if (el + 3u >= count) t3 = 0u;
+            }
+            const uint32_t v = pack_quad_hi(t0, t1, t2, t3, b, 2u * b, 3u * b);
+            if (TAIL == kTailNone || el < count) {
+                const uint32_t w0 = (ql >> 3) * b + word_in_cell + word_shift;
+                atomicOr(&sm.words[wave][w0], v << sh);
+                if (straddle) atomicOr(&sm.words[wave][w0 + 1u], v >> (32u - sh));
+            }
+        }
+    }
+}
+
 // ---- phase 2: scales, grid position, stochastic rounding, packing, store -------------------------
 template <int R, int WPB, int NW, bool FULL>
 __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_t cb, uint32_t count, uint32_t lane,
@@ -285,53 +345,7 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
     }
     wave_lds_fence();   // every lane reads its buckets' factors; the packing area was cleared by other lanes
 
-    const uint32_t odd = lane & 1u;
-    const uint32_t cell_bit = 4u * b * (lane & 7u);            // this lane's bit offset in its 32-element cell
-    const uint32_t sh = cell_bit & 31u;
-    const uint32_t word_in_cell = cell_bit >> 5;
-    const bool straddle = sh + 4u * b > 32u;
-
-#pragma unroll
-    for (int jp = 0; jp < R; jp += 2) {
-        // The lane pair's call for rows jp and jp + 1 (made here unless it was made earlier); each lane
-        // then takes the half it needs from its partner.  The swaps run with every lane active (a lane
-        // swap under a divergent branch would read switched-off partners); the selects that follow
-        // keep the half each lane needs.
-        uint32_t o[4];
-        if (drawn != nullptr) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = drawn->o[jp / 2][i];
-        } else {
-            draw_pair(a, cb, lane, jp, o);
-        }
-        const uint32_t p0 = swap_adjacent(o[0]), p1 = swap_adjacent(o[1]);
-        const uint32_t p2 = swap_adjacent(o[2]), p3 = swap_adjacent(o[3]);
-        const uint32_t rw[2][2] = {{odd ? p2 : o[0], odd ? p3 : o[1]},    // row jp: the even lane's call
-                                   {odd ? o[2] : p0, odd ? o[3] : p1}};   // row jp+1: the odd lane's call
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int j = jp + t;
-            const uint32_t ql = j * 64u + lane;
-            const uint32_t el = 4u * ql;
-            const float ainv = sm.ainv[wave][slot[j]];
-            uint32_t t0 = round_code_hi(x[j].x, ainv, fg, rw[t][0] & 0xFFFFu);
-            uint32_t t1 = round_code_hi(x[j].y, ainv, fg, rw[t][0] >> 16);
-            uint32_t t2 = round_code_hi(x[j].z, ainv, fg, rw[t][1] & 0xFFFFu);
-            uint32_t t3 = round_code_hi(x[j].w, ainv, fg, rw[t][1] >> 16);
-            if (!FULL) {   // elements past the end contribute zero bits
-                if (el + 0u >= count) t0 = 0u;
-                if (el + 1u >= count) t1 = 0u;
-                if (el + 2u >= count) t2 = 0u;
-                if (el + 3u >= count) t3 = 0u;
-            }
-            const uint32_t v = pack_quad_hi(t0, t1, t2, t3, b, 2u * b, 3u * b);
-            if (FULL || el < count) {
-                const uint32_t w0 = (ql >> 3) * b + word_in_cell;
-                atomicOr(&sm.words[wave][w0], v << sh);
-                if (straddle) atomicOr(&sm.words[wave][w0 + 1u], v >> (32u - sh));
-            }
-        }
-    }
+    round_and_pack_rows<R, NW, FULL ? kTailNone : kTailElements>(a, cb, count, lane, wave, slot, x, sm, fg, drawn);
 
     // store the chunk's words
     wave_lds_fence();   // a word holds bits placed by several lanes
@@ -422,6 +436,157 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
     a.scales = ba.t[lo].scales;
     a.scales_in = ba.t[lo].scales_in;
     quantize_wave_block<R, WPB, NW, HOIST>(a, blockIdx.x - ba.tile_start[lo], sm);
+}
+
+// ---- buckets of any whole number of cells ------------------------------------------------------------
+// Bucket sizes that are multiples of 32 but not powers of two (96 .. 4064 elements).  A workgroup owns a
+// tile of whole buckets, as many as fit into NW * 2048 elements; the tile's 32-element cells are dealt out
+// to the waves in equal runs (a run is at most 64 cells, one per 8 lanes and row), so a bucket may lie in
+// two or more waves: the cells' maxima meet in one LDS slot per bucket (integer max on the bit patterns),
+// between the workgroup's two barriers.  The first barrier falls while the loads are in flight.
+// Everything after the second -- the bucket factors a wave needs, rounding, packing, stores -- is
+// wave-local as in the kernel above.
+struct CellGeometry {
+    uint32_t bucket_cells;     // cells per bucket: bucket / 32, 3 .. 127
+    uint32_t tile_buckets;     // whole buckets per tile
+    uint32_t tile_cells;       // bucket_cells * tile_buckets <= NW * 64
+    uint32_t cells_per_wave;   // ceil(tile_cells / NW) <= 64
+    uint32_t magic;            // ceil(65536 / bucket_cells): (cell * magic) >> 16 = cell / bucket_cells for cell < 512
+};
+
+template <int NW>
+struct CellShared {
+    uint32_t bmax[NW * 64 / 3 + 1];   // per bucket of the tile: bit pattern of max |g|
+};
+
+template <int NW, bool HOIST>
+__device__ __forceinline__ void quantize_cells_block(const QuantizeArgs& a, const CellGeometry& g, const uint64_t tile,
+                                                     WaveShared<8, NW>& sm, CellShared<NW>& cs) {
+    constexpr int R = 8;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    const uint64_t tile_base = tile * ((uint64_t)g.tile_cells * 32u);          // first element of the tile (< n)
+    const uint32_t cell0 = wave * g.cells_per_wave;                             // the wave's run of cells
+    const uint32_t ncell = cell0 >= g.tile_cells ? 0u : (g.tile_cells - cell0 < g.cells_per_wave ? g.tile_cells - cell0 : g.cells_per_wave);
+    const uint64_t cb = tile_base + 32u * cell0;                                // first element of the run
+    const uint32_t count = (ncell == 0u || cb >= a.n) ? 0u : (a.n - cb < 32u * ncell ? (uint32_t)(a.n - cb) : 32u * ncell);
+    const bool whole_quads = (count & 3u) == 0u;   // always, except for the run that holds the tensor's ragged end
+
+    float4 x[R];
+    if (whole_quads) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const uint32_t el = 4u * (j * 64u + lane);
+            if (el < count) {
+                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f_a4*>(a.grad + cb + el));
+                x[j] = make_float4(t.x, t.y, t.z, t.w);
+            } else {
+                x[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+        }
+    } else {
+        load_chunk<R, false>(a.grad + cb, count, lane, x);
+    }
+    // while the loads are in flight
+    clear_words<R, NW>(lane, wave, sm);
+    if (lane == 0u) *reinterpret_cast<v4u*>(&sm.words[wave][64u * R]) = v4u{0u, 0u, 0u, 0u};   // the run's words may sit up to three further on
+    for (uint32_t i = tid; i < g.tile_buckets; i += 64u * NW) cs.bmax[i] = 0u;
+    Draws<R> draws;
+    if (HOIST) {
+#pragma unroll
+        for (int jp = 0; jp < R; jp += 2) draw_pair(a, cb, lane, jp, draws.o[jp / 2]);
+    }
+    // tile-local bucket of row j's cell; rows past the run point at buckets that are never used
+    uint32_t kb[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) kb[j] = ((cell0 + 8u * j + (lane >> 3)) * g.magic) >> 16;
+    __syncthreads();
+
+    if (a.scales_in == nullptr) {
+        uint32_t m[R];   // bit patterns of non-negative floats: integer order = value order
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            m[j] = __builtin_bit_cast(uint32_t, fmaxf(fmaxf(fabsf(x[j].x), fabsf(x[j].y)), fmaxf(fabsf(x[j].z), fabsf(x[j].w))));
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) m[j] = max(m[j], dpp_u32<kDppQuadSwap1>(m[j]));
+#pragma unroll
+        for (int j = 0; j < R; ++j) m[j] = max(m[j], dpp_u32<kDppQuadSwap2>(m[j]));
+#pragma unroll
+        for (int j = 0; j < R; ++j) m[j] = max(m[j], dpp_u32<kDppRowHalfMirror>(m[j]));
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if ((lane & 7u) == 0u && 8u * j + (lane >> 3) < ncell) atomicMax(&cs.bmax[kb[j]], m[j]);
+        }
+    }
+    __syncthreads();
+    if (count == 0u) return;
+
+    // the buckets this run touches: kbw0 .. kbw0 + nbw - 1 (nbw <= 64 / 3 + 2); one lane each
+    const uint32_t kbw0 = (cell0 * g.magic) >> 16;
+    const uint32_t nbw = (((cell0 + ncell - 1u) * g.magic) >> 16) - kbw0 + 1u;
+    const uint32_t b = a.bits;
+    const float halfL = 0.5f * (float)((1u << b) - 1u);
+    if (lane < nbw) {
+        const uint32_t k = kbw0 + lane;
+        const uint64_t kg = tile * g.tile_buckets + k;                                    // global bucket index
+        const bool exists = tile_base + (uint64_t)k * a.bucket < a.n;                     // the bucket starts inside the tensor
+        float s = 0.0f;
+        if (exists) {
+            if (a.scales_in != nullptr) {
+                s = a.scales_in[kg];
+            } else {
+                s = __builtin_bit_cast(float, cs.bmax[k]);
+                if (!(s >= 0x1p-96f)) s = 0.0f;
+            }
+            if (k * g.bucket_cells >= cell0) a.scales[kg] = s;   // the run that holds the bucket's first cell stores it
+        }
+        sm.ainv[wave][lane] = (s > 0.0f) ? (halfL / s) * 65536.0f : 0.0f;   // IEEE-correct fp32 division, times 2^16 (exact)
+    }
+    uint32_t slot[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) slot[j] = kb[j] - kbw0;   // < 64 / 3 + 2 + 64 / 3: inside sm.ainv[wave]
+    wave_lds_fence();
+
+    const FixedGrid fg = fixed_grid(b);
+    const Draws<R>* drawn = HOIST ? &draws : nullptr;
+    // The run's words start at any word of the stream.  They are kept in LDS shifted by the stream
+    // position modulo four, so that 16-byte groups of the stream are 16-byte groups in LDS: up to three
+    // single words, then 128-bit stores at aligned addresses (unaligned ones cost 10 % of the kernel's
+    // time), then up to three single words.  Every store carries the same agent scope: ordinary stores
+    // into cache lines that also receive agent-scope stores slowed the kernel from 72 to 128 us.
+    const uint64_t word0 = (cb >> 5) * b;
+    const uint32_t shift4 = (uint32_t)word0 & 3u;
+    if (whole_quads) {
+        round_and_pack_rows<R, NW, kTailQuads>(a, cb, count, lane, wave, slot, x, sm, fg, drawn, shift4);
+    } else {
+        round_and_pack_rows<R, NW, kTailElements>(a, cb, count, lane, wave, slot, x, sm, fg, drawn, shift4);
+    }
+    wave_lds_fence();   // a word holds bits placed by several lanes
+
+    const uint32_t nwords = (count * b + 31u) >> 5;
+    const uint32_t* __restrict__ lw = sm.words[wave];                 // stream word word0 + i is lw[shift4 + i]
+    uint32_t* __restrict__ out = a.packed + (word0 - shift4);         // 16-byte aligned when a.packed is; out[shift4 + i] is stream word word0 + i
+    const uint32_t first = shift4, last = shift4 + nwords;            // the run in units of `out` / `lw` words
+    const uint32_t body0 = (first + 3u) & ~3u;                        // first aligned group
+    const uint32_t body1 = last & ~3u;                                // end of the last whole group
+    if (body0 < body1) {
+        if (first + lane < body0) store_u32_agent(out, 4u * (first + lane), lw[first + lane]);
+        for (uint32_t i = (body0 >> 2) + lane; i < (body1 >> 2); i += 64u) {
+            store_v4u_agent(out, 16u * i, *reinterpret_cast<const v4u*>(&lw[4u * i]));
+        }
+        if (body1 + lane < last) store_u32_agent(out, 4u * (body1 + lane), lw[body1 + lane]);
+    } else if (first + lane < last) {   // fewer than seven words and no whole group
+        store_u32_agent(out, 4u * (first + lane), lw[first + lane]);
+    }
+}
+
+template <int NW, int OCC, bool HOIST>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_cells_kernel(const QuantizeArgs a, const CellGeometry g) {
+    __shared__ WaveShared<8, NW> sm;
+    __shared__ CellShared<NW> cs;
+    quantize_cells_block<NW, HOIST>(a, g, blockIdx.x, sm, cs);
 }
 
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
@@ -862,6 +1027,63 @@ hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
         return launch_wave<decltype(r)::value, decltype(wpb)::value, decltype(nw)::value, decltype(occ)::value,
                            decltype(hoist)::value>(a, stream);
     });
+}
+
+// Buckets of a whole number of cells that are not powers of two, up to 4064 elements, with the max-abs
+// range or given scales.
+bool quantize_cells_supported(const QuantizeArgs& a) {
+    return a.bucket_shift < 0 && a.bucket <= 4096u && (a.scales_in != nullptr || a.scale_mode == MQG_SCALE_MAXABS);
+}
+
+// Four waves per workgroup unless a larger workgroup's NW * 64 cells are filled at least a tenth better
+// by whole buckets: measured at 100 M elements, buckets of 2752 elements (67 % of four waves, 84 % of
+// eight) gain 7 us per launch from eight waves, buckets of 1504 (92 % of four, 98 % of six) lose 4 us
+// with six.
+static CellGeometry cell_geometry(uint32_t bucket, uint32_t* nw_out) {
+    const uint32_t bc = bucket >> 5;
+    uint32_t nw = 4u;
+    for (uint32_t w = 5u; w <= 8u; ++w) {
+        // used fractions (w * 64 / bc) * bc / (w * 64), compared by cross-multiplication
+        if (((w * 64u) / bc) * bc * nw * 10u > ((nw * 64u) / bc) * bc * w * 11u) nw = w;
+    }
+    CellGeometry g;
+    g.bucket_cells = bc;
+    g.tile_buckets = (nw * 64u) / bc;
+    g.tile_cells = g.tile_buckets * bc;
+    g.cells_per_wave = (g.tile_cells + nw - 1u) / nw;
+    g.magic = (65536u + bc - 1u) / bc;
+    *nw_out = nw;
+    return g;
+}
+
+uint32_t quantize_cells_tile_elems(uint32_t bucket) {
+    uint32_t nw;
+    return cell_geometry(bucket, &nw).tile_cells * 32u;
+}
+
+template <int NW>
+static hipError_t launch_cells_nw(const QuantizeArgs& a, const CellGeometry& g, uint32_t tiles, hipStream_t stream) {
+    // Five waves per SIMD instead of six pay where a wave writes much or places many codes across word
+    // boundaries (measured at 100 M elements: buckets 96 and 480 from 3 bits on by 2-4 us, 1504 at 7 and 8 bits)
+    const bool cap = a.bits >= (a.bucket < 1024u ? 3u : 7u);
+    if (cap) hipLaunchKernelGGL((quantize_cells_kernel<NW, 5, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
+    else hipLaunchKernelGGL((quantize_cells_kernel<NW, 8, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_cells(const QuantizeArgs& a, hipStream_t stream) {
+    uint32_t nw;
+    const CellGeometry g = cell_geometry(a.bucket, &nw);
+    const uint64_t tile_elems = (uint64_t)g.tile_cells * 32u;
+    const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
+    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    switch (nw) {
+        case 4: return launch_cells_nw<4>(a, g, (uint32_t)tiles, stream);
+        case 5: return launch_cells_nw<5>(a, g, (uint32_t)tiles, stream);
+        case 6: return launch_cells_nw<6>(a, g, (uint32_t)tiles, stream);
+        case 7: return launch_cells_nw<7>(a, g, (uint32_t)tiles, stream);
+        default: return launch_cells_nw<8>(a, g, (uint32_t)tiles, stream);
+    }
 }
 
 // The [min, max] encoder takes the same shapes (a given whole-tensor range needs no bucket at all and

@@ -78,6 +78,27 @@ def test_multi_tile_with_ragged_tail_and_straddling_widths():
             assert_quantize_parity(g, bits, bucket, seed=11, iteration=9, worker=5, label="B=%d b=%d" % (bucket, bits))
 
 
+@pytest.mark.parametrize("bucket", [96, 160, 480, 1504, 2752, 4064])
+def test_buckets_of_any_whole_number_of_cells(bucket):
+    # multiples of 32 that are not powers of two: several workgroup tiles, buckets that lie in two waves,
+    # four and eight waves per workgroup (2752), a ragged tail, a 4-byte aligned view, given scales
+    n = 3 * 16384 + 4096 + 777
+    base = workloads.normal_with_outliers(n + 3, 1e-3, 1e-3, 100.0, 6, DEV)
+    for bits in (1, 3, 4, 7, 8):
+        assert_quantize_parity(base[:n], bits, bucket, seed=13, iteration=2, worker=4, elem_base=1 << 33,
+                               label="B=%d b=%d" % (bucket, bits))
+    for off, m in ((1, n), (3, bucket * 5), (2, bucket * 5 + 31), (0, 5)):
+        assert_quantize_parity(base[off:off + m], 5, bucket, seed=3, label="B=%d off=%d n=%d" % (bucket, off, m))
+    g = base[:n]
+    nb = ref.num_buckets(n, bucket)
+    inj = (np.abs(np.random.default_rng(1).normal(2e-3, 1e-3, nb)) + 1e-4).astype(np.float32)
+    inj[1] = 0.0
+    pk_g, sc_g = gpu_quantize(g, 6, bucket, 5, 1, 2, 0, scales_in=torch.from_numpy(inj).to(DEV))
+    pk_o, sc_o = ref.quantize(g.cpu().numpy(), 6, bucket, 5, 1, 2, 0, scales_in=inj)
+    assert sc_g.tobytes() == inj.tobytes() == sc_o.tobytes()
+    assert np.array_equal(pk_g, pk_o)
+
+
 def test_unaligned_views():
     base = workloads.normal(20000, 0.01, 3, DEV)
     pbase = workloads.uniform(20000, -0.05, 0.05, 4, DEV)
