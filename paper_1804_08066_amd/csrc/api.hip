@@ -319,7 +319,7 @@ mqg_status mqg_quantize_tensors_mode(const mqg_quantize_item* items, uint32_t co
     a.common.packed = nullptr;
     a.common.scales = nullptr;
     a.count = count;
-    a.tile_elems = mqg::quantize_batch_tile(bucket, bits, a.common.bucket_shift);
+    a.tile_elems = mqg::quantize_batch_tile(a);
     uint64_t tiles = 0;
     for (uint32_t i = 0; i < mqg::kMaxBatchTensors; ++i) {
         a.tile_start[i] = (uint32_t)tiles;

@@ -83,7 +83,7 @@ struct BatchQuantizeArgs {
 
 uint32_t aggregate_batch_tile();
 hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles, hipStream_t stream);
-uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift);   // elements per workgroup
+uint32_t quantize_batch_tile(const BatchQuantizeArgs& a);   // elements per workgroup of the kernel the batch will run (reads a.common only)
 uint32_t quantize_wave_block_elems(uint32_t bucket, uint32_t bits);                             // quantize_wave.hip
 hipError_t launch_quantize_tensors_wave(const BatchQuantizeArgs& a, uint32_t blocks, hipStream_t stream);
 hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream);
@@ -95,6 +95,8 @@ hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream);
 bool quantize_cells_supported(const QuantizeArgs& a);         // quantize_wave.hip: other multiples of 32 up to 4064
 hipError_t launch_quantize_cells(const QuantizeArgs& a, hipStream_t stream);
 uint32_t quantize_cells_tile_elems(uint32_t bucket);
+bool quantize_tensors_cells_supported(const BatchQuantizeArgs& a);
+hipError_t launch_quantize_tensors_cells(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream);
 bool quantize_minmax_wave_supported(const QuantizeArgs& a);   // quantize_wave.hip
 hipError_t launch_quantize_minmax_wave(const QuantizeArgs& a, hipStream_t stream);
 bool requantize_wave_supported(const RequantArgs& a);         // quantize_wave.hip

@@ -446,8 +446,10 @@ hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
 // Power-of-two buckets take the wave-local kernel, like single calls.
 static bool batch_takes_wave_kernel(int bucket_shift) { return bucket_shift >= 5; }
 
-uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift) {
-    if (batch_takes_wave_kernel(bucket_shift)) return quantize_wave_block_elems(bucket, bits);
+uint32_t quantize_batch_tile(const BatchQuantizeArgs& a) {
+    const uint32_t bucket = a.common.bucket;
+    if (batch_takes_wave_kernel(a.common.bucket_shift)) return quantize_wave_block_elems(bucket, a.common.bits);
+    if (quantize_tensors_cells_supported(a)) return quantize_cells_tile_elems(bucket);
     const uint32_t cap = bucket <= 4096u ? Tile<4>::kCap : (bucket <= 8192u ? Tile<8>::kCap : Tile<16>::kCap);
     return (cap / bucket) * bucket;
 }
@@ -455,6 +457,7 @@ uint32_t quantize_batch_tile(uint32_t bucket, uint32_t bits, int bucket_shift) {
 hipError_t launch_quantize_tensors(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream) {
     if (tiles == 0) return hipSuccess;
     if (batch_takes_wave_kernel(a.common.bucket_shift)) return launch_quantize_tensors_wave(a, tiles, stream);
+    if (quantize_tensors_cells_supported(a)) return launch_quantize_tensors_cells(a, tiles, stream);
     if (a.common.bucket <= 4096u) return launch_tensors_r<4>(a, tiles, stream);
     if (a.common.bucket <= 8192u) return launch_tensors_r<8>(a, tiles, stream);
     return launch_tensors_r<16>(a, tiles, stream);

@@ -589,6 +589,26 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC)
     quantize_cells_block<NW, HOIST>(a, g, blockIdx.x, sm, cs);
 }
 
+// Several layer tensors of one worker in one launch, as quantize_tensors_wave_kernel maps them.
+template <int NW, int OCC, bool HOIST>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, OCC))) void quantize_tensors_cells_kernel(const BatchQuantizeArgs ba, const CellGeometry g) {
+    __shared__ WaveShared<8, NW> sm;
+    __shared__ CellShared<NW> cs;
+    uint32_t lo = 0, hi = ba.count;          // tile_start[lo] <= blockIdx.x < tile_start[hi]
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (blockIdx.x >= ba.tile_start[mid]) lo = mid; else hi = mid;
+    }
+    QuantizeArgs a = ba.common;
+    a.grad = ba.t[lo].grad;
+    a.n = ba.t[lo].n;
+    a.elem_base = ba.t[lo].elem_base;
+    a.packed = ba.t[lo].packed;
+    a.scales = ba.t[lo].scales;
+    a.scales_in = ba.t[lo].scales_in;
+    quantize_cells_block<NW, HOIST>(a, g, blockIdx.x - ba.tile_start[lo], sm, cs);
+}
+
 // ---- the server's re-quantizing step on the same decomposition -------------------------------------
 // ReceiveQGThenSendQG of Algorithm 1: the chunk's values are not loaded but decoded -- the sum over the
 // W workers' de-quantized gradients, the ordered fma chain of the fused update -- and then quantized
@@ -1034,15 +1054,20 @@ hipError_t launch_quantize_wave(const QuantizeArgs& a, hipStream_t stream) {
 bool quantize_cells_supported(const QuantizeArgs& a) {
     return a.bucket_shift < 0 && a.bucket <= 4096u && (a.scales_in != nullptr || a.scale_mode == MQG_SCALE_MAXABS);
 }
+// the batched call: layers without given scales compute them, so the range must be max-abs
+bool quantize_tensors_cells_supported(const BatchQuantizeArgs& a) {
+    return a.common.bucket_shift < 0 && a.common.bucket <= 4096u && a.common.scale_mode == MQG_SCALE_MAXABS;
+}
 
 // Four waves per workgroup unless a larger workgroup's NW * 64 cells are filled at least a tenth better
 // by whole buckets: measured at 100 M elements, buckets of 2752 elements (67 % of four waves, 84 % of
-// eight) gain 7 us per launch from eight waves, buckets of 1504 (92 % of four, 98 % of six) lose 4 us
-// with six.
+// eight) gain 7 us per launch from the larger workgroup, buckets of 1504 (92 % of four, 98 % of six) lose
+// 4 us with six.  Up to seven waves: for no admissible bucket do eight fill a tenth better than seven
+// or fewer.
 static CellGeometry cell_geometry(uint32_t bucket, uint32_t* nw_out) {
     const uint32_t bc = bucket >> 5;
     uint32_t nw = 4u;
-    for (uint32_t w = 5u; w <= 8u; ++w) {
+    for (uint32_t w = 5u; w <= 7u; ++w) {
         // used fractions (w * 64 / bc) * bc / (w * 64), compared by cross-multiplication
         if (((w * 64u) / bc) * bc * nw * 10u > ((nw * 64u) / bc) * bc * w * 11u) nw = w;
     }
@@ -1061,14 +1086,33 @@ uint32_t quantize_cells_tile_elems(uint32_t bucket) {
     return cell_geometry(bucket, &nw).tile_cells * 32u;
 }
 
+// Five waves per SIMD instead of six pay where a wave writes much or places many codes across word
+// boundaries (measured at 100 M elements: buckets 96 and 480 from 3 bits on by 2-4 us, 1504 at 7 and 8 bits)
+static bool cells_cap_occupancy(uint32_t bits, uint32_t bucket) { return bits >= (bucket < 1024u ? 3u : 7u); }
+
 template <int NW>
 static hipError_t launch_cells_nw(const QuantizeArgs& a, const CellGeometry& g, uint32_t tiles, hipStream_t stream) {
-    // Five waves per SIMD instead of six pay where a wave writes much or places many codes across word
-    // boundaries (measured at 100 M elements: buckets 96 and 480 from 3 bits on by 2-4 us, 1504 at 7 and 8 bits)
-    const bool cap = a.bits >= (a.bucket < 1024u ? 3u : 7u);
-    if (cap) hipLaunchKernelGGL((quantize_cells_kernel<NW, 5, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
+    if (cells_cap_occupancy(a.bits, a.bucket)) hipLaunchKernelGGL((quantize_cells_kernel<NW, 5, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
     else hipLaunchKernelGGL((quantize_cells_kernel<NW, 8, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
     return hipGetLastError();
+}
+template <int NW>
+static hipError_t launch_tensors_cells_nw(const BatchQuantizeArgs& a, const CellGeometry& g, uint32_t tiles, hipStream_t stream) {
+    if (cells_cap_occupancy(a.common.bits, a.common.bucket)) hipLaunchKernelGGL((quantize_tensors_cells_kernel<NW, 5, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
+    else hipLaunchKernelGGL((quantize_tensors_cells_kernel<NW, 8, false>), dim3(tiles), dim3(64 * NW), 0, stream, a, g);
+    return hipGetLastError();
+}
+
+// `tiles` counts tiles of quantize_cells_tile_elems(bucket) elements over all layers
+hipError_t launch_quantize_tensors_cells(const BatchQuantizeArgs& a, uint32_t tiles, hipStream_t stream) {
+    uint32_t nw;
+    const CellGeometry g = cell_geometry(a.common.bucket, &nw);
+    switch (nw) {
+        case 5: return launch_tensors_cells_nw<5>(a, g, tiles, stream);
+        case 6: return launch_tensors_cells_nw<6>(a, g, tiles, stream);
+        case 7: return launch_tensors_cells_nw<7>(a, g, tiles, stream);
+        default: return launch_tensors_cells_nw<4>(a, g, tiles, stream);
+    }
 }
 
 hipError_t launch_quantize_cells(const QuantizeArgs& a, hipStream_t stream) {
@@ -1078,11 +1122,10 @@ hipError_t launch_quantize_cells(const QuantizeArgs& a, hipStream_t stream) {
     const uint64_t tiles = (a.n + tile_elems - 1) / tile_elems;
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     switch (nw) {
-        case 4: return launch_cells_nw<4>(a, g, (uint32_t)tiles, stream);
         case 5: return launch_cells_nw<5>(a, g, (uint32_t)tiles, stream);
         case 6: return launch_cells_nw<6>(a, g, (uint32_t)tiles, stream);
         case 7: return launch_cells_nw<7>(a, g, (uint32_t)tiles, stream);
-        default: return launch_cells_nw<8>(a, g, (uint32_t)tiles, stream);
+        default: return launch_cells_nw<4>(a, g, (uint32_t)tiles, stream);
     }
 }
 

@@ -78,10 +78,11 @@ def test_multi_tile_with_ragged_tail_and_straddling_widths():
             assert_quantize_parity(g, bits, bucket, seed=11, iteration=9, worker=5, label="B=%d b=%d" % (bucket, bits))
 
 
-@pytest.mark.parametrize("bucket", [96, 160, 480, 1504, 2752, 4064])
+@pytest.mark.parametrize("bucket", [96, 160, 480, 1184, 1376, 1504, 1760, 2752, 4064])
 def test_buckets_of_any_whole_number_of_cells(bucket):
     # multiples of 32 that are not powers of two: several workgroup tiles, buckets that lie in two waves,
-    # four and eight waves per workgroup (2752), a ragged tail, a 4-byte aligned view, given scales
+    # workgroups of four (96 .. 480, 1504, 4064), five (1376), six (1184, 2752) and seven (1760) waves, a
+    # ragged tail, a 4-byte aligned view, given scales
     n = 3 * 16384 + 4096 + 777
     base = workloads.normal_with_outliers(n + 3, 1e-3, 1e-3, 100.0, 6, DEV)
     for bits in (1, 3, 4, 7, 8):
