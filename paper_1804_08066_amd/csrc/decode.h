@@ -189,35 +189,38 @@ __device__ __forceinline__ void accumulate_quad_bytes(uint32_t lo, float d, floa
     acc.w = __builtin_fmaf(__builtin_fmaf(k3, 2.0f, -255.0f), d, acc.w);
 }
 
-// Widths 1, 2 and 3 (and 4) through a table of multipliers in LDS.  The multiplier (float)(2c - L) depends on the code alone, so the pairs
-// (2 c0 - L, 2 c1 - L) of two adjacent codes are tabulated once per workgroup -- 4^bits entries of two
-// floats: 32, 128 or 512 bytes -- and a lane fetches the two pairs of its quad with two 64-bit LDS reads
-// (the LDS pipe, not the vector ALU).  What is left for the vector ALU is one rotation per quad, the two
-// table offsets, and the chain's own fma per code -- an fp32 fma whose multiplicand is a register, which
-// this chip issues alongside other vector work.  Results are those of the all-fp32 form bit for bit: the
-// table holds the same multiplier, and the chain's fma is the same instruction.
+// Widths 1 to 4 through a table in LDS.  The multiplier (float)(2c - L) depends on the code alone, so the
+// pairs (2 c0 - L, 2 c1 - L) of two adjacent codes are tabulated once per workgroup -- 4^bits entries of
+// two floats: 32 bytes to 2 KB -- and a lane fetches the two pairs of its quad with two 64-bit LDS reads
+// (the LDS pipe, not the vector ALU); at one bit a whole quad indexes a table of 16 entries of four
+// floats.  What is left for the vector ALU is one rotation per quad, the two table offsets and the
+// chain's own fma per code.  Results are those of the all-fp32 form bit for bit: the table holds the same
+// multiplier, and the chain's fma is the same instruction.  Used where the decode's vector operations
+// limit the kernel: the fused update with more than eight workers up to 3 bits, the re-quantizing step
+// up to 4 bits (the [min, max] re-encoding kernels did not gain: 164 against 149 us).  Wider codes gain
+// nothing either: a pair table for 5 bits (8 KB) helped at some
+// bucket sizes and hurt at others, one for 6 bits (32 KB) costs more occupancy than the decode saves.
 constexpr uint32_t kLutFloats = 512;   // 4^4 entries of two floats
-__device__ __forceinline__ void build_pair_lut(float* lut, uint32_t b, uint32_t tid) {
-    const uint32_t L = (1u << b) - 1u;
+// Filled by `nthreads` threads (tid = 0 .. nthreads - 1); a barrier must follow.
+__device__ __forceinline__ void build_pair_lut(float* lut, uint32_t b, uint32_t tid, uint32_t nthreads = 256u) {
+    const int L = (int)((1u << b) - 1u);
+    const auto value = [&](uint32_t c) { return (float)(2 * (int)c - L); };
     if (b == 1u) {
-        // one bit: a whole quad indexes the table (16 entries of four floats), one 128-bit read per quad
-        if (tid < 64u) lut[tid] = ((tid >> 2) >> (tid & 3u)) & 1u ? 1.0f : -1.0f;
-    } else if (tid < (1u << (2u * b))) {
-        lut[2u * tid] = (float)(2 * (int)(tid & L) - (int)L);
-        lut[2u * tid + 1u] = (float)(2 * (int)(tid >> b) - (int)L);
+        if (tid < 64u) lut[tid] = value(((tid >> 2) >> (tid & 3u)) & 1u);   // entry tid / 4, element tid % 4
+    } else {
+        for (uint32_t e = tid; e < (1u << (2u * b)); e += nthreads) {
+            lut[2u * e] = value(e & (uint32_t)L);
+            lut[2u * e + 1u] = value(e >> b);
+        }
     }
 }
-// B = bits (1, 2, 4: a quad lies inside one word; 3: it may spill into the next lane's word)
+// The table entries of one quad: B = bits (1, 2, 4: the quad lies inside one word; 3: it may spill into
+// the next lane's word, which arrives through a one-lane DPP shift -- call with all lanes active).
 template <int B>
-__device__ __forceinline__ void accumulate_quad_lut(uint32_t lo, uint32_t sh, const float* lut, float d, float4& acc) {
+__device__ __forceinline__ float4 lut_quad(uint32_t lo, uint32_t sh, const float* lut) {
     if (B == 1) {
         const uint32_t r = __builtin_amdgcn_alignbit(lo, lo, (sh - 4u) & 31u);   // rotate: bit sh moves to bit 4
-        const float4 m = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(lut) + (r & 0xF0u));
-        acc.x = __builtin_fmaf(m.x, d, acc.x);
-        acc.y = __builtin_fmaf(m.y, d, acc.y);
-        acc.z = __builtin_fmaf(m.z, d, acc.z);
-        acc.w = __builtin_fmaf(m.w, d, acc.w);
-        return;
+        return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(lut) + (r & 0xF0u));
     }
     constexpr uint32_t kMask = ((1u << (2 * B)) - 1u) << 3;   // a pair's index times the entry size
     uint32_t oa, ob;
@@ -233,10 +236,15 @@ __device__ __forceinline__ void accumulate_quad_lut(uint32_t lo, uint32_t sh, co
     }
     const float2 ma = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(lut) + oa);
     const float2 mb = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(lut) + ob);
-    acc.x = __builtin_fmaf(ma.x, d, acc.x);
-    acc.y = __builtin_fmaf(ma.y, d, acc.y);
-    acc.z = __builtin_fmaf(mb.x, d, acc.z);
-    acc.w = __builtin_fmaf(mb.y, d, acc.w);
+    return make_float4(ma.x, ma.y, mb.x, mb.y);
+}
+template <int B>
+__device__ __forceinline__ void accumulate_quad_lut(uint32_t lo, uint32_t sh, const float* lut, float d, float4& acc) {
+    const float4 m = lut_quad<B>(lo, sh, lut);
+    acc.x = __builtin_fmaf(m.x, d, acc.x);
+    acc.y = __builtin_fmaf(m.y, d, acc.y);
+    acc.z = __builtin_fmaf(m.z, d, acc.z);
+    acc.w = __builtin_fmaf(m.w, d, acc.w);
 }
 
 // Dispatch on the width class: WIDTH = 1 or 8 select the three-operation forms above, 0 the general one.
