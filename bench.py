@@ -386,7 +386,11 @@ def time_exchange(wl, bits, bucket, lr, steps, warmup):
     m_bytes = W * (n * bits / 8.0 + 4.0 * nb) + 4.0 * n
     r_bytes = (W + 1) * (n * bits / 8.0 + 4.0 * nb)
     d_bytes = n * bits / 8.0 + 4.0 * nb + 8.0 * n
-    r_ops = n * ((3.0 if bits in (1, 8) else 3.5) * W + 17.0)   # decode: 3 operations per code at 1 and 8 bits, else 3.5
+    # vector operations the kernel's algorithm issues per element: per worker's code 1.5 (1 bit: quad table)
+    # or 1.75 (2-4 bits: pair table) for table offsets + the chain's fma, 3 at 8 bits, 3.5 at 5-7 bits
+    # (arithmetic decode); about 14 to encode (range, Philox / 8, fixed-point rounding, packing)
+    per_code = 1.5 if bits == 1 else (1.75 if bits <= 4 else (3.0 if bits == 8 else 3.5))
+    r_ops = n * (per_code * W + 14.0)
     log("exchange: requantize %.1f us (%.1f T lane-ops/s, %.0f GB/s), dequantize_update %.1f us (%.0f GB/s), "
         "aggregate_mean %.1f us (%.0f GB/s)" %
         (r_ms * 1e3, r_ops / (r_ms * 1e-3) / 1e12, r_bytes / (r_ms * 1e-3) / 1e9, d_ms * 1e3, d_bytes / (d_ms * 1e-3) / 1e9,
