@@ -74,12 +74,16 @@ def aggregate_bytes(n, bits, bucket, W):
 
 
 class Workload:
-    def __init__(self, n, W, device):
+    def __init__(self, n, W, device, buffers=0):
+        """W workers over `buffers` distinct gradient buffers (0: one per worker); worker w reads buffer
+        w % buffers -- for shapes whose W full-size gradients would not fit beside the code streams."""
         import torch
         from paper_1804_08066_amd import workloads
         self.n, self.W, self.device = n, W, device
-        log("generating %d gradient buffers of %d fp32 (%.2f GB)" % (W, n, 4e-9 * n * W))
-        self.grads = [workloads.config4_grad(w, n, device) for w in range(W)]
+        G = W if buffers <= 0 else min(buffers, W)
+        log("generating %d gradient buffers of %d fp32 (%.2f GB) for %d workers" % (G, n, 4e-9 * n * G, W))
+        distinct = [workloads.config4_grad(w, n, device) for w in range(G)]
+        self.grads = [distinct[w % G] for w in range(W)]
         self.params = workloads.uniform(n, -0.05, 0.05, 1, device)
         self.bufs = {}
         torch.cuda.synchronize()
@@ -604,6 +608,9 @@ def main():
                          "same --steps / --warmup are also timed BEFORE them and reported as `cold`")
     ap.add_argument("--n", type=int, default=100_000_000)
     ap.add_argument("--workers", type=int, default=8)
+    ap.add_argument("--grad-buffers", type=int, default=0,
+                    help="distinct gradient buffers shared by the workers (0 = one per worker); for sizes like "
+                         "--n 1000000000 --workers 16, where 16 full gradients do not need to be resident")
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--bucket", type=int, default=1024)
     ap.add_argument("--lr", type=float, default=0.1)
@@ -641,7 +648,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     n, W, bits, bucket = args.n, args.workers, args.bits, args.bucket
-    wl = Workload(n, W, dev)
+    wl = Workload(n, W, dev, args.grad_buffers)
 
     transient_series = transient(wl, bits, bucket, args.lr, args.transient) if args.transient > 0 else None
     qb, ab = quantize_bytes(n, bits, bucket), aggregate_bytes(n, bits, bucket, W)

@@ -21,11 +21,16 @@ import os
 import subprocess
 import sys
 
-KERNELS = ("requantize_wave_kernel", "requantize_pack_kernel", "requantize_minmax_kernel", "aggregate_update_rows_kernel",
-           "aggregate_update_lds_kernel", "aggregate_update_minmax_kernel", "aggregate_update_tensors_kernel",
-           "aggregate_mean_kernel", "tensor_range_kernel", "sum_squares_kernel", "quantize_minmax_wave_kernel",
-           "quantize_minmax_kernel", "quantize_tensors_wave_kernel", "quantize_tensors_kernel", "quantize_wave_kernel",
-           "quantize_pack_kernel", "stream_quantize_kernel", "stream_update_kernel", "range_", "clear_", "finish_")
+# matched as substrings, first hit wins: a name that contains another comes before it
+KERNELS = ("requantize_wave_kernel", "requantize_pack_kernel", "requantize_minmax_tensor_kernel", "requantize_minmax_kernel",
+           "sum_range_minmax_tensor_kernel", "aggregate_update_rows_kernel", "aggregate_update_lds_kernel",
+           "aggregate_update_minmax_tensors_kernel", "aggregate_update_minmax_kernel", "aggregate_update_tensors_kernel",
+           "aggregate_mean_kernel", "tensor_range_batch_kernel", "tensor_range_kernel", "sum_squares_partial_kernel",
+           "sum_squares_finish_kernel", "sum_squares_kernel", "quantize_minmax_tensors_wave_kernel",
+           "quantize_minmax_tensors_kernel", "quantize_minmax_wave_kernel", "quantize_minmax_kernel",
+           "quantize_tensors_wave_kernel", "quantize_tensors_cells_kernel", "quantize_tensors_kernel", "quantize_wave_kernel",
+           "quantize_cells_kernel", "quantize_pack_kernel", "stream_quantize_kernel", "stream_update_kernel", "range_",
+           "clear_", "finish_")
 
 
 def short(name):
@@ -105,8 +110,9 @@ def cmd_stats(a):
 def cmd_sweep(a):
     out = head(a.title, a.cmd)
     out += ["| bits | bucket | workers | quantize kernel | calls | avg us (rocprofv3) | avg us (HIP events) | % of 8 TB/s | "
-            "server kernel | calls | avg us (rocprofv3) | avg us (HIP events) | % of 8 TB/s |",
-            "|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+            "streaming ceiling us | server kernel | calls | avg us (rocprofv3) | avg us (HIP events) | % of 8 TB/s | "
+            "streaming ceiling us |",
+            "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for spec in a.run:
         point, sdir, jpath = spec.split(":")
         b, B, W = (int(x) for x in point.split(","))
@@ -115,13 +121,18 @@ def cmd_sweep(a):
         qk = next((k for k in ks if k.startswith("quantize")), None)
         sk = next((k for k in ks if k.startswith("aggregate")), None)
         r, ra = d["roofline"], d["roofline_aggregate"]
-        out.append("| %d | %d | %d | %s | %d | %.1f | %.1f | %.1f | %s | %d | %.1f | %.1f | %.1f |" %
-                   (b, B, W, qk, ks[qk][0], ks[qk][1] / 1e3, r["avg_launch_us"], 100 * r["frac"],
-                    sk, ks[sk][0], ks[sk][1] / 1e3, ra["avg_launch_us"], 100 * ra["frac"]))
+        ce = d.get("stream_ceiling") or {}
+        cq = "%.1f" % ce["quantize_mix"]["us"] if ce else "-"
+        cu = "%.1f" % ce["update_mix"]["us"] if ce else "-"
+        out.append("| %d | %d | %d | %s | %d | %.1f | %.1f | %.1f | %s | %s | %d | %.1f | %.1f | %.1f | %s |" %
+                   (b, B, W, qk, ks[qk][0], ks[qk][1] / 1e3, r["avg_launch_us"], 100 * r["frac"], cq,
+                    sk, ks[sk][0], ks[sk][1] / 1e3, ra["avg_launch_us"], 100 * ra["frac"], cu))
     out.append("")
     out.append("The HIP-event columns are bench.py's averages over its timed region (after the conditioning steps); the "
                "rocprofv3 columns average every launch of the process, the cold region and the warm-up included.  "
-               "Percentages: algorithmic bytes per launch / HIP-event time / 8 TB/s.")
+               "Percentages: algorithmic bytes per launch / HIP-event time / 8 TB/s.  Streaming ceiling: the time of "
+               "bench.py's streaming kernel for that kernel's read/write mix in the same run (same loads and stores, no "
+               "arithmetic; HIP events).")
     write(a.out, out)
 
 
