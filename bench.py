@@ -172,6 +172,10 @@ def bench_lib():
         L.mqg_bench_stream_quantize.restype = C.c_int
         L.mqg_bench_stream_update.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
         L.mqg_bench_stream_update.restype = C.c_int
+        L.mqg_bench_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+        L.mqg_bench_stream_read.restype = C.c_int
+        L.mqg_bench_stream_write.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
+        L.mqg_bench_stream_write.restype = C.c_int
         _bench_lib = L
     return _bench_lib
 
@@ -215,7 +219,28 @@ def stream_ceilings(wl, bits, bucket, steps=40, warmup=20):
     (q_ms, q_shape), (u_ms, u_shape) = best, best_u
     q_gbs = n8 * (4.0 + bits / 8.0) / (q_ms * 1e-3) / 1e9
     u_gbs = n8 * (8.0 + wl.W * bits / 8.0) / (u_ms * 1e-3) / 1e9
+    # pure read and pure write of one gradient buffer: the additive bound of a mix is its read bytes at the
+    # read rate plus its written bytes at the write rate
     dst = torch.empty_like(wl.grads[0])
+    sink = torch.zeros(256, dtype=torch.float32, device=wl.device)
+    def pure(fn, reps=30):
+        for k in range(10):
+            fn(k)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            fn(k)
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(reps))
+        return 4.0 * n8 / (ts[reps // 2] * 1e-3) / 1e9
+    def rd(k):
+        assert L.mqg_bench_stream_read(wl.grads[k % wl.W].data_ptr(), n8, sink.data_ptr(), stream) == 0
+    def wr(k):
+        assert L.mqg_bench_stream_write(dst.data_ptr(), n8, stream) == 0
+    read_gbs, write_gbs = pure(rd), pure(wr)
+    q_add_us = (4.0 * n8 / read_gbs + n8 * bits / 8.0 / write_gbs) * 1e-3
+    u_add_us = ((4.0 + wl.W * bits / 8.0) * n8 / read_gbs + 4.0 * n8 / write_gbs) * 1e-3
     reps = 30
     for k in range(10):
         dst.copy_(wl.grads[k % wl.W])
@@ -234,6 +259,10 @@ def stream_ceilings(wl, bits, bucket, steps=40, warmup=20):
             "update_mix": {"kernel": "stream_update_kernel (bench only), best of two occupancy caps: " + u_shape,
                            "us": u_ms * 1e3, "gbs": u_gbs,
                            "frac_of_peak": u_gbs / HBM_PEAK_GBS},
+            "pure_read": {"kernel": "stream_read_kernel (bench only)", "gbs": read_gbs, "frac_of_peak": read_gbs / HBM_PEAK_GBS},
+            "pure_write": {"kernel": "stream_write_kernel (bench only)", "gbs": write_gbs, "frac_of_peak": write_gbs / HBM_PEAK_GBS},
+            "additive_bound": {"what": "read bytes / pure read rate + written bytes / pure write rate",
+                               "quantize_us": q_add_us, "update_us": u_add_us},
             "torch_copy": {"kernel": "torch copy_ of one gradient buffer", "gbs": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS}}
 
 
@@ -681,10 +710,11 @@ def main():
     spread = dict(time_config.last)
     ceil = stream_ceilings(wl, bits, bucket)
     log("streaming ceilings: quantize mix %.1f us = %.0f GB/s (%.1f%% of peak), update mix %.1f us = %.0f GB/s (%.1f%%), "
-        "torch copy_ %.0f GB/s (%.1f%%)" %
+        "torch copy_ %.0f GB/s (%.1f%%); pure read %.0f GB/s, pure write %.0f GB/s -> additive bounds %.1f us / %.1f us" %
         (ceil["quantize_mix"]["us"], ceil["quantize_mix"]["gbs"], 100 * ceil["quantize_mix"]["frac_of_peak"],
          ceil["update_mix"]["us"], ceil["update_mix"]["gbs"], 100 * ceil["update_mix"]["frac_of_peak"],
-         ceil["torch_copy"]["gbs"], 100 * ceil["torch_copy"]["frac_of_peak"]))
+         ceil["torch_copy"]["gbs"], 100 * ceil["torch_copy"]["frac_of_peak"], ceil["pure_read"]["gbs"], ceil["pure_write"]["gbs"],
+         ceil["additive_bound"]["quantize_us"], ceil["additive_bound"]["update_us"]))
 
     traffic = measured_traffic(n, W, bits, bucket)
     q_traffic = traffic["quantize_wave_kernel"] if traffic else None

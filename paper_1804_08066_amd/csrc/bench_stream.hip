@@ -7,6 +7,9 @@
 //   mqg_bench_stream_quantize   reads n floats, writes n * bits / 32 words        (mqg_quantize's mix)
 //   mqg_bench_stream_update     reads W streams of n * bits / 32 words and n floats, writes n floats
 //                               (mqg_aggregate_update's mix)
+//   mqg_bench_stream_read / _write   a pure read and a pure write of n floats: the two rates from which the
+//                               benchmark adds up the time a mix would take if reads and writes did not
+//                               disturb each other
 //
 // Built into libmqgrad_bench.so, which only bench.py loads.  Sizes: n is rounded down to whole tiles by
 // the caller (bench.py passes multiples of 8192); pointers are device pointers, 16-byte aligned.
@@ -99,9 +102,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, OCC))) v
     }
 }
 
+// Pure streams: 4096 floats per workgroup of 256 lanes, four float4 per lane, streaming hints.  What a
+// kernel that only reads, or only writes, reaches on this machine.
+__global__ __launch_bounds__(256) void stream_read_kernel(const float* __restrict__ src, uint64_t n, float* sink) {
+    const uint64_t base = (uint64_t)blockIdx.x * 4096u;
+    if (base + 4096u > n) return;
+    v4f x[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) x[j] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + base + 4u * (j * 256u + threadIdx.x)));
+    float m = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) m += (x[j].x + x[j].y) + (x[j].z + x[j].w);
+    if (m == 1234.5678f) sink[threadIdx.x] = m;   // practically never taken: keeps the loads alive
+}
+__global__ __launch_bounds__(256) void stream_write_kernel(float* __restrict__ dst, uint64_t n) {
+    const uint64_t base = (uint64_t)blockIdx.x * 4096u;
+    if (base + 4096u > n) return;
+    const v4f v = {1.0f, 2.0f, 3.0f, (float)blockIdx.x};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(dst + base + 4u * (j * 256u + threadIdx.x)));
+}
+
 }  // namespace
 
 extern "C" {
+
+// Read n floats (n a multiple of 4096); sink: device, 256 floats, practically never written.
+int mqg_bench_stream_read(const float* src, uint64_t n, float* sink, void* stream) {
+    if (n == 0) return 0;
+    if (n % 4096u != 0u || n / 4096u > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(stream_read_kernel, dim3((uint32_t)(n / 4096u)), dim3(256), 0, (hipStream_t)stream, src, n, sink);
+    return (int)hipGetLastError();
+}
+// Overwrite n floats (n a multiple of 4096).
+int mqg_bench_stream_write(float* dst, uint64_t n, void* stream) {
+    if (n == 0) return 0;
+    if (n % 4096u != 0u || n / 4096u > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(stream_write_kernel, dim3((uint32_t)(n / 4096u)), dim3(256), 0, (hipStream_t)stream, dst, n);
+    return (int)hipGetLastError();
+}
 
 // 0 on success, otherwise the hipError_t of the launch.  n must be a multiple of 8192, bits in 1..8.
 // shape: 0 = 2048 floats per wave, 4 waves per workgroup (the quantizer's shape up to 7 bits);
