@@ -13,8 +13,9 @@
 // spilling into the next word otherwise (and that word is the next lane's first word).  Each lane
 // fetches its first word of every worker with one aligned dword load -- adjacent lanes read the same
 // or adjacent words, so a wave's request is one contiguous run of 32*bits bytes -- and all loads of
-// a chunk of 8 workers are issued before any is consumed.  Parameters and codes are touched once, so they move with the
-// non-temporal hint.  The de-quantized gradient never exists in HBM.
+// a chunk of 8 workers are issued before any is consumed.  Parameters are touched once and move with
+// the non-temporal hint; so do the code words from 4 bits on (decode::codes_read_once).  The
+// de-quantized gradient never exists in HBM.
 //
 // The per-bucket steps d = s_w / L (one IEEE division per bucket and worker) are shared in one of
 // two ways.  Buckets that are multiples of 128 elements: a wave's row of 256 parameters touches
@@ -28,14 +29,13 @@
 
 #include <type_traits>
 
-#ifndef MQG_AGG_ROWS_R
-#define MQG_AGG_ROWS_R 2
-#endif
-
 namespace mqg {
 namespace {
 
 constexpr int kChunk = 8;   // workers whose code loads are in flight together
+// float4 per lane in the wave-local kernel (2048 parameters per workgroup); four spilled registers at the
+// eight waves per SIMD the kernel needs and ran 2-4 times slower
+constexpr int kRowsR = 2;
 
 using namespace tile_io;
 
@@ -375,7 +375,7 @@ hipError_t launch_mean_s(const AggregateArgs& a, hipStream_t stream) {
 // a.params: the output (n floats); a.neg_c unused
 hipError_t launch_aggregate_mean(const AggregateArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
-    constexpr int R = MQG_AGG_ROWS_R;
+    constexpr int R = kRowsR;
     const bool straddle = (32u % a.bits) != 0u;
     if (a.bucket % 256u == 0u) {
         return straddle ? launch_mean_rows<R, 1, true>(a, stream) : launch_mean_rows<R, 1, false>(a, stream);
@@ -396,7 +396,7 @@ hipError_t launch_aggregate_tensors(const BatchAggregateArgs& a, uint32_t tiles,
 
 hipError_t launch_aggregate(const AggregateArgs& a, hipStream_t stream) {
     if (a.n == 0) return hipSuccess;
-    constexpr int R = MQG_AGG_ROWS_R;
+    constexpr int R = kRowsR;
     const bool straddle = (32u % a.bits) != 0u;   // widths 3, 5, 6, 7
     if (a.bucket % 256u == 0u) {
         return straddle ? launch_rows<R, 1, true>(a, stream) : launch_rows<R, 1, false>(a, stream);
