@@ -156,6 +156,12 @@ mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* 
                                     uint64_t n, uint32_t bits, uint32_t bucket,
                                     uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
                                     uint32_t* packed_out, float* scales_out, void* stream);
+/* The same with the bucket range of mqg_quantize_mode: MQG_SCALE_L2 takes S = the L2 norm of the sum's
+ * bucket (raised to max |sum| if rounding left it below), and stores S / W. */
+mqg_status mqg_aggregate_requantize_mode(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                         uint64_t n, uint32_t bits, uint32_t bucket, mqg_scale_mode mode,
+                                         uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                                         uint32_t* packed_out, float* scales_out, void* stream);
 
 /* The worker's half: params[i] <- fma(-lr, (2 c_i - L) * (s_k / L), params[i]), i.e. w <- w - eta *
  * De-quantize(gbar).  Same as mqg_aggregate_update with one worker. */

@@ -72,6 +72,23 @@ mqg_status sumsq_batch_args(const mqg_sumsq_item* items, uint32_t count, const d
     return MQG_OK;
 }
 
+// The W workers' stream and scale pointers of a server call into a launch table (slots past W cleared).
+// `pairs`: the scale arrays hold (min, max) pairs and must be 8-byte aligned.
+mqg_status worker_tables(const uint32_t* const* packed, const float* const* scales, uint32_t W, bool pairs,
+                         const uint32_t* (&packed_tab)[MQG_MAX_WORKERS], const float* (&scales_tab)[MQG_MAX_WORKERS]) {
+    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
+        packed_tab[w] = nullptr;
+        scales_tab[w] = nullptr;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
+        if (misaligned4(packed[w]) || (pairs ? misaligned8(scales[w]) : misaligned4(scales[w]))) return MQG_EALIGN;
+        packed_tab[w] = packed[w];
+        scales_tab[w] = scales[w];
+    }
+    return MQG_OK;
+}
+
 // Fills the launch table of a batched server step; `minmax`: the scale arrays hold (min, max) pairs and
 // must be 8-byte aligned.  MQG_OK with *tiles_out == 0 when there is nothing to do.
 mqg_status update_batch_args(const mqg_update_item* items, uint32_t count, uint32_t W, uint32_t bits,
@@ -188,16 +205,8 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(params)) return MQG_EALIGN;
     mqg::AggregateArgs a;
-    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
-        a.packed[w] = nullptr;
-        a.scales[w] = nullptr;
-    }
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned4(scales[w])) return MQG_EALIGN;
-        a.packed[w] = packed[w];
-        a.scales[w] = scales[w];
-    }
+    const mqg_status tables = worker_tables(packed, scales, W, false, a.packed, a.scales);
+    if (tables != MQG_OK) return tables;
     a.W = W;
     a.n = n;
     a.bits = bits;
@@ -220,16 +229,8 @@ mqg_status mqg_aggregate_mean(const uint32_t* const* packed, const float* const*
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(mean_out)) return MQG_EALIGN;
     mqg::AggregateArgs a;
-    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
-        a.packed[w] = nullptr;
-        a.scales[w] = nullptr;
-    }
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned4(scales[w])) return MQG_EALIGN;
-        a.packed[w] = packed[w];
-        a.scales[w] = scales[w];
-    }
+    const mqg_status tables = worker_tables(packed, scales, W, false, a.packed, a.scales);
+    if (tables != MQG_OK) return tables;
     a.W = W;
     a.n = n;
     a.bits = bits;
@@ -246,7 +247,16 @@ mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* 
                                     uint64_t n, uint32_t bits, uint32_t bucket,
                                     uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
                                     uint32_t* packed_out, float* scales_out, void* stream) {
+    return mqg_aggregate_requantize_mode(packed, scales, W, n, bits, bucket, MQG_SCALE_MAXABS, seed, iteration, worker,
+                                         elem_base, packed_out, scales_out, stream);
+}
+
+mqg_status mqg_aggregate_requantize_mode(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                         uint64_t n, uint32_t bits, uint32_t bucket, mqg_scale_mode mode,
+                                         uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                                         uint32_t* packed_out, float* scales_out, void* stream) {
     if (!valid_common(bits, bucket)) return MQG_EINVAL;
+    if (mode != MQG_SCALE_MAXABS && mode != MQG_SCALE_L2) return MQG_EINVAL;
     if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
     if ((elem_base & 7u) != 0u) return MQG_EINVAL;
     if (n == 0) return MQG_OK;
@@ -254,23 +264,15 @@ mqg_status mqg_aggregate_requantize(const uint32_t* const* packed, const float* 
     if (n > (UINT64_MAX >> 4) || elem_base > UINT64_MAX - n) return MQG_EINVAL;
     if (misaligned4(packed_out) || misaligned4(scales_out)) return MQG_EALIGN;
     mqg::RequantArgs ra;
-    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
-        ra.packed[w] = nullptr;
-        ra.scales[w] = nullptr;
-    }
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || scales[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned4(scales[w])) return MQG_EALIGN;
-        ra.packed[w] = packed[w];
-        ra.scales[w] = scales[w];
-    }
+    const mqg_status tables = worker_tables(packed, scales, W, false, ra.packed, ra.scales);
+    if (tables != MQG_OK) return tables;
     ra.W = W;
     ra.q.grad = nullptr;
     ra.q.n = n;
     ra.q.bits = bits;
     ra.q.bucket = bucket;
     ra.q.bucket_shift = log2_if_pow2(bucket);
-    ra.q.scale_mode = MQG_SCALE_MAXABS;
+    ra.q.scale_mode = mode;
     ra.q.key0 = (uint32_t)seed;
     ra.q.key1 = (uint32_t)(seed >> 32);
     ra.q.iteration = iteration;
@@ -445,16 +447,8 @@ mqg_status mqg_aggregate_update_minmax(const uint32_t* const* packed, const floa
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(params)) return MQG_EALIGN;
     mqg::AggregateArgs a;
-    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
-        a.packed[w] = nullptr;
-        a.scales[w] = nullptr;
-    }
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
-        a.packed[w] = packed[w];
-        a.scales[w] = ranges[w];
-    }
+    const mqg_status tables = worker_tables(packed, ranges, W, true, a.packed, a.scales);
+    if (tables != MQG_OK) return tables;
     a.W = W;
     a.n = n;
     a.bits = bits;
@@ -477,12 +471,8 @@ mqg_status mqg_aggregate_requantize_minmax(const uint32_t* const* packed, const 
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(packed_out) || misaligned8(ranges_out)) return MQG_EALIGN;
     mqg::RequantArgs ra = {};
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
-        ra.packed[w] = packed[w];
-        ra.scales[w] = ranges[w];
-    }
+    const mqg_status tables = worker_tables(packed, ranges, W, true, ra.packed, ra.scales);
+    if (tables != MQG_OK) return tables;
     ra.W = W;
     ra.q.n = n;
     ra.q.bits = bits;
@@ -535,16 +525,8 @@ mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, con
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(params)) return MQG_EALIGN;
     mqg::AggregateArgs a;
-    for (uint32_t w = 0; w < MQG_MAX_WORKERS; ++w) {
-        a.packed[w] = nullptr;
-        a.scales[w] = nullptr;
-    }
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
-        a.packed[w] = packed[w];
-        a.scales[w] = ranges[w];
-    }
+    const mqg_status tables = worker_tables(packed, ranges, W, true, a.packed, a.scales);
+    if (tables != MQG_OK) return tables;
     a.W = W;
     a.n = n;
     a.bits = bits;
@@ -567,12 +549,8 @@ mqg_status mqg_aggregate_requantize_minmax_tensor(const uint32_t* const* packed,
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(packed_out) || misaligned8(range_out)) return MQG_EALIGN;
     mqg::RequantArgs ra = {};
-    for (uint32_t w = 0; w < W; ++w) {
-        if (packed[w] == nullptr || ranges[w] == nullptr) return MQG_EINVAL;
-        if (misaligned4(packed[w]) || misaligned8(ranges[w])) return MQG_EALIGN;
-        ra.packed[w] = packed[w];
-        ra.scales[w] = ranges[w];
-    }
+    const mqg_status tables = worker_tables(packed, ranges, W, true, ra.packed, ra.scales);
+    if (tables != MQG_OK) return tables;
     ra.W = W;
     ra.q.n = n;
     ra.q.bits = bits;

@@ -37,7 +37,7 @@ struct AggregateArgs {
 };
 
 // Server side of the full exchange: quantize the sum over W workers' de-quantized gradients
-// (q.grad, q.scales_in unused; q.scale_mode max-abs); the stored bucket range is divided by W.
+// (q.grad, q.scales_in unused); the stored bucket range is divided by W.
 struct RequantArgs {
     QuantizeArgs q;
     const uint32_t* packed[MQG_MAX_WORKERS];

@@ -739,7 +739,7 @@ __global__ __launch_bounds__(64 * NW) void requantize_wave_kernel(const RequantA
             }
         }
     }
-    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm);
+    reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm, a.scale_mode == MQG_SCALE_L2);
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
     if (!active) return;
     const float Wf = (float)ra.W;

@@ -26,7 +26,7 @@ EXPORTS = [
     "mqg_mdp_current_bits", "mqg_mdp_smoothed_losses", "mqg_mdp_last_reward", "mqg_mdp_decisions",
     "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
     "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch", "mqg_sum_squares_batch_static",
-    "mqg_quantize_minmax_tensors", "mqg_aggregate_update_minmax_tensors",
+    "mqg_quantize_minmax_tensors", "mqg_aggregate_update_minmax_tensors", "mqg_aggregate_requantize_mode",
 ]
 
 
@@ -99,6 +99,8 @@ def lib():
     L.mqg_aggregate_update.restype = C.c_int
     L.mqg_aggregate_requantize.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp]
     L.mqg_aggregate_requantize.restype = C.c_int
+    L.mqg_aggregate_requantize_mode.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, C.c_int, u64, u32, u32, u64, vp, vp, vp]
+    L.mqg_aggregate_requantize_mode.restype = C.c_int
     L.mqg_dequantize_update.argtypes = [vp, vp, u64, u32, u32, f32, vp, vp]
     L.mqg_dequantize_update.restype = C.c_int
     L.mqg_quantize_tensors.argtypes = [C.POINTER(QuantizeItem), u32, u32, u32, u64, u32, u32, vp]
@@ -283,9 +285,9 @@ def mqg_aggregate_mean(packed, scales, n, bits, bucket, mean_out=None, stream=No
 
 
 def mqg_aggregate_requantize(packed, scales, n, bits, bucket, seed, iteration=0, worker=0, elem_base=0,
-                             packed_out=None, scales_out=None, stream=None):
-    """Server's half of the full exchange: quantized mean of the W workers' gradients.
-    Returns (packed int32[words], scales fp32[nb])."""
+                             packed_out=None, scales_out=None, stream=None, mode=MQG_SCALE_MAXABS):
+    """Server's half of the full exchange: quantized mean of the W workers' gradients (mode: the bucket
+    range of the sum, max-abs or L2 norm).  Returns (packed int32[words], scales fp32[nb])."""
     W, pa, sa = _worker_arrays(packed, scales, n, bits, bucket)
     dev = packed[0].device if W else "cuda"
     if packed_out is None or scales_out is None:
@@ -296,8 +298,8 @@ def mqg_aggregate_requantize(packed, scales, n, bits, bucket, seed, iteration=0,
     _check(scales_out, torch.float32, "scales_out")
     if packed_out.numel() < mqg_packed_words(n, bits) or scales_out.numel() < mqg_num_buckets(n, bucket):
         raise ValueError("output buffers too small")
-    st = lib().mqg_aggregate_requantize(pa, sa, W, n, bits, bucket, seed, iteration, worker, elem_base,
-                                        packed_out.data_ptr(), scales_out.data_ptr(), _stream_handle(stream))
+    st = lib().mqg_aggregate_requantize_mode(pa, sa, W, n, bits, bucket, int(mode), seed, iteration, worker, elem_base,
+                                             packed_out.data_ptr(), scales_out.data_ptr(), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_requantize")
     return packed_out, scales_out

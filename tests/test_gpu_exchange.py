@@ -99,3 +99,28 @@ def test_mean_gradient_output_matches_oracle(bits, W, bucket):
     want = ref.aggregate_mean([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n, bits, bucket)
     assert out.cpu().numpy().tobytes() == want.tobytes()
     assert store[0].item() == 7.0 and store[n + 1].item() == 7.0          # neighbours untouched
+
+
+@pytest.mark.parametrize("bucket", [96, 128, 512, 1024, 4096, 16384])
+def test_requantize_with_the_l2_range(bucket):
+    # the server's re-encoding step with the bucket's L2 norm of the sum as the range: the stored scales are
+    # S / W with S within 1e-6 of the oracle's norm (summed in fp64) and never below max |sum|; the codes are
+    # those of the oracle's quantizer on the fp32 sum with the library's own S injected (W a power of two,
+    # so S = W * (S / W) exactly)
+    n, W = 3 * 16384 + 4096 + 21, 4
+    grads = [workloads.normal_with_outliers(n, 1e-2, 1e-2, 30.0, 300 + w, DEV) for w in range(W)]
+    for bits in (1, 3, 4, 7):
+        q = [mqgrad.mqg_quantize(g, bits, bucket, seed=2, iteration=1, worker=w) for w, g in enumerate(grads)]
+        mpk, msc = mqgrad.mqg_aggregate_requantize([x[0] for x in q], [x[1] for x in q], n, bits, bucket, seed=2,
+                                                   iteration=1, worker=W, mode=mqgrad.MQG_SCALE_L2)
+        again = mqgrad.mqg_aggregate_requantize([x[0] for x in q], [x[1] for x in q], n, bits, bucket, seed=2,
+                                                iteration=1, worker=W, mode=mqgrad.MQG_SCALE_L2)
+        torch.cuda.synchronize()
+        assert torch.equal(mpk, again[0]) and torch.equal(msc, again[1])          # reproducible
+        total = ref.aggregate_sum([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n, bits, bucket)
+        S = msc.cpu().numpy() * np.float32(W)
+        want = ref.bucket_scales(total, bucket, ref.SCALE_L2)
+        assert np.all(np.abs(S.astype(np.float64) - want) <= 1e-6 * want), "b=%d" % bits
+        assert np.all(S >= ref.bucket_scales(total, bucket, ref.SCALE_MAXABS))
+        pk_o, _ = ref.quantize(total, bits, bucket, 2, 1, W, 0, scales_in=S)
+        assert np.array_equal(to_u32(mpk), pk_o), "b=%d" % bits
