@@ -353,40 +353,58 @@ __device__ __forceinline__ void quantize_and_pack(const QuantizeArgs& a, uint64_
     store_chunk_words<R, NW, FULL>(out, count, b, lane, wave, sm);
 }
 
+// A wave's chunk and how buckets lie in it.  WPB == 1: the chunk holds nbc = CH / bucket whole buckets; a
+// bucket is `seg_lanes` lanes of one row (bucket <= 256) or `rpb` whole rows (bucket >= 256).  WPB > 1:
+// the chunk is part of one bucket.
+template <int R>
+struct ChunkShape {
+    uint32_t lane, wave;   // wave: uniform (read with v_readfirstlane), so what follows from it is scalar work
+    uint64_t chunk, cb;    // chunk index; first element of the chunk
+    bool active, full;     // the chunk starts inside the tensor; it lies inside it entirely
+    uint32_t count;        // elements of the chunk inside the tensor
+    uint32_t nbc;          // buckets per chunk
+    uint32_t seg_lanes;    // lanes of a row that share a bucket
+    uint32_t rpb;          // rows per bucket
+    uint64_t kb_first;     // global index of the chunk's first bucket
+    uint32_t slot[R];      // bucket (chunk-local) of row j's quad
+};
+template <int R, int WPB, int NW>
+__device__ __forceinline__ ChunkShape<R> chunk_shape(const QuantizeArgs& a, const uint64_t block) {
+    constexpr uint32_t CH = 256u * R;
+    static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
+    ChunkShape<R> c;
+    const uint32_t tid = threadIdx.x;
+    c.lane = tid & 63u;
+    c.wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    c.chunk = block * NW + c.wave;
+    c.cb = c.chunk * CH;
+    c.active = c.cb < a.n;   // waves past the end only keep the barrier company
+    c.count = !c.active ? 0u : (a.n - c.cb < CH ? (uint32_t)(a.n - c.cb) : CH);
+    c.full = c.count == CH;
+    const uint32_t shift = (uint32_t)a.bucket_shift;   // log2(bucket), >= 5
+    c.nbc = WPB > 1 ? 1u : (CH >> shift);
+    c.seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
+    c.rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);
+    c.kb_first = WPB > 1 ? (c.chunk / WPB) : (c.cb >> shift);
+#pragma unroll
+    for (int j = 0; j < R; ++j) c.slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + c.lane)) >> shift);
+    return c;
+}
+
 // R: float4 per lane; WPB: waves per bucket (1: bucket <= CH; otherwise bucket = WPB*CH);
 // NW: waves per workgroup, a multiple of WPB
 // HOIST: the Philox calls of the chunk are made before the range reduction and its barrier (they depend
 // on the position only) and kept in 2*R registers until the rounding.
 template <int R, int WPB, int NW, bool HOIST>
 __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const uint64_t block, WaveShared<R, NW>& sm) {
-    constexpr uint32_t CH = 256u * R;
-    static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
-
-    const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u;
-    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
-    const uint64_t chunk = block * NW + wave;
-    const uint64_t cb = chunk * CH;                 // first element of the chunk
-    const bool active = cb < a.n;                   // waves past the end only keep the barrier company
-    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
-    const bool full = count == CH;
-
-    // WPB == 1: the chunk holds nbc = CH / bucket whole buckets; a bucket is `seg_lanes` lanes of one
-    // row (bucket <= 256) or `rpb` whole rows (bucket >= 256).  WPB > 1: the chunk is part of one bucket.
-    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 5
-    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);                    // buckets per chunk
-    const uint32_t seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
-    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);   // rows per bucket
-    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);    // global index of the chunk's first bucket
-    uint32_t slot[R];                                                      // bucket (chunk-local) of row j's quad
-#pragma unroll
-    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> shift);
+    const ChunkShape<R> c = chunk_shape<R, WPB, NW>(a, block);
+    const uint32_t lane = c.lane, wave = c.wave;
 
     float4 x[R];
-    if (full) {
-        load_chunk<R, true>(a.grad + cb, count, lane, x);
+    if (c.full) {
+        load_chunk<R, true>(a.grad + c.cb, c.count, lane, x);
     } else {
-        load_chunk<R, false>(a.grad + cb, count, lane, x);
+        load_chunk<R, false>(a.grad + c.cb, c.count, lane, x);
     }
     // while the loads are in flight: clear the wave's packing area; when asked to, draw the chunk's
     // random numbers ahead of the barrier
@@ -394,18 +412,18 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
     Draws<R> draws;
     if (HOIST) {
 #pragma unroll
-        for (int jp = 0; jp < R; jp += 2) draw_pair(a, cb, lane, jp, draws.o[jp / 2]);
+        for (int jp = 0; jp < R; jp += 2) draw_pair(a, c.cb, lane, jp, draws.o[jp / 2]);
     }
     if (a.scales_in == nullptr) {
-        reduce_ranges<R, WPB, NW>(x, lane, wave, slot, seg_lanes, rpb, sm, a.scale_mode == MQG_SCALE_L2);
+        reduce_ranges<R, WPB, NW>(x, lane, wave, c.slot, c.seg_lanes, c.rpb, sm, a.scale_mode == MQG_SCALE_L2);
     }
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
-    if (!active) return;
+    if (!c.active) return;
     const Draws<R>* drawn = HOIST ? &draws : nullptr;
-    if (full) {
-        quantize_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
+    if (c.full) {
+        quantize_and_pack<R, WPB, NW, true>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, 1.0f, drawn);
     } else {
-        quantize_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, false>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, 1.0f, drawn);
     }
 }
 
@@ -919,48 +937,29 @@ __device__ __forceinline__ void encode_minmax_and_pack(const QuantizeArgs& a, ui
 template <int R, int WPB, int NW>
 __device__ __forceinline__ void quantize_minmax_wave_block(const QuantizeArgs& a, const uint32_t block, WaveShared<R, NW>& sm,
                                                            WaveLows<R, NW>& lw) {
-    constexpr uint32_t CH = 256u * R;
-    static_assert(NW % WPB == 0, "the waves of a bucket share a workgroup");
-
-    const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u;
-    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));   // uniform: what follows from it is scalar work
-    const uint64_t chunk = (uint64_t)block * NW + wave;
-    const uint64_t cb = chunk * CH;
-    const bool active = cb < a.n;                   // waves past the end only keep the barrier company
-    const uint32_t count = !active ? 0u : (a.n - cb < CH ? (uint32_t)(a.n - cb) : CH);
-    const bool full = count == CH;
-
-    // chunk / bucket geometry as in quantize_wave_block
-    const uint32_t shift = (uint32_t)a.bucket_shift;                      // log2(bucket), >= 5
-    const uint32_t nbc = WPB > 1 ? 1u : (CH >> shift);
-    const uint32_t seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
-    const uint32_t rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);
-    const uint64_t kb_first = WPB > 1 ? (chunk / WPB) : (cb >> shift);
-    uint32_t slot[R];
-#pragma unroll
-    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> shift);
+    const ChunkShape<R> c = chunk_shape<R, WPB, NW>(a, block);
+    const uint32_t lane = c.lane, wave = c.wave;
 
     float4 x[R];
-    if (full) {
-        load_chunk<R, true>(a.grad + cb, count, lane, x);
+    if (c.full) {
+        load_chunk<R, true>(a.grad + c.cb, c.count, lane, x);
     } else {
-        load_chunk<R, false>(a.grad + cb, count, lane, x);
+        load_chunk<R, false>(a.grad + c.cb, c.count, lane, x);
     }
     clear_words<R, NW>(lane, wave, sm);   // while the loads are in flight
     if (a.scales_in == nullptr) {
-        if (full) {
-            reduce_minmax<R, WPB, NW, true>(x, count, lane, wave, slot, seg_lanes, rpb, sm, lw);
+        if (c.full) {
+            reduce_minmax<R, WPB, NW, true>(x, c.count, lane, wave, c.slot, c.seg_lanes, c.rpb, sm, lw);
         } else {
-            reduce_minmax<R, WPB, NW, false>(x, count, lane, wave, slot, seg_lanes, rpb, sm, lw);
+            reduce_minmax<R, WPB, NW, false>(x, c.count, lane, wave, c.slot, c.seg_lanes, c.rpb, sm, lw);
         }
     }
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
-    if (!active) return;
-    if (full) {
-        encode_minmax_and_pack<R, WPB, NW, true>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
+    if (!c.active) return;
+    if (c.full) {
+        encode_minmax_and_pack<R, WPB, NW, true>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, lw);
     } else {
-        encode_minmax_and_pack<R, WPB, NW, false>(a, cb, count, lane, wave, slot, nbc, kb_first, x, sm, lw);
+        encode_minmax_and_pack<R, WPB, NW, false>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, lw);
     }
 }
 
