@@ -152,6 +152,36 @@ def test_config4_sampled_ranges_and_global_properties():
             assert bool(((params - p0).abs() <= bound).all())
 
 
+def test_config4_size_with_buckets_that_are_not_powers_of_two():
+    # the cell-granular quantizer at the benchmark's size: sampled ranges against the oracle (ranges start on
+    # bucket boundaries), every scale against the bucket maxima, and the server step on the same ranges
+    n, W, lr = 100_000_000, 2, 0.1
+    grads = [workloads.config4_grad(w, n, DEV) for w in range(W)]
+    for bucket in (96, 1504, 2752):
+        span = bucket * (16384 // bucket)
+        for bits in (1, 4, 7):
+            params = workloads.uniform(n, -0.05, 0.05, 1, DEV)
+            p0 = params.clone()
+            outs = [mqgrad.mqg_quantize(grads[w], bits, bucket, seed=99, iteration=bits, worker=w) for w in range(W)]
+            mqgrad.mqg_aggregate_update([o[0] for o in outs], [o[1] for o in outs], n, bits, bucket, lr, params)
+            torch.cuda.synchronize()
+            starts = sample_starts(n, span, 3, seed=bits + bucket)
+            check_quantize_ranges(grads[1], outs[1][0], outs[1][1], bits, bucket, 99, bits, 1, starts, span)
+            for lo in starts[:1] + starts[-1:]:
+                hi = min(n, lo + span)
+                want = [ref.quantize(grads[w][lo:hi].cpu().numpy(), bits, bucket, 99, bits, w, lo) for w in range(W)]
+                p_ref = ref.aggregate_update([x[0] for x in want], [x[1] for x in want], hi - lo, bits, bucket, lr,
+                                             p0[lo:hi].cpu().numpy())
+                assert ulp_distance(params[lo:hi].cpu().numpy(), p_ref).max() == 0, "b=%d B=%d range %d" % (bits, bucket, lo)
+            nb = mqgrad.mqg_num_buckets(n, bucket)
+            full = (n // bucket) * bucket
+            smax = grads[0][:full].abs().view(-1, bucket).amax(dim=1)
+            assert torch.equal(outs[0][1][: n // bucket], smax), "B=%d b=%d" % (bucket, bits)
+            if full < n:
+                assert outs[0][1][nb - 1] == grads[0][full:].abs().max()
+            del outs
+
+
 def test_config4_exchange_and_minmax_on_sampled_ranges():
     # the widened rows at the benchmark's full size and launch configuration: the re-quantized mean, the
     # worker's update from it, and the deterministic [min, max] encoding with its server step
