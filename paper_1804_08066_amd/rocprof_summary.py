@@ -43,12 +43,17 @@ def short(name):
     return None
 
 
+_measured_at = None   # --measured-at: the commit the measurement ran on, when the summary is written later
+
+
 def commit():
+    if _measured_at:
+        return _measured_at
     try:
         root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
         h = subprocess.run(["git", "rev-parse", "--short", "HEAD"], cwd=root, capture_output=True, text=True).stdout.strip()
-        dirty = subprocess.run(["git", "status", "--porcelain", "--untracked-files=no"], cwd=root, capture_output=True,
-                               text=True).stdout.strip()
+        dirty = subprocess.run(["git", "status", "--porcelain", "--untracked-files=no", "--", ".", ":!profiles"], cwd=root,
+                               capture_output=True, text=True).stdout.strip()   # the summaries themselves do not count
         return h + ("+changes" if dirty else "")
     except OSError:
         return "unknown"
@@ -251,6 +256,8 @@ def main():
         p.add_argument("--cmd", action="append", required=True, help="command that produced the input (repeatable)")
         p.add_argument("--out", required=True)
         p.add_argument("--note", action="append")
+        p.add_argument("--measured-at", help="commit the measurement ran on (default: the work tree's HEAD, "
+                                             "'+changes' if tracked files other than the summaries differ from it)")
 
     p = sub.add_parser("stats"); common(p)
     p.add_argument("--csv", required=True); p.add_argument("--bench-json")
@@ -266,6 +273,8 @@ def main():
     p = sub.add_parser("transient"); common(p); p.add_argument("--bench-json", required=True)
     p = sub.add_parser("machine"); common(p); p.add_argument("--bench-json", required=True)
     a = ap.parse_args()
+    global _measured_at
+    _measured_at = a.measured_at
     {"stats": cmd_stats, "sweep": cmd_sweep, "traffic": cmd_traffic, "counters": cmd_counters,
      "transient": cmd_transient, "machine": cmd_machine}[a.sub](a)
 
