@@ -158,6 +158,32 @@ def condition(wl, bits, bucket, lr, ms):
     return done, (time.perf_counter() - t0) * 1e3
 
 
+def time_cold_codes(wl, bits, bucket, lr, steps=20, warmup=5):
+    """The server step when the code words are NOT in this GPU's caches -- the state on a real parameter
+    server, where the W streams arrive over the network: each step quantizes as usual, then copies two
+    gradient buffers (torch copy_, ordinary loads and stores: 1.6 GB through the caches, untimed) and only
+    then times mqg_aggregate_update."""
+    import torch
+    from paper_1804_08066_amd import mqgrad
+    outs = wl.outputs(bits, bucket)
+    pk, sc = [o[0] for o in outs], [o[1] for o in outs]
+    dst = torch.empty_like(wl.grads[0])
+    ev = []
+    for k in range(warmup + steps):
+        for w in range(wl.W):
+            mqgrad.mqg_quantize(wl.grads[w], bits, bucket, seed=1234, iteration=k, worker=w, packed_out=pk[w], scales_out=sc[w])
+        for f in range(2):
+            dst.copy_(wl.grads[f % wl.W])
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        mqgrad.mqg_aggregate_update(pk, sc, wl.n, bits, bucket, lr, wl.params)
+        e[1].record()
+        if k >= warmup:
+            ev.append(e)
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+
+
 _bench_lib = None
 
 
@@ -716,6 +742,9 @@ def main():
          ceil["torch_copy"]["gbs"], 100 * ceil["torch_copy"]["frac_of_peak"], ceil["pure_read"]["gbs"], ceil["pure_write"]["gbs"],
          ceil["additive_bound"]["quantize_us"], ceil["additive_bound"]["update_us"]))
 
+    a_cold_ms = time_cold_codes(wl, bits, bucket, args.lr)
+    log("aggregate_update with the code words out of cache (two 400 MB copies in between): %.1f us (%.1f%%)" %
+        (a_cold_ms * 1e3, 100 * ab / (a_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS))
     traffic = measured_traffic(n, W, bits, bucket)
     q_traffic = traffic["quantize_wave_kernel"] if traffic else None
     a_traffic = traffic["aggregate_update_rows_kernel"] if traffic else None
@@ -741,7 +770,12 @@ def main():
                                "algorithmic_bytes_per_launch": ab, "avg_launch_us": a_ms * 1e3,
                                "median_launch_us": spread["aggregate_us_median"], "min_launch_us": spread["aggregate_us_min"],
                                "first5_launch_us": spread["aggregate_us_first5"],
-                               "frac_of_stream_ceiling": a_gbs / ceil["update_mix"]["gbs"]},
+                               "frac_of_stream_ceiling": a_gbs / ceil["update_mix"]["gbs"],
+                               "codes_out_of_cache": {"what": "the same launch after two 400 MB device copies, so that no "
+                                                              "code word is left in this GPU's caches (the state on a parameter "
+                                                              "server whose streams arrive over the network)",
+                                                      "avg_launch_us": a_cold_ms * 1e3,
+                                                      "frac": ab / (a_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}},
         "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "conditioning": conditioning,
         "cold": cold,
