@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("bucket", [96, 512, 2048, 8192, 16384])
+@pytest.mark.parametrize("bucket", [96, 512, 1184, 1376, 1760, 2048, 8192, 16384])
 def test_batched_quantize_equals_per_tensor_and_oracle(bucket):
     sizes = [n for _, n in workloads.SMALL_CNN_SHAPES] + [0, 1, 40000 + 3]
     bases, run = [], 0
@@ -130,7 +130,7 @@ def test_batch_limits_are_reported():
 MINMAX_SIZES = [n for _, n in workloads.SMALL_CNN_SHAPES] + [0, 1, 40000 + 3, 3 * 16384 + 4096 + 37]
 
 
-@pytest.mark.parametrize("bucket", [96, 512, 2048, 8192, 16384, 0])
+@pytest.mark.parametrize("bucket", [96, 512, 2048, 4096, 6144, 8192, 12288, 16384, 0])
 def test_batched_minmax_encode_equals_the_oracle_per_layer(bucket):
     # bucket 0: one range per layer, as the paper encodes (the oracle with one bucket that covers the layer)
     grads = [workloads.normal_with_outliers(n, 0.01, 1e-3, 25.0, 90 + i, DEV) + 1e-3 * i if n else torch.empty(0, device=DEV)
@@ -148,7 +148,7 @@ def test_batched_minmax_encode_equals_the_oracle_per_layer(bucket):
 
 
 @pytest.mark.parametrize("bucket", [160, 1024, 0])
-@pytest.mark.parametrize("bits", [2, 5, 8])
+@pytest.mark.parametrize("bits", [2, 3, 5, 8])
 def test_batched_minmax_server_step_with_raw_small_layers(bits, bucket):
     # the paper's selective quantization with the footnote's encoder: large layers encoded, small ones raw;
     # one encode call per worker and one update launch
