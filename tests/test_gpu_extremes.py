@@ -25,7 +25,7 @@ def magnitudes(n, seed):
 
 
 @pytest.mark.parametrize("bits", [1, 2, 5, 8])
-@pytest.mark.parametrize("bucket", [64, 256, 4096])
+@pytest.mark.parametrize("bucket", [64, 96, 256, 1504, 4096])
 def test_extreme_magnitudes_match_the_oracle(bits, bucket):
     n = 40 * 256 + 19
     grads = [magnitudes(n, 3 + w) for w in range(3)]
@@ -66,13 +66,14 @@ def test_scale_threshold_buckets():
     # buckets whose maximum sits just below, at and just above 2^-96, and all-zero / all-negative-zero ones
     vals = [2.0 ** -97, np.nextafter(np.float32(2.0 ** -96), np.float32(0)), 2.0 ** -96,
             np.nextafter(np.float32(2.0 ** -96), np.float32(1)), 0.0, -0.0, 2.0 ** -140]
-    g = torch.zeros(len(vals) * 64, device=DEV)
-    for i, v in enumerate(vals):
-        g[i * 64 + 7] = float(v)
-        g[i * 64 + 9] = -float(v) / 2
-    for bits in (1, 4, 8):
-        pk, sc = mqgrad.mqg_quantize(g, bits, 64, seed=5)
-        torch.cuda.synchronize()
-        want_pk, want_sc = ref.quantize(g.cpu().numpy(), bits, 64, 5)
-        assert sc.cpu().numpy().tobytes() == want_sc.tobytes()
-        assert np.array_equal(to_u32(pk), want_pk)
+    for bucket in (64, 96):   # the wave-local kernel and the cell-granular one
+        g = torch.zeros(len(vals) * bucket, device=DEV)
+        for i, v in enumerate(vals):
+            g[i * bucket + 7] = float(v)
+            g[i * bucket + 9] = -float(v) / 2
+        for bits in (1, 4, 8):
+            pk, sc = mqgrad.mqg_quantize(g, bits, bucket, seed=5)
+            torch.cuda.synchronize()
+            want_pk, want_sc = ref.quantize(g.cpu().numpy(), bits, bucket, 5)
+            assert sc.cpu().numpy().tobytes() == want_sc.tobytes()
+            assert np.array_equal(to_u32(pk), want_pk)
