@@ -366,8 +366,13 @@ struct ChunkShape {
     uint32_t seg_lanes;    // lanes of a row that share a bucket
     uint32_t rpb;          // rows per bucket
     uint64_t kb_first;     // global index of the chunk's first bucket
-    uint32_t slot[R];      // bucket (chunk-local) of row j's quad
 };
+// bucket (chunk-local) of row j's quad
+template <int R, int WPB>
+__device__ __forceinline__ void chunk_slots(const QuantizeArgs& a, uint32_t lane, uint32_t (&slot)[R]) {
+#pragma unroll
+    for (int j = 0; j < R; ++j) slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + lane)) >> (uint32_t)a.bucket_shift);
+}
 template <int R, int WPB, int NW>
 __device__ __forceinline__ ChunkShape<R> chunk_shape(const QuantizeArgs& a, const uint64_t block) {
     constexpr uint32_t CH = 256u * R;
@@ -386,8 +391,6 @@ __device__ __forceinline__ ChunkShape<R> chunk_shape(const QuantizeArgs& a, cons
     c.seg_lanes = (WPB > 1 || shift >= 8u) ? 64u : (1u << (shift - 2u));
     c.rpb = WPB > 1 ? (uint32_t)R : (shift >= 8u ? (1u << (shift - 8u)) : 1u);
     c.kb_first = WPB > 1 ? (c.chunk / WPB) : (c.cb >> shift);
-#pragma unroll
-    for (int j = 0; j < R; ++j) c.slot[j] = WPB > 1 ? 0u : ((4u * (j * 64u + c.lane)) >> shift);
     return c;
 }
 
@@ -399,6 +402,8 @@ template <int R, int WPB, int NW, bool HOIST>
 __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const uint64_t block, WaveShared<R, NW>& sm) {
     const ChunkShape<R> c = chunk_shape<R, WPB, NW>(a, block);
     const uint32_t lane = c.lane, wave = c.wave;
+    uint32_t slot[R];
+    chunk_slots<R, WPB>(a, lane, slot);
 
     float4 x[R];
     if (c.full) {
@@ -415,15 +420,15 @@ __device__ __forceinline__ void quantize_wave_block(const QuantizeArgs& a, const
         for (int jp = 0; jp < R; jp += 2) draw_pair(a, c.cb, lane, jp, draws.o[jp / 2]);
     }
     if (a.scales_in == nullptr) {
-        reduce_ranges<R, WPB, NW>(x, lane, wave, c.slot, c.seg_lanes, c.rpb, sm, a.scale_mode == MQG_SCALE_L2);
+        reduce_ranges<R, WPB, NW>(x, lane, wave, slot, c.seg_lanes, c.rpb, sm, a.scale_mode == MQG_SCALE_L2);
     }
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
     if (!c.active) return;
     const Draws<R>* drawn = HOIST ? &draws : nullptr;
     if (c.full) {
-        quantize_and_pack<R, WPB, NW, true>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, true>(a, c.cb, c.count, lane, wave, slot, c.nbc, c.kb_first, x, sm, 1.0f, drawn);
     } else {
-        quantize_and_pack<R, WPB, NW, false>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, 1.0f, drawn);
+        quantize_and_pack<R, WPB, NW, false>(a, c.cb, c.count, lane, wave, slot, c.nbc, c.kb_first, x, sm, 1.0f, drawn);
     }
 }
 
@@ -939,6 +944,8 @@ __device__ __forceinline__ void quantize_minmax_wave_block(const QuantizeArgs& a
                                                            WaveLows<R, NW>& lw) {
     const ChunkShape<R> c = chunk_shape<R, WPB, NW>(a, block);
     const uint32_t lane = c.lane, wave = c.wave;
+    uint32_t slot[R];
+    chunk_slots<R, WPB>(a, lane, slot);
 
     float4 x[R];
     if (c.full) {
@@ -949,17 +956,17 @@ __device__ __forceinline__ void quantize_minmax_wave_block(const QuantizeArgs& a
     clear_words<R, NW>(lane, wave, sm);   // while the loads are in flight
     if (a.scales_in == nullptr) {
         if (c.full) {
-            reduce_minmax<R, WPB, NW, true>(x, c.count, lane, wave, c.slot, c.seg_lanes, c.rpb, sm, lw);
+            reduce_minmax<R, WPB, NW, true>(x, c.count, lane, wave, slot, c.seg_lanes, c.rpb, sm, lw);
         } else {
-            reduce_minmax<R, WPB, NW, false>(x, c.count, lane, wave, c.slot, c.seg_lanes, c.rpb, sm, lw);
+            reduce_minmax<R, WPB, NW, false>(x, c.count, lane, wave, slot, c.seg_lanes, c.rpb, sm, lw);
         }
     }
     if (WPB > 1) __syncthreads();   // every wave of the group arrives here exactly once
     if (!c.active) return;
     if (c.full) {
-        encode_minmax_and_pack<R, WPB, NW, true>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, lw);
+        encode_minmax_and_pack<R, WPB, NW, true>(a, c.cb, c.count, lane, wave, slot, c.nbc, c.kb_first, x, sm, lw);
     } else {
-        encode_minmax_and_pack<R, WPB, NW, false>(a, c.cb, c.count, lane, wave, c.slot, c.nbc, c.kb_first, x, sm, lw);
+        encode_minmax_and_pack<R, WPB, NW, false>(a, c.cb, c.count, lane, wave, slot, c.nbc, c.kb_first, x, sm, lw);
     }
 }
 
