@@ -158,7 +158,7 @@ def condition(wl, bits, bucket, lr, ms):
     return done, (time.perf_counter() - t0) * 1e3
 
 
-def time_cold_codes(wl, bits, bucket, lr, steps=20, warmup=5):
+def time_cold_codes(wl, bits, bucket, lr, steps=20, warmup=5, origin=0):
     """The server step when the code words are NOT in this GPU's caches -- the state on a real parameter
     server, where the W streams arrive over the network: each step quantizes as usual, then copies two
     gradient buffers (torch copy_, ordinary loads and stores: 1.6 GB through the caches, untimed) and only
@@ -176,7 +176,7 @@ def time_cold_codes(wl, bits, bucket, lr, steps=20, warmup=5):
             dst.copy_(wl.grads[f % wl.W])
         e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         e[0].record()
-        mqgrad.mqg_aggregate_update(pk, sc, wl.n, bits, bucket, lr, wl.params)
+        mqgrad.mqg_aggregate_update(pk, sc, wl.n, bits, bucket, lr, wl.params, origin=origin)
         e[1].record()
         if k >= warmup:
             ev.append(e)
@@ -743,8 +743,10 @@ def main():
          ceil["additive_bound"]["quantize_us"], ceil["additive_bound"]["update_us"]))
 
     a_cold_ms = time_cold_codes(wl, bits, bucket, args.lr)
-    log("aggregate_update with the code words out of cache (two 400 MB copies in between): %.1f us (%.1f%%)" %
-        (a_cold_ms * 1e3, 100 * ab / (a_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+    a_cold_hint_ms = time_cold_codes(wl, bits, bucket, args.lr, origin=mqgrad.MQG_CODES_FROM_MEMORY)
+    log("aggregate_update with the code words out of cache (two 400 MB copies in between): %.1f us (%.1f%%); called with "
+        "MQG_CODES_FROM_MEMORY: %.1f us" %
+        (a_cold_ms * 1e3, 100 * ab / (a_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, a_cold_hint_ms * 1e3))
     traffic = measured_traffic(n, W, bits, bucket)
     q_traffic = traffic["quantize_wave_kernel"] if traffic else None
     a_traffic = traffic["aggregate_update_rows_kernel"] if traffic else None
@@ -775,7 +777,11 @@ def main():
                                                               "code word is left in this GPU's caches (the state on a parameter "
                                                               "server whose streams arrive over the network)",
                                                       "avg_launch_us": a_cold_ms * 1e3,
-                                                      "frac": ab / (a_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}},
+                                                      "frac": ab / (a_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                                      "avg_launch_us_told_so": a_cold_hint_ms * 1e3,
+                                                      "frac_told_so": ab / (a_cold_hint_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                                      "told_so": "mqg_aggregate_update_from(..., MQG_CODES_FROM_MEMORY): "
+                                                                 "streaming loads of the code words at every width"}},
         "hbm_frac_end_to_end": (W * qb + ab) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "conditioning": conditioning,
         "cold": cold,

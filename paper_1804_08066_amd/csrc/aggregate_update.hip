@@ -299,21 +299,28 @@ hipError_t launch_rows(const AggregateArgs& a, hipStream_t stream) {
     // Up to 3 bits the step is bound by vector-ALU issue once there are more than eight workers; there the
     // codes are decoded through the multiplier table in LDS (measured at 100 M parameters, 16 workers: 181,
     // 222, 271 us against 199, 246, 280 us; with eight workers the direct forms are 1-3 % faster).
+    // streaming loads of the code words: by the width, or because the caller says they come from memory
+    const bool once_now = decode::codes_read_once(a.bits) || a.stream_codes != 0u;
     if (a.W > 8u && a.bits <= 3u) {
-        if (a.bits == 1u) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, 0, false, 1>), grid, block, 0, stream, a);
-        if (a.bits == 2u) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, 0, false, 2>), grid, block, 0, stream, a);
-        if (a.bits == 3u) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, true, false, 0, false, 3>), grid, block, 0, stream, a);
+        with_once(once_now, [&](auto once) {
+            constexpr bool ONCE = decltype(once)::value;
+            if (a.bits == 1u) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, ONCE, 0, false, 1>), grid, block, 0, stream, a);
+            if (a.bits == 2u) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, ONCE, 0, false, 2>), grid, block, 0, stream, a);
+            if (a.bits == 3u) hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, true, ONCE, 0, false, 3>), grid, block, 0, stream, a);
+        });
         return hipGetLastError();
     }
     if (a.bits == 1u || a.bits == 8u) {   // three-operation decodes; neither width straddles words
         if (a.bits == 1u) {
-            hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, false, 1>), grid, block, 0, stream, a);
+            with_once(once_now, [&](auto once) {
+                hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, decltype(once)::value, 1>), grid, block, 0, stream, a);
+            });
         } else {
             hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, false, true, 8>), grid, block, 0, stream, a);
         }
         return hipGetLastError();
     }
-    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+    with_once(once_now, [&](auto once) {
         hipLaunchKernelGGL((aggregate_update_rows_kernel<R, NBR, STRADDLE, decltype(once)::value, 0>),
                            grid, block, 0, stream, a);
     });
@@ -326,7 +333,7 @@ hipError_t launch_lds(const AggregateArgs& a, hipStream_t stream) {
     if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid((uint32_t)tiles), block(kThreads);
     const size_t lds = sizeof(float) * a.W * kMaxBuckets;
-    with_once(decode::codes_read_once(a.bits), [&](auto once) {
+    with_once(decode::codes_read_once(a.bits) || a.stream_codes != 0u, [&](auto once) {
         hipLaunchKernelGGL((aggregate_update_lds_kernel<STRADDLE, decltype(once)::value>),
                            grid, block, lds, stream, a);
     });

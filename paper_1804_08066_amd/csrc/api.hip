@@ -198,6 +198,13 @@ mqg_status mqg_quantize_with_scales(const float* grad, uint64_t n, uint32_t bits
 mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* const* scales, uint32_t W,
                                 uint64_t n, uint32_t bits, uint32_t bucket,
                                 float lr, float* params, void* stream) {
+    return mqg_aggregate_update_from(packed, scales, W, n, bits, bucket, lr, params, MQG_CODES_MAY_BE_CACHED, stream);
+}
+
+mqg_status mqg_aggregate_update_from(const uint32_t* const* packed, const float* const* scales, uint32_t W,
+                                     uint64_t n, uint32_t bits, uint32_t bucket,
+                                     float lr, float* params, mqg_codes_origin origin, void* stream) {
+    if (origin != MQG_CODES_MAY_BE_CACHED && origin != MQG_CODES_FROM_MEMORY) return MQG_EINVAL;
     if (!valid_common(bits, bucket)) return MQG_EINVAL;
     if (W < 1u || W > MQG_MAX_WORKERS) return MQG_EINVAL;
     if (n == 0) return MQG_OK;
@@ -205,6 +212,7 @@ mqg_status mqg_aggregate_update(const uint32_t* const* packed, const float* cons
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(params)) return MQG_EALIGN;
     mqg::AggregateArgs a;
+    a.stream_codes = origin == MQG_CODES_FROM_MEMORY ? 1u : 0u;
     const mqg_status tables = worker_tables(packed, scales, W, false, a.packed, a.scales);
     if (tables != MQG_OK) return tables;
     a.W = W;
@@ -229,6 +237,7 @@ mqg_status mqg_aggregate_mean(const uint32_t* const* packed, const float* const*
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(mean_out)) return MQG_EALIGN;
     mqg::AggregateArgs a;
+    a.stream_codes = 0u;
     const mqg_status tables = worker_tables(packed, scales, W, false, a.packed, a.scales);
     if (tables != MQG_OK) return tables;
     a.W = W;
@@ -447,6 +456,7 @@ mqg_status mqg_aggregate_update_minmax(const uint32_t* const* packed, const floa
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(params)) return MQG_EALIGN;
     mqg::AggregateArgs a;
+    a.stream_codes = 0u;
     const mqg_status tables = worker_tables(packed, ranges, W, true, a.packed, a.scales);
     if (tables != MQG_OK) return tables;
     a.W = W;
@@ -525,6 +535,7 @@ mqg_status mqg_aggregate_update_minmax_tensor(const uint32_t* const* packed, con
     if (n > (UINT64_MAX >> 4)) return MQG_EINVAL;
     if (misaligned4(params)) return MQG_EALIGN;
     mqg::AggregateArgs a;
+    a.stream_codes = 0u;
     const mqg_status tables = worker_tables(packed, ranges, W, true, a.packed, a.scales);
     if (tables != MQG_OK) return tables;
     a.W = W;

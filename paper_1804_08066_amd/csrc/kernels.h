@@ -34,6 +34,7 @@ struct AggregateArgs {
     float neg_c;             // -(lr / W)
     float* params;
     uint32_t per_tensor;     // [min, max] encoding only: every worker has ONE (min, max) pair for the whole tensor
+    uint32_t stream_codes;   // the code words are not in this GPU's caches: streaming loads at every width
 };
 
 // Server side of the full exchange: quantize the sum over W workers' de-quantized gradients

@@ -13,6 +13,7 @@ from . import build as _build
 
 MQG_OK, MQG_EINVAL, MQG_EALIGN, MQG_ELAUNCH = 0, -1, -2, -3
 MQG_SCALE_MAXABS, MQG_SCALE_L2 = 0, 1
+MQG_CODES_MAY_BE_CACHED, MQG_CODES_FROM_MEMORY = 0, 1
 MQG_MAX_WORKERS = 64
 
 EXPORTS = [
@@ -27,6 +28,7 @@ EXPORTS = [
     "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
     "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch", "mqg_sum_squares_batch_static",
     "mqg_quantize_minmax_tensors", "mqg_aggregate_update_minmax_tensors", "mqg_aggregate_requantize_mode",
+    "mqg_aggregate_update_from",
 ]
 
 
@@ -97,6 +99,8 @@ def lib():
     L.mqg_quantize_with_scales.restype = C.c_int
     L.mqg_aggregate_update.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, vp]
     L.mqg_aggregate_update.restype = C.c_int
+    L.mqg_aggregate_update_from.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, f32, vp, C.c_int, vp]
+    L.mqg_aggregate_update_from.restype = C.c_int
     L.mqg_aggregate_requantize.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp]
     L.mqg_aggregate_requantize.restype = C.c_int
     L.mqg_aggregate_requantize_mode.argtypes = [C.POINTER(vp), C.POINTER(vp), u32, u64, u32, u32, C.c_int, u64, u32, u32, u64, vp, vp, vp]
@@ -235,8 +239,10 @@ def mqg_quantize(grad, bits, bucket, seed, iteration=0, worker=0, elem_base=0,
     return packed_out, scales_out
 
 
-def mqg_aggregate_update(packed, scales, n, bits, bucket, lr, params, stream=None):
-    """Server side.  packed / scales: lists of W CUDA tensors; params: fp32 CUDA tensor, updated in place."""
+def mqg_aggregate_update(packed, scales, n, bits, bucket, lr, params, stream=None, origin=MQG_CODES_MAY_BE_CACHED):
+    """Server side.  packed / scales: lists of W CUDA tensors; params: fp32 CUDA tensor, updated in place.
+    origin: MQG_CODES_FROM_MEMORY when the streams were not written by this GPU just before (same results,
+    streaming loads of the code words at every width)."""
     W = len(packed)
     if W != len(scales):
         raise ValueError("packed and scales must have one entry per worker")
@@ -250,7 +256,7 @@ def mqg_aggregate_update(packed, scales, n, bits, bucket, lr, params, stream=Non
             raise ValueError("a worker's buffers are too small for n")
     pa = (C.c_void_p * max(W, 1))(*[p.data_ptr() for p in packed])
     sa = (C.c_void_p * max(W, 1))(*[s.data_ptr() for s in scales])
-    st = lib().mqg_aggregate_update(pa, sa, W, n, bits, bucket, lr, params.data_ptr(), _stream_handle(stream))
+    st = lib().mqg_aggregate_update_from(pa, sa, W, n, bits, bucket, lr, params.data_ptr(), int(origin), _stream_handle(stream))
     if st != MQG_OK:
         raise MqgError(st, "mqg_aggregate_update")
     return params

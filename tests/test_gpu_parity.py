@@ -246,3 +246,25 @@ def test_l2_scale_mode(bucket):
         pk_i, sc_i = gpu_quantize(g, bits, bucket, 9, 1, 2, 0, scales_in=s_in)
         pk_o, _ = ref.quantize(gh, bits, bucket, 9, 1, 2, 0, scale_mode=ref.SCALE_L2)
         assert np.array_equal(sc_i, sc_o) and np.array_equal(pk_i, pk_o)
+
+
+@pytest.mark.parametrize("W,bucket", [(3, 1024), (16, 1024), (5, 128), (9, 96)])
+def test_code_origin_hint_changes_no_result(W, bucket):
+    # streaming loads of the code words at every width (MQG_CODES_FROM_MEMORY): the wave-local kernel with
+    # one and two buckets per row, its table decode with many workers, and the LDS-table kernel
+    n = 2 * 16384 + 2048 + 13
+    grads = [workloads.laplace(n, 2e-3, 50 + w, DEV) for w in range(W)]
+    for bits in ALL_BITS:
+        q = [mqgrad.mqg_quantize(g, bits, bucket, seed=8, iteration=2, worker=w) for w, g in enumerate(grads)]
+        a = workloads.uniform(n, -0.05, 0.05, 3, DEV)
+        b = a.clone()
+        p0 = a.cpu().numpy().copy()
+        mqgrad.mqg_aggregate_update([x[0] for x in q], [x[1] for x in q], n, bits, bucket, 0.1, a)
+        mqgrad.mqg_aggregate_update([x[0] for x in q], [x[1] for x in q], n, bits, bucket, 0.1, b,
+                                    origin=mqgrad.MQG_CODES_FROM_MEMORY)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), "b=%d" % bits
+        want = ref.aggregate_update([to_u32(x[0]) for x in q], [x[1].cpu().numpy() for x in q], n, bits, bucket, 0.1, p0)
+        assert ulp_distance(b.cpu().numpy(), want).max() == 0
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_aggregate_update([q[0][0]], [q[0][1]], n, 8, bucket, 0.1, a, origin=7)
