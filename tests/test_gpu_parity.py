@@ -248,7 +248,7 @@ def test_l2_scale_mode(bucket):
         assert np.array_equal(sc_i, sc_o) and np.array_equal(pk_i, pk_o)
 
 
-@pytest.mark.parametrize("W,bucket", [(3, 1024), (16, 1024), (5, 128), (9, 96)])
+@pytest.mark.parametrize("W,bucket", [(3, 1024), (16, 1024), (5, 128), (12, 128), (9, 96)])
 def test_code_origin_hint_changes_no_result(W, bucket):
     # streaming loads of the code words at every width (MQG_CODES_FROM_MEMORY): the wave-local kernel with
     # one and two buckets per row, its table decode with many workers, and the LDS-table kernel
