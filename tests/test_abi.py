@@ -196,3 +196,18 @@ def test_adaptive_rule_matches_the_oracle_rule():
         mqgrad.mqg_adaptive_bits([0.1], norm_per_bit=0.0)
     with pytest.raises(mqgrad.MqgError):
         mqgrad.mqg_adaptive_bits([0.1], bits_min=5, bits_max=4)
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must stand alone under a C compiler, warnings as errors
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "mqgrad.h"\nint main(void) { return (int)mqg_packed_words(0, 1) + (int)MQG_CODES_FROM_MEMORY * 0; }\n')
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                        "-c", str(src), "-o", str(tmp_path / "use_header.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
