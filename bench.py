@@ -74,6 +74,8 @@ def aggregate_bytes(n, bits, bucket, W):
 
 
 class Workload:
+    dest = None   # mqg_quantize's cache policy for the code words (None: the library's default, keep cached)
+
     def __init__(self, n, W, device, buffers=0):
         """W workers over `buffers` distinct gradient buffers (0: one per worker); worker w reads buffer
         w % buffers -- for shapes whose W full-size gradients would not fit beside the code streams."""
@@ -110,7 +112,7 @@ def run_steps(wl, bits, bucket, lr, steps, iteration0, events=None):
             ev[0].record()
         for w in range(wl.W):
             mqgrad.mqg_quantize(wl.grads[w], bits, bucket, seed=1234, iteration=iteration0 + k, worker=w,
-                                packed_out=pk[w], scales_out=sc[w])
+                                packed_out=pk[w], scales_out=sc[w], dest=wl.dest)
         if events is not None:
             ev[1].record()
         mqgrad.mqg_aggregate_update(pk, sc, wl.n, bits, bucket, lr, wl.params)
@@ -141,6 +143,27 @@ def time_config(wl, bits, bucket, lr, steps, warmup):
                         "aggregate_us_median": a_all[steps // 2] * 1e3, "aggregate_us_min": a_all[0] * 1e3,
                         "aggregate_us_first5": sum(a_series[:head]) / head * 1e3}
     return (t1 - t0) / steps * 1e3, q_ms, a_ms
+
+
+def choose_code_stores(wl, bits, bucket, lr, policy):
+    """The quantizer's cache policy for the code words (mqg_quantize_to): kept in the last-level cache for the
+    update that follows, or streamed to memory.  Which is faster depends on how the W streams together sit
+    in that cache; a caller knows W, the library does not, so the caller chooses: here, under "auto", by
+    timing a few untimed steps each way (streaming stores must win by more than 1 % to be taken).  Sets
+    wl.dest and returns what was decided."""
+    from paper_1804_08066_amd import mqgrad
+    stores = {"policy": policy}
+    if policy == "auto":
+        probe = {}
+        for name, dest in (("cached", None), ("stream", mqgrad.MQG_CODES_TO_MEMORY)):
+            wl.dest = dest
+            probe[name] = time_config(wl, bits, bucket, lr, 10, 5)[0]
+        stores["probe_ms_per_step"] = probe
+        stores["chosen"] = "stream" if probe["stream"] < 0.99 * probe["cached"] else "cached"
+    else:
+        stores["chosen"] = policy
+    wl.dest = mqgrad.MQG_CODES_TO_MEMORY if stores["chosen"] == "stream" else None
+    return stores
 
 
 def condition(wl, bits, bucket, lr, ms):
@@ -669,6 +692,9 @@ def main():
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--bucket", type=int, default=1024)
     ap.add_argument("--lr", type=float, default=0.1)
+    ap.add_argument("--code-stores", choices=("auto", "cached", "stream"), default="auto",
+                    help="cache policy of the quantizer's code words: kept for the update that follows, streamed to "
+                         "memory, or whichever a short untimed probe finds faster (the cold region always runs 'cached')")
     ap.add_argument("--sweep", action="store_true", help="also time every (b, bucket) of the sweep")
     ap.add_argument("--exchange", action="store_true",
                     help="also time the paper's full exchange: server re-quantizes the mean, worker de-quantizes and updates")
@@ -727,6 +753,8 @@ def main():
         conditioning = {"ms": took, "steps": done,
                         "what": "untimed steps of the same loop between the cold region and the counted warm-up: after an "
                                 "idle gap the chip passes through a throttled state for about 20 ms (profiles/transient_*.md)"}
+    stores = choose_code_stores(wl, bits, bucket, args.lr, args.code_stores)
+    log("code stores: %s" % json.dumps(stores))
     ms_step, q_ms, a_ms = time_config(wl, bits, bucket, args.lr, args.steps, args.warmup)
     value = 4.0 * n * W / (ms_step * 1e-3) / 1e9
     q_gbs, a_gbs = qb / (q_ms * 1e-3) / 1e9, ab / (a_ms * 1e-3) / 1e9
@@ -758,7 +786,7 @@ def main():
         "config": {"workload": "bandwidth sweep point: flat fp32 gradient of %d elements ~ N(0, 0.01^2), "
                                "W=%d worker buffers, b=%d, bucket=%d; one step = %d x quantize + 1 x aggregate_update"
                                % (n, W, bits, bucket, W),
-                   "n": n, "workers": W, "bits": bits, "bucket": bucket},
+                   "n": n, "workers": W, "bits": bits, "bucket": bucket, "code_stores": stores},
         # the quantize kernel runs W times per step and is the dominant kernel by time
         "roofline": {"bound": "hbm", "kernel": "quantize_wave_kernel", "achieved": q_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": q_gbs / HBM_PEAK_GBS, "traffic": q_traffic,
@@ -795,14 +823,16 @@ def main():
         rows = []
         for bk in (128, 1024, 8192):
             for b in (1, 2, 4, 8):
+                point_stores = choose_code_stores(wl, b, bk, args.lr, args.code_stores)
                 ms, q, a = time_config(wl, b, bk, args.lr, max(5, args.steps // 4), max(2, args.warmup // 4))
-                rows.append({"bits": b, "bucket": bk, "ms_per_step": ms,
+                rows.append({"bits": b, "bucket": bk, "ms_per_step": ms, "code_stores": point_stores["chosen"],
                              "grad_gbs": 4.0 * n * W / (ms * 1e-3) / 1e9,
                              "quantize_us": q * 1e3, "quantize_hbm_frac": quantize_bytes(n, b, bk) / (q * 1e-3) / 1e9 / HBM_PEAK_GBS,
                              "aggregate_us": a * 1e3, "aggregate_hbm_frac": aggregate_bytes(n, b, bk, W) / (a * 1e-3) / 1e9 / HBM_PEAK_GBS})
                 log("sweep b=%d B=%d: quantize %.1f us (%.1f%%), aggregate %.1f us (%.1f%%)" %
                     (b, bk, q * 1e3, 100 * rows[-1]["quantize_hbm_frac"], a * 1e3, 100 * rows[-1]["aggregate_hbm_frac"]))
         out["sweep"] = rows
+        choose_code_stores(wl, bits, bucket, args.lr, stores["chosen"])   # back to the headline's policy
 
     if args.exchange:
         out["exchange"] = time_exchange(wl, bits, bucket, args.lr, max(10, args.steps // 4), max(5, args.warmup // 4))

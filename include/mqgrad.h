@@ -91,6 +91,22 @@ mqg_status mqg_quantize(const float* grad, uint64_t n, uint32_t bits, uint32_t b
                         uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
                         uint32_t* packed_out, float* scales_out, void* stream);
 
+/* mqg_quantize with a statement about what happens to the code words next.  Results are identical; only
+ * the cache policy of the stores differs.  MQG_CODES_KEEP_CACHED (what mqg_quantize does): stores with
+ * agent scope -- written through to memory at once, the lines stay in the last-level cache, where a
+ * server step that follows on this GPU finds them (8 workers, 100 M elements, 4 bits: the update takes
+ * 181 us instead of 196, and the quantizer itself is 1-3 us faster).  MQG_CODES_TO_MEMORY: streaming
+ * stores, for streams that leave this GPU or that, together with the other workers' streams, exceed its
+ * caches before they are read (16 workers, 3 bits: the update takes 243 us instead of 276).
+ * MQG_EINVAL for any other value of `dest`; other arguments and errors as for mqg_quantize. */
+typedef enum {
+    MQG_CODES_KEEP_CACHED = 0,
+    MQG_CODES_TO_MEMORY = 1
+} mqg_codes_destination;
+mqg_status mqg_quantize_to(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                           uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                           uint32_t* packed_out, float* scales_out, mqg_codes_destination dest, void* stream);
+
 /* Same, with the bucket range taken as the L2 norm of the bucket when mode == MQG_SCALE_L2
  * (the norm scaling of the QSGD family the paper cites in Section 2).  mode == MQG_SCALE_MAXABS
  * is exactly mqg_quantize.  The sum of squares is accumulated in a fixed order (groups of four squares

@@ -23,7 +23,7 @@ bool misaligned8(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 7u) !
 mqg_status quantize_impl(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket, int mode,
                          uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
                          const float* scales_in, bool use_scales_in, uint32_t* packed_out,
-                         float* scales_out, void* stream) {
+                         float* scales_out, void* stream, bool stream_codes = false) {
     if (!valid_common(bits, bucket)) return MQG_EINVAL;
     if ((elem_base & 7u) != 0u) return MQG_EINVAL;
     if (mode != MQG_SCALE_MAXABS && mode != MQG_SCALE_L2) return MQG_EINVAL;
@@ -50,6 +50,7 @@ mqg_status quantize_impl(const float* grad, uint64_t n, uint32_t bits, uint32_t 
     a.scales_in = use_scales_in ? scales_in : nullptr;
     a.packed = packed_out;
     a.scales = scales_out;
+    a.stream_codes = stream_codes ? 1u : 0u;
     const hipError_t err = mqg::launch_quantize(a, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? MQG_OK : MQG_ELAUNCH;
 }
@@ -177,6 +178,14 @@ mqg_status mqg_quantize(const float* grad, uint64_t n, uint32_t bits, uint32_t b
                         uint32_t* packed_out, float* scales_out, void* stream) {
     return quantize_impl(grad, n, bits, bucket, MQG_SCALE_MAXABS, seed, iteration, worker, elem_base,
                          nullptr, false, packed_out, scales_out, stream);
+}
+
+mqg_status mqg_quantize_to(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,
+                           uint64_t seed, uint32_t iteration, uint32_t worker, uint64_t elem_base,
+                           uint32_t* packed_out, float* scales_out, mqg_codes_destination dest, void* stream) {
+    if (dest != MQG_CODES_KEEP_CACHED && dest != MQG_CODES_TO_MEMORY) return MQG_EINVAL;
+    return quantize_impl(grad, n, bits, bucket, MQG_SCALE_MAXABS, seed, iteration, worker, elem_base,
+                         nullptr, false, packed_out, scales_out, stream, dest == MQG_CODES_TO_MEMORY);
 }
 
 mqg_status mqg_quantize_mode(const float* grad, uint64_t n, uint32_t bits, uint32_t bucket,

@@ -21,6 +21,7 @@ struct QuantizeArgs {
                              // (min, max) pair that holds for the whole tensor)
     uint32_t* packed;        // ceil(n*bits/32) words
     float* scales;           // ceil(n/bucket) floats
+    uint32_t stream_codes = 0;   // 1: the code words are stored with the streaming hint instead of agent scope
 };
 
 struct AggregateArgs {

@@ -14,6 +14,7 @@ from . import build as _build
 MQG_OK, MQG_EINVAL, MQG_EALIGN, MQG_ELAUNCH = 0, -1, -2, -3
 MQG_SCALE_MAXABS, MQG_SCALE_L2 = 0, 1
 MQG_CODES_MAY_BE_CACHED, MQG_CODES_FROM_MEMORY = 0, 1
+MQG_CODES_KEEP_CACHED, MQG_CODES_TO_MEMORY = 0, 1
 MQG_MAX_WORKERS = 64
 
 EXPORTS = [
@@ -28,7 +29,7 @@ EXPORTS = [
     "mqg_mdp_num_weights", "mqg_mdp_get_weights", "mqg_mdp_set_weights", "mqg_mdp_q_values",
     "mqg_sum_squares_workspace_bytes", "mqg_sum_squares_batch", "mqg_sum_squares_batch_static",
     "mqg_quantize_minmax_tensors", "mqg_aggregate_update_minmax_tensors", "mqg_aggregate_requantize_mode",
-    "mqg_aggregate_update_from",
+    "mqg_aggregate_update_from", "mqg_quantize_to",
 ]
 
 
@@ -93,6 +94,8 @@ def lib():
     L.mqg_packed_words.restype = C.c_size_t
     L.mqg_quantize.argtypes = [vp, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp]
     L.mqg_quantize.restype = C.c_int
+    L.mqg_quantize_to.argtypes = [vp, u64, u32, u32, u64, u32, u32, u64, vp, vp, C.c_int, vp]
+    L.mqg_quantize_to.restype = C.c_int
     L.mqg_quantize_mode.argtypes = [vp, u64, u32, u32, C.c_int, u64, u32, u32, u64, vp, vp, vp]
     L.mqg_quantize_mode.restype = C.c_int
     L.mqg_quantize_with_scales.argtypes = [vp, u64, u32, u32, u64, u32, u32, u64, vp, vp, vp, vp]
@@ -205,10 +208,11 @@ def alloc_outputs(n, bits, bucket, device):
 
 
 def mqg_quantize(grad, bits, bucket, seed, iteration=0, worker=0, elem_base=0,
-                 packed_out=None, scales_out=None, stream=None, mode=None, scales_in=None):
+                 packed_out=None, scales_out=None, stream=None, mode=None, scales_in=None, dest=None):
     """Worker side.  grad: fp32 CUDA tensor.  Returns (packed int32[words], scales fp32[nb]).
 
-    mode selects mqg_quantize_mode; scales_in selects mqg_quantize_with_scales."""
+    mode selects mqg_quantize_mode; scales_in selects mqg_quantize_with_scales; dest (MQG_CODES_KEEP_CACHED /
+    MQG_CODES_TO_MEMORY) selects mqg_quantize_to."""
     _check(grad, torch.float32, "grad")
     n = grad.numel()
     if packed_out is None or scales_out is None:
@@ -231,6 +235,9 @@ def mqg_quantize(grad, bits, bucket, seed, iteration=0, worker=0, elem_base=0,
     elif mode is not None:
         st = L.mqg_quantize_mode(grad.data_ptr(), n, bits, bucket, int(mode), seed, iteration, worker,
                                  elem_base, packed_out.data_ptr(), scales_out.data_ptr(), sh)
+    elif dest is not None:
+        st = L.mqg_quantize_to(grad.data_ptr(), n, bits, bucket, seed, iteration, worker, elem_base,
+                               packed_out.data_ptr(), scales_out.data_ptr(), int(dest), sh)
     else:
         st = L.mqg_quantize(grad.data_ptr(), n, bits, bucket, seed, iteration, worker, elem_base,
                             packed_out.data_ptr(), scales_out.data_ptr(), sh)

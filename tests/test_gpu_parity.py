@@ -268,3 +268,22 @@ def test_code_origin_hint_changes_no_result(W, bucket):
         assert ulp_distance(b.cpu().numpy(), want).max() == 0
     with pytest.raises(mqgrad.MqgError):
         mqgrad.mqg_aggregate_update([q[0][0]], [q[0][1]], n, 8, bucket, 0.1, a, origin=7)
+
+
+@pytest.mark.parametrize("bucket", [128, 1024, 4096, 16384, 96, 1504])
+def test_code_destination_hint_changes_no_result(bucket):
+    # streaming stores of the code words (MQG_CODES_TO_MEMORY): every shape of the wave-local quantizer and the
+    # cell-granular one, whole chunks and a ragged tail, an unaligned output view
+    n = 3 * 16384 + 4096 + 37
+    g = workloads.normal_with_outliers(n, 1e-2, 1e-2, 30.0, 17, DEV)
+    for bits in (1, 3, 4, 8):
+        pk_o, sc_o = ref.quantize(g.cpu().numpy(), bits, bucket, 4, 1, 2, 64)
+        store = torch.full((mqgrad.mqg_packed_words(n, bits) + 5,), -1, dtype=torch.int32, device=DEV)
+        for view in (store[:-5], store[1:-4]):
+            store.fill_(-1)
+            pk, sc = mqgrad.mqg_quantize(g, bits, bucket, 4, 1, 2, 64, packed_out=view, dest=mqgrad.MQG_CODES_TO_MEMORY)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_u32(pk[:pk_o.size]), pk_o) and np.array_equal(sc.cpu().numpy(), sc_o), "b=%d" % bits
+        assert store[0].item() == -1 and bool((store[pk_o.size + 1:] == -1).all())
+    with pytest.raises(mqgrad.MqgError):
+        mqgrad.mqg_quantize(g, 4, bucket, 4, dest=5)
