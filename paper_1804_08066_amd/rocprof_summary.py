@@ -114,10 +114,10 @@ def cmd_stats(a):
 
 def cmd_sweep(a):
     out = head(a.title, a.cmd)
-    out += ["| bits | bucket | workers | quantize kernel | calls | avg us (rocprofv3) | avg us (HIP events) | % of 8 TB/s | "
+    out += ["| bits | bucket | workers | code stores | quantize kernel | calls | avg us (rocprofv3) | avg us (HIP events) | % of 8 TB/s | "
             "streaming ceiling us | server kernel | calls | avg us (rocprofv3) | avg us (HIP events) | % of 8 TB/s | "
             "streaming ceiling us |",
-            "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+            "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for spec in a.run:
         point, sdir, jpath = spec.split(":")
         b, B, W = (int(x) for x in point.split(","))
@@ -129,15 +129,17 @@ def cmd_sweep(a):
         ce = d.get("stream_ceiling") or {}
         cq = "%.1f" % ce["quantize_mix"]["us"] if ce else "-"
         cu = "%.1f" % ce["update_mix"]["us"] if ce else "-"
-        out.append("| %d | %d | %d | %s | %d | %.1f | %.1f | %.1f | %s | %s | %d | %.1f | %.1f | %.1f | %s |" %
-                   (b, B, W, qk, ks[qk][0], ks[qk][1] / 1e3, r["avg_launch_us"], 100 * r["frac"], cq,
+        policy = (d.get("config", {}).get("code_stores") or {}).get("chosen", "cached")
+        out.append("| %d | %d | %d | %s | %s | %d | %.1f | %.1f | %.1f | %s | %s | %d | %.1f | %.1f | %.1f | %s |" %
+                   (b, B, W, policy, qk, ks[qk][0], ks[qk][1] / 1e3, r["avg_launch_us"], 100 * r["frac"], cq,
                     sk, ks[sk][0], ks[sk][1] / 1e3, ra["avg_launch_us"], 100 * ra["frac"], cu))
     out.append("")
     out.append("The HIP-event columns are bench.py's averages over its timed region (after the conditioning steps); the "
                "rocprofv3 columns average every launch of the process, the cold region and the warm-up included.  "
                "Percentages: algorithmic bytes per launch / HIP-event time / 8 TB/s.  Streaming ceiling: the time of "
                "bench.py's streaming kernel for that kernel's read/write mix in the same run (same loads and stores, no "
-               "arithmetic; HIP events).")
+               "arithmetic; HIP events).  Code stores: the cache policy of the quantizer's code words that bench.py's untimed "
+               "probe chose for the point (mqg_quantize_to: kept cached for the update, or streamed to memory).")
     write(a.out, out)
 
 
